@@ -1,0 +1,319 @@
+"""Pins that hold the CPU oracle in place (no GPU, no HIP library).
+
+Each test checks the oracle against something other than itself: brute-force
+loops, a library masked softmax, closed forms and invariants that follow from
+Sec. 3.3 (key-set rule) and Alg. 2 (stage then commit) of the paper.
+"""
+import math
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import brute
+from oracle.longlive_oracle import (Oracle, OracleConfig, attention, bf16_bits_to_f64, key_frames,
+                                    rope_angles, rope_pair_split, rope_rotate)
+from paper_2509_22622_amd import synth
+
+
+def _bits(shape, seed, scale=1.0):
+    g = np.random.default_rng(seed)
+    return synth.f32_to_bf16_bits(g.standard_normal(shape, dtype=np.float32) * np.float32(scale))
+
+
+def _stream(cfg, n_chunks, seed, layer=0, n_frames=None):
+    P = cfg.tokens_per_frame
+    C = cfg.chunk_frames if n_frames is None else n_frames
+    shape = (C * P, cfg.heads, cfg.head_dim)
+    return [(_bits(shape, seed + 3 * i), _bits(shape, seed + 3 * i + 1), _bits(shape, seed + 3 * i + 2))
+            for i in range(n_chunks)]
+
+
+# ---- P1: brute force -------------------------------------------------------
+@pytest.mark.parametrize("S,W,C", [(2, 2, 2), (2, 4, 2), (0, 3, 2), (1, 2, 2), (3, 1, 3)])
+def test_brute_force_agrees(S, W, C):
+    cfg = OracleConfig(1, 2, 12, 2, 2, C, S, W)
+    chunks = _stream(cfg, 5, 100 + S * 7 + W)
+    want = brute.stream_attention([(q.tolist(), k.tolist(), v.tolist()) for q, k, v in chunks],
+                                  cfg.heads, cfg.head_dim, cfg.grid_h, cfg.grid_w, C, S, W)
+    o = Oracle(cfg)
+    for i, (q, k, v) in enumerate(chunks):
+        o.append(0, i * C, q, k, v)
+        got = o.attn(0)
+        assert np.abs(got - np.array(want[i])).max() < 1e-12
+
+
+# ---- P2: no sink, window over everything == plain chunk-causal attention ---
+def test_reduces_to_chunk_causal_sdpa():
+    cfg = OracleConfig(1, 3, 24, 3, 4, 2, 0, 1000)
+    P, C, n_chunks = cfg.tokens_per_frame, cfg.chunk_frames, 5
+    chunks = _stream(cfg, n_chunks, 7)
+    o = Oracle(cfg)
+    outs, qs, ks, vs = [], [], [], []
+    for i, (q, k, v) in enumerate(chunks):
+        qs.append(o.append(0, i * C, q, k, v))
+        outs.append(o.attn(0))
+    for f in range(n_chunks * C):
+        kf, vf = o.frame_kv(0, f)
+        ks.append(kf)
+        vs.append(vf)
+    Q = torch.from_numpy(np.concatenate(qs)).permute(1, 0, 2)      # [H, N, D]
+    K = torch.from_numpy(np.concatenate(ks)).permute(1, 0, 2)
+    V = torch.from_numpy(np.concatenate(vs)).permute(1, 0, 2)
+    N = Q.shape[1]
+    chunk_of = torch.arange(N) // (C * P)
+    mask = chunk_of[:, None] >= chunk_of[None, :]                  # bidirectional inside a chunk
+    ref = torch.nn.functional.scaled_dot_product_attention(Q, K, V, attn_mask=mask)
+    ref = ref.permute(1, 0, 2).numpy()
+    assert np.abs(np.concatenate(outs) - ref).max() < 1e-12
+
+
+# ---- P3: normalisation -----------------------------------------------------
+def test_constant_v_gives_constant_output():
+    cfg = OracleConfig(1, 2, 16, 2, 3, 2, 2, 4)
+    o = Oracle(cfg)
+    shape = (cfg.chunk_frames * cfg.tokens_per_frame, cfg.heads, cfg.head_dim)
+    const = synth.f32_to_bf16_bits(np.full(shape, 0.75, np.float32))
+    for i in range(6):
+        o.append(0, 2 * i, _bits(shape, i), _bits(shape, 50 + i), const)
+        assert np.abs(o.attn(0) - 0.75).max() < 1e-12      # rows of the softmax sum to one
+
+
+# ---- P5: closed-form key-set probe ----------------------------------------
+@pytest.mark.parametrize("S,W,C", [(3, 6, 3), (3, 9, 3), (0, 21, 3), (2, 5, 3), (4, 4, 2)])
+def test_key_set_probe(S, W, C):
+    """q = 0 makes the softmax uniform; V = one-hot(frame) reads the key set out."""
+    n_chunks = 10
+    nf = n_chunks * C
+    cfg = OracleConfig(1, 1, max(16, 2 * ((nf + 1) // 2)), 1, 2, C, S, W)
+    D, P = cfg.head_dim, cfg.tokens_per_frame
+    o = Oracle(cfg)
+    for i in range(n_chunks):
+        shape = (C * P, 1, D)
+        v = np.zeros(shape, np.float32)
+        for t in range(C * P):
+            v[t, 0, i * C + t // P] = 1.0
+        o.append(0, i * C, synth.f32_to_bf16_bits(np.zeros(shape, np.float32)), _bits(shape, i),
+                 synth.f32_to_bf16_bits(v))
+        out = o.attn(0)
+        f0 = i * C
+        expect = sorted(set(range(min(S, f0 + C))) | set(range(max(S, f0 - W), f0 + C)))
+        want = np.zeros(D)
+        want[expect] = 1.0 / len(expect)
+        assert np.abs(out - want).max() < 1e-14
+        assert o.live_frames(0) == expect
+
+
+# ---- P4: frames outside the key set have no influence ---------------------
+def test_evicted_frames_have_zero_influence():
+    cfg = OracleConfig(1, 2, 16, 2, 2, 2, 2, 2)
+    chunks = _stream(cfg, 6, 11)
+    o = Oracle(cfg)
+    for i, (q, k, v) in enumerate(chunks):
+        o.append(0, 2 * i, q, k, v)
+    base = o.attn(0)
+    live = set(o.live_frames(0))
+    assert live == {0, 1, 8, 9, 10, 11}
+    for f in list(o.layer[0].committed):
+        if f not in live:
+            kf, vf = o.layer[0].committed[f]
+            o.layer[0].committed[f] = (np.full_like(kf, np.nan), np.full_like(vf, np.inf))
+    assert np.array_equal(o.attn(0), base)
+
+
+# ---- P6: order of the concatenation does not matter -----------------------
+def test_key_order_invariance():
+    cfg = OracleConfig(1, 2, 16, 2, 3, 3, 3, 6)
+    o = Oracle(cfg)
+    for i, (q, k, v) in enumerate(_stream(cfg, 6, 23)):
+        o.append(0, 3 * i, q, k, v)
+    F = o.live_frames(0)
+    perm = list(np.random.default_rng(0).permutation(F))
+    assert np.abs(o.attn(0) - o.attn(0, order=perm)).max() < 1e-13
+
+
+# ---- P7: streaming == recache prefill -------------------------------------
+@pytest.mark.parametrize("S,W,C,n_win", [(3, 9, 3, 12), (3, 6, 3, 9), (2, 4, 3, 7), (0, 6, 3, 9)])
+def test_streaming_equals_prefill(S, W, C, n_win):
+    cfg = OracleConfig(1, 2, 16, 2, 3, C, S, W)
+    P = cfg.tokens_per_frame
+    nf = S + n_win
+    shape = (nf * P, cfg.heads, cfg.head_dim)
+    q, k, v = _bits(shape, 1), _bits(shape, 2), _bits(shape, 3)
+    # streaming from frame 0 (the window directly follows the sink)
+    a = Oracle(cfg)
+    outs = []
+    for f0 in range(0, nf, C):
+        n = min(C, nf - f0)
+        sl = slice(f0 * P, (f0 + n) * P)
+        a.append(0, f0, q[sl], k[sl], v[sl])
+        outs.append(a.attn(0))
+    b = Oracle(cfg)
+    # chunk boundaries of the prefill are sink|window; make them coincide with streaming's
+    if S % C == 0:
+        got = b.recache_prefill(0, True, S, n_win, q, k, v)
+        assert np.abs(got - np.concatenate(outs)).max() < 1e-12
+        for f in range(nf):
+            assert np.array_equal(a.frame_kv(0, f)[0], b.frame_kv(0, f)[0])
+            assert np.array_equal(a.frame_kv(0, f)[1], b.frame_kv(0, f)[1])
+        # the next chunk sees the same thing in both
+        nq, nk, nv = (_bits((C * P, cfg.heads, cfg.head_dim), 90 + i) for i in range(3))
+        a.append(0, nf, nq, nk, nv)
+        b.append(0, nf, nq, nk, nv)
+        assert np.array_equal(a.attn(0), b.attn(0))
+    else:
+        got = b.recache_prefill(0, True, S, n_win, q, k, v)
+        assert got.shape == (nf * P, cfg.heads, cfg.head_dim)
+        assert sorted(b._store(0)) == list(range(nf))
+
+
+def test_prefill_late_window_is_plain_chunk_causal():
+    """Sink + 12 window frames with W = 9, C = 3: every earlier chunk is visible."""
+    cfg = OracleConfig(1, 2, 16, 1, 2, 3, 3, 9)
+    P = cfg.tokens_per_frame
+    nf, ws = 15, 177
+    shape = (nf * P, cfg.heads, cfg.head_dim)
+    q, k, v = _bits(shape, 4), _bits(shape, 5), _bits(shape, 6)
+    o = Oracle(cfg)
+    got = o.recache_prefill(0, True, ws, 12, q, k, v)
+    frames = list(range(3)) + list(range(ws, ws + 12))
+    qr = np.concatenate([rope_rotate(cfg, bf16_bits_to_f64(q[i * P:(i + 1) * P]), f) for i, f in enumerate(frames)])
+    kr = np.concatenate([rope_rotate(cfg, bf16_bits_to_f64(k[i * P:(i + 1) * P]), f) for i, f in enumerate(frames)])
+    Q = torch.from_numpy(qr).permute(1, 0, 2)
+    K = torch.from_numpy(kr).permute(1, 0, 2)
+    V = torch.from_numpy(bf16_bits_to_f64(v)).permute(1, 0, 2)
+    chunk_of = torch.arange(nf * P) // (3 * P)
+    ref = torch.nn.functional.scaled_dot_product_attention(Q, K, V, attn_mask=chunk_of[:, None] >= chunk_of[None, :])
+    assert np.abs(got - ref.permute(1, 0, 2).numpy()).max() < 1e-12
+    assert o.live_frames(0) == [0, 1, 2] + list(range(ws + 12 - 12, ws + 12))
+
+
+def test_prefill_without_sink_keeps_old_sink():
+    cfg = OracleConfig(1, 1, 16, 1, 2, 3, 3, 6)
+    o = Oracle(cfg)
+    chunks = _stream(cfg, 6, 40)
+    for i, (q, k, v) in enumerate(chunks):
+        o.append(0, 3 * i, q, k, v)
+    sink_before = [o.frame_kv(0, f)[0].copy() for f in range(3)]
+    P = cfg.tokens_per_frame
+    shape = (9 * P, 1, 16)
+    o.recache_prefill(0, False, 9, 9, _bits(shape, 1), _bits(shape, 2), _bits(shape, 3))
+    assert sorted(o._store(0)) == [0, 1, 2] + list(range(9, 18))
+    for f in range(3):
+        assert np.array_equal(o.frame_kv(0, f)[0], sink_before[f])
+    assert o.live_frames(0) == [0, 1, 2] + list(range(9, 18))
+
+
+# ---- P8: two configurations with identical key sets -----------------------
+def test_cross_config_equal_while_key_sets_coincide():
+    a_cfg = OracleConfig(1, 2, 16, 2, 2, 3, 3, 9)
+    b_cfg = OracleConfig(1, 2, 16, 2, 2, 3, 0, 21)
+    a, b = Oracle(a_cfg), Oracle(b_cfg)
+    for i, (q, k, v) in enumerate(_stream(a_cfg, 7, 5)):
+        a.append(0, 3 * i, q, k, v)
+        b.append(0, 3 * i, q, k, v)
+        same = a.live_frames(0) == b.live_frames(0)
+        assert same == (i <= 4)
+        if same:
+            assert np.array_equal(a.attn(0), b.attn(0))
+        else:
+            assert not np.array_equal(a.attn(0), b.attn(0))
+
+
+# ---- P9: resident set does not grow with the video ------------------------
+@pytest.mark.parametrize("S,W,C", [(3, 9, 3), (3, 6, 3), (0, 21, 3), (2, 7, 3)])
+def test_constant_resident_size(S, W, C):
+    cfg = OracleConfig(1, 1, 16, 1, 1, C, S, W)
+    existing = set()
+    for i in range(320):                       # 240 s of video at chunk 3
+        f0 = i * C
+        existing |= set(range(f0, f0 + C))
+        F = key_frames(cfg, f0, C, existing)
+        assert len(F) == len(set(F))
+        if f0 >= S + W:
+            assert len(F) == S + W + C
+        assert len(F) <= S + W + C
+        assert all(f < S or f0 - W <= f < f0 + C for f in F)
+        assert set(range(f0, f0 + C)) <= set(F)
+
+
+# ---- P10: rotary closed forms ---------------------------------------------
+def test_rope_split_and_layout():
+    assert rope_pair_split(128) == (22, 21, 21)
+    assert rope_pair_split(64) == (12, 10, 10)
+    cfg = OracleConfig(1, 1, 128, 30, 52, 3, 3, 9)
+    base = rope_angles(cfg, 5, 7, 11)
+    df = rope_angles(cfg, 6, 7, 11) - base
+    dy = rope_angles(cfg, 5, 8, 11) - base
+    dx = rope_angles(cfg, 5, 7, 12) - base
+    assert np.all(df[:22] != 0) and np.all(df[22:] == 0)
+    assert np.all(dy[22:43] != 0) and np.all(dy[:22] == 0) and np.all(dy[43:] == 0)
+    assert np.all(dx[43:] != 0) and np.all(dx[:43] == 0)
+    # first pair of each axis turns by the position itself; last pair by pos * theta^-(1 - 2/d_a)
+    assert base[0] == 5.0 and base[22] == 7.0 and base[43] == 11.0
+    assert math.isclose(base[21], 5.0 * 10000.0 ** (-42.0 / 44.0), rel_tol=1e-15)
+    assert math.isclose(base[42], 7.0 * 10000.0 ** (-40.0 / 42.0), rel_tol=1e-15)
+    assert math.isclose(base[63], 11.0 * 10000.0 ** (-40.0 / 42.0), rel_tol=1e-15)
+
+
+def test_rope_closed_forms():
+    cfg = OracleConfig(1, 1, 64, 4, 5, 1, 0, 4)
+    P = cfg.tokens_per_frame
+    x = np.zeros((P, 1, 64))
+    x[:, 0, 0] = 1.0            # (1, 0) in frame pair 0
+    x[:, 0, 24] = 2.0           # (2, 0) in row pair 0
+    x[:, 0, 45] = 1.0           # (0, 1) in column pair 0
+    r = rope_rotate(cfg, x, 3)  # frame 3
+    for t in range(P):
+        y, xx = divmod(t, 5)
+        assert np.allclose(r[t, 0, 0:2], [math.cos(3), math.sin(3)], atol=1e-15)
+        assert np.allclose(r[t, 0, 24:26], [2 * math.cos(y), 2 * math.sin(y)], atol=1e-15)
+        assert np.allclose(r[t, 0, 44:46], [-math.sin(xx), math.cos(xx)], atol=1e-15)
+    # origin is the identity; pair norms are preserved
+    z = np.random.default_rng(0).standard_normal((P, 2, 64))
+    r0 = rope_rotate(cfg, z, 0)
+    assert np.array_equal(r0[0], z[0])
+    r9 = rope_rotate(cfg, z, 9)
+    assert np.allclose(r9[..., 0::2] ** 2 + r9[..., 1::2] ** 2, z[..., 0::2] ** 2 + z[..., 1::2] ** 2, rtol=1e-13)
+
+
+def test_rope_scores_depend_on_frame_difference_only():
+    cfg = OracleConfig(1, 2, 64, 2, 3, 2, 0, 8)
+    P = cfg.tokens_per_frame
+    g = np.random.default_rng(3)
+    q = g.standard_normal((2 * P, 2, 64))
+    k = g.standard_normal((2 * P, 2, 64))
+    def scores(shift):
+        qr = rope_rotate(cfg, q, 10 + shift)
+        kr = rope_rotate(cfg, k, 4 + shift)
+        return np.einsum("qhd,khd->hqk", qr, kr)
+    assert np.abs(scores(0) - scores(950)).max() < 1e-10
+
+
+# ---- P11: only the last pass of a chunk stays (Alg. 2) --------------------
+def test_stage_then_commit():
+    cfg = OracleConfig(1, 2, 16, 2, 2, 2, 2, 4)
+    clean = _stream(cfg, 5, 60)
+    noisy = _stream(cfg, 5, 600)
+    a, b = Oracle(cfg), Oracle(cfg)
+    for i in range(5):
+        for _ in range(3):
+            a.append(0, 2 * i, *noisy[i])
+            a.attn(0)
+        a.append(0, 2 * i, *clean[i])
+        b.append(0, 2 * i, *clean[i])
+        assert np.array_equal(a.attn(0), b.attn(0))
+    with pytest.raises(ValueError):
+        a.append(0, 4, *clean[0])          # neither a repeat nor the next chunk
+    with pytest.raises(ValueError):
+        Oracle(cfg).append(0, 2, *clean[0])
+
+
+def test_attention_matches_library_softmax():
+    g = np.random.default_rng(9)
+    q, K, V = g.standard_normal((7, 2, 8)), g.standard_normal((13, 2, 8)), g.standard_normal((13, 2, 8))
+    got = attention(q, K, V)
+    sc = torch.einsum("qhd,khd->hqk", torch.from_numpy(q), torch.from_numpy(K)) / math.sqrt(8)
+    ref = torch.einsum("hqk,khd->qhd", torch.softmax(sc, dim=-1), torch.from_numpy(V)).numpy()
+    assert np.abs(got - ref).max() < 1e-14
+    assert np.array_equal(attention(q, K, V, rows=[5, 1]), got[[5, 1]])
