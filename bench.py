@@ -1,0 +1,182 @@
+"""Benchmark of the sink+window attention hot path on one MI355X.
+
+A step is one pass of the hot path over one 3-frame chunk: for each of the 30 layers,
+ll_chunk_append (rotary + ring write) then ll_sink_window_attn, at the Wan-1.3B shape
+(12 heads x 128, 1560 tokens/frame, sink 3, window 9, chunk 3: 4680 queries x 23400
+keys per layer) in steady state (ring full, wrapping).  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
+PEAK_HBM_GBS = 8000.0
+
+
+def attn_flops(nq, nk, d, h):
+    return 4.0 * nq * nk * d * h
+
+
+def cpu_baseline(w, rows=2048):
+    """Time the fp64 oracle as it stands on a bounded sample of the same workload: one layer in
+    steady state, all heads, `rows` of the 4680 query rows (key-set build + attention)."""
+    import numpy as np
+    from oracle.longlive_oracle import Oracle, OracleConfig
+    from paper_2509_22622_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = len(os.sched_getaffinity(0))
+    o = Oracle(OracleConfig(1, w.heads, w.head_dim, w.grid_h, w.grid_w, w.chunk_frames, w.sink_frames, w.window_frames))
+    n_fill = (w.sink_frames + w.window_frames) // w.chunk_frames + 1
+    t_append = 0.0
+    for i in range(n_fill):
+        q, k, v = synth.chunk_qkv(w, 0, i)
+        t0 = time.perf_counter()
+        o.append(0, i * w.chunk_frames, q, k, v)
+        t_append = time.perf_counter() - t0
+    sel = np.random.default_rng(0).choice(w.chunk_tokens, size=rows, replace=False)
+    t0 = time.perf_counter()
+    o.attn(0, rows=np.sort(sel))
+    t_attn = time.perf_counter() - t0
+    nk = len(o.live_frames(0)) * w.tokens_per_frame
+    fl = attn_flops(rows, nk, w.head_dim, w.heads)
+    # whole-layer estimate: the append of the chunk plus attention scaled to all query rows
+    per_layer_s = t_append + t_attn * (w.chunk_tokens / rows)
+    return {"value": fl / t_attn / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"1 layer, steady state, {w.heads} heads, {rows} of {w.chunk_tokens} query rows x {nk} keys, "
+                      f"fp64 numpy: attention {t_attn:.2f} s, append {t_append:.2f} s; "
+                      f"extrapolated {per_layer_s * 30:.0f} s per 30-layer chunk step",
+            "seconds": t_attn, "affinity_cores": len(os.sched_getaffinity(0)), "os_cpu_count": os.cpu_count()}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--variant", type=int, default=0, help="attention kernel variant (0 = default)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-recache", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (--gpus 1); the path shards by head, see DESIGN.md")
+
+    import torch
+    from paper_2509_22622_amd import binding, synth
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2509_22622_amd import build as _b
+        _b.build()
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    binding.set_attn_variant(args.variant)
+
+    w = synth.WAN_LOOP
+    L, Hh, D, P, Cf = w.layers, w.heads, w.head_dim, w.tokens_per_frame, w.chunk_frames
+    nq = w.chunk_tokens
+    nk = (w.sink_frames + w.window_frames + Cf) * P
+    cache = binding.Cache(L, Hh, D, w.grid_h, w.grid_w, Cf, w.sink_frames, w.window_frames)
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.MASTER_SEED)
+    pool = 2
+    shape = (pool, L, nq, Hh, D)
+    # generate layer by layer to keep the fp32 staging small
+    def gen_bf16():
+        t = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+        for i in range(pool):
+            for l in range(L):
+                t[i, l] = torch.randn((nq, Hh, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        return t
+    q, k, v = gen_bf16(), gen_bf16(), gen_bf16()
+    qr = torch.empty((L, nq, Hh, D), dtype=torch.bfloat16, device="cuda")
+    out = torch.empty((L, nq, Hh, D), dtype=torch.bfloat16, device="cuda")
+
+    chunk = 0
+    def step(events=None):
+        nonlocal chunk
+        f0, i = chunk * Cf, chunk % pool
+        for l in range(L):
+            if events is not None:
+                e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
+                e0.record()
+            cache.chunk_append(l, f0, Cf, q[i, l], k[i, l], v[i, l], qr[l])
+            if events is not None:
+                e1.record()
+            cache.sink_window_attn(l, qr[l], out[l])
+            if events is not None:
+                e2.record()
+                events.append((e0, e1, e2))
+        chunk += 1
+
+    n_fill = (w.sink_frames + w.window_frames) // Cf + 1      # chunks until every ring slot is live
+    for _ in range(n_fill + args.warmup):
+        step()
+    assert sum(b - a for a, b in cache.live_ranges(0)) == nk
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    append_ms = sum(a.elapsed_time(b) for a, b, _ in events) / len(events)
+    attn_ms = sum(b.elapsed_time(c) for _, b, c in events) / len(events)
+    fl_layer = attn_flops(nq, nk, D, Hh)
+    tflops = fl_layer * L / (ms_per_step * 1e-3) / 1e12
+    attn_tflops = fl_layer / (attn_ms * 1e-3) / 1e12
+    append_bytes = 4 * nq * Hh * D * 2 + 2 * nq * Hh * D * 2       # read q,k,v + write q', K', V
+    res = {
+        "metric": "sink+window attn TFLOP/s & ms per 3-frame chunk (30 layers); % bf16 MFMA peak",
+        "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "wan1.3b-30layers: 30 layers x (12 heads x 128, 1560 tok/frame, chunk 3, sink 3, window 9; "
+                               "4680 queries x 23400 keys), steady state, append + attention per layer",
+                   "attn_variant": binding.attn_variant_names().get(args.variant, "default")},
+        "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
+        "attn_ms_per_layer": round(attn_ms, 4), "append_ms_per_layer": round(append_ms, 4),
+        "append_GBps": round(append_bytes / (append_ms * 1e-3) / 1e9, 1),
+        "roofline": {"bound": "mfma", "kernel": "ll_attn_kernel", "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None},
+    }
+
+    if not args.no_recache:
+        # KV-recache prefill, config 5: sink 3 + 12 window frames at a late position, per layer, 30 layers
+        wr = synth.RECACHE
+        nf = wr.sink_frames + wr.window_frames + wr.chunk_frames
+        rshape = (nf * P, Hh, D)
+        rq, rk, rv = (torch.randn(rshape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16) for _ in range(3))
+        ro = torch.empty(rshape, dtype=torch.bfloat16, device="cuda")
+        ws = chunk * Cf - (wr.window_frames + wr.chunk_frames)
+        def recache():
+            for l in range(L):
+                cache.recache_prefill(l, True, ws, wr.window_frames + wr.chunk_frames, rq, rk, rv, ro)
+        recache()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        reps = 3
+        for _ in range(reps):
+            recache()
+        torch.cuda.synchronize()
+        r_ms = (time.perf_counter() - t0) / reps * 1e3
+        n_ch = nf // Cf
+        pairs = sum(min(i + 1, (wr.sink_frames + wr.window_frames) // Cf + 1) for i in range(n_ch))
+        r_fl = attn_flops(nq, nq, D, Hh) * pairs * L
+        res["recache_prefill"] = {"ms_30_layers": round(r_ms, 3), "TFLOP/s": round(r_fl / (r_ms * 1e-3) / 1e12, 2),
+                                  "workload": f"{nf} frames = {n_ch} chunks, chunk-causal, {nf * P} queries, 30 layers"}
+
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(synth.WAN_LAYER)
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,143 @@
+/*
+ * longlive.h - C-ABI of the MI355X (gfx950) library for LongLive's inference hot
+ * path: short-window attention with a frame-level attention sink over a rolling
+ * per-layer KV cache, and the chunk-causal re-prefill used by KV-recache.
+ *
+ * Paper passages behind each call are named at the call.  Shapes use the
+ * paper's names: chunk (C frames), local window (W frames), sink (S frames);
+ * P = tokens per frame, H = heads, D = head_dim.
+ *
+ * Conventions for every call
+ *   - Return value is an ll_status; nothing throws or aborts across this ABI.
+ *     ll_last_error() gives a thread-local message for the last failure.
+ *   - "device" pointers are HIP device memory of the current device, "host"
+ *     pointers are ordinary process memory.  Tensors are bfloat16, token-major
+ *     [tokens, H, D], densely packed; tokens of a chunk are frame-major and
+ *     row-major (y * grid_w + x) inside a frame.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Device
+ *     work is enqueued on it and the call returns without synchronising.  Tensors
+ *     are borrowed until the stream has passed the call.
+ *   - The cache's device buffer is owned by the caller and must outlive the
+ *     handle.  The library allocates no device memory.
+ *   - Host-side bookkeeping changes at call time, so calls for one layer must be
+ *     made in program order; layers are independent of each other.
+ *   - One handle = one video (batch 1, the paper's interactive setting).
+ */
+#ifndef LONGLIVE_H
+#define LONGLIVE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ll_cache ll_cache; /* opaque; host bookkeeping only */
+
+typedef enum {
+    LL_OK = 0,
+    LL_ERR_INVALID_ARG = 1,      /* null pointer, value out of range, shape mismatch      */
+    LL_ERR_STATE = 2,            /* call out of order for this layer                       */
+    LL_ERR_BUFFER_TOO_SMALL = 3, /* caller's buffer smaller than required                  */
+    LL_ERR_UNSUPPORTED = 4,      /* valid request this build has no kernel for             */
+    LL_ERR_HIP = 5               /* a HIP runtime call failed (message has the HIP error)  */
+} ll_status;
+
+/* Bytes of device memory ll_cache_create needs for these shapes; 0 if they are invalid.
+ * Resident size is O(S + W + C) frames per layer and independent of video length
+ * (Sec. 3.3, "Consistency between Training and Inference"). */
+size_t ll_cache_bytes(int layers, int heads, int head_dim, int tokens_per_frame,
+                      int sink_frames, int window_frames, int chunk_frames);
+
+/* Create the bookkeeping for `layers` independent rolling caches laid out in `dev_buffer`.
+ *   Key set of a chunk starting at frame f0 (Sec. 3.3 "Frame Sink", "Short-window
+ *   Attention"): sink frames [0, S), the last W non-sink frames before f0, and the chunk
+ *   itself.  window_frames counts past frames only; the ring holds W + C frames.
+ *   head_dim must be 64 or 128; tokens_per_frame must equal grid_h * grid_w;
+ *   chunk_frames >= 1, sink_frames >= 0, window_frames >= 0.
+ *   rope_theta: base of the rotary embedding (10000 for the benchmark configs).
+ *   dev_buffer: device, 256-byte aligned, at least ll_cache_bytes(...) bytes; it is zeroed
+ *   and the rotary tables are written into its tail (synchronous copies on the null
+ *   stream).  dev_buffer == NULL with dev_bytes == 0 makes an index-only handle: the
+ *   bookkeeping and the introspection calls work, compute calls accept NULL tensors and
+ *   enqueue nothing (used to test the indexing without a GPU). */
+ll_status ll_cache_create(int layers, int heads, int head_dim, int tokens_per_frame,
+                          int sink_frames, int window_frames, int chunk_frames,
+                          int grid_h, int grid_w, float rope_theta,
+                          void* dev_buffer, size_t dev_bytes, ll_cache** out);
+
+/* Free the host bookkeeping.  The device buffer stays with the caller. */
+ll_status ll_cache_destroy(ll_cache* cache);
+
+/* Forget every frame of `layer` (-1 = all layers): the next append must start at frame 0. */
+ll_status ll_cache_reset(ll_cache* cache, int layer);
+
+/* Stage chunk [frame_start, frame_start + n_frames) of `layer`  (Appendix Alg. 2: every
+ * denoising pass of a chunk runs with the chunk's own K/V, only the final clean pass stays).
+ *   Rotates q and k by the 3D rotary embedding at (absolute frame, row, column) in fp32,
+ *   writes rotated q to q_out (may alias q), rotated k and v into the layer's cache slots.
+ *   frame_start equal to the staged chunk's start  -> overwrite the same slots;
+ *   frame_start equal to staged start + its length -> the staged chunk becomes permanent,
+ *       frames older than frame_start - W (non-sink) stop being live, sink frames stay;
+ *   first call after create/reset must have frame_start 0; anything else -> LL_ERR_STATE.
+ *   1 <= n_frames <= chunk_frames.  q, k, v, q_out: device, [n_frames*P, H, D] bf16. */
+ll_status ll_chunk_append(ll_cache* cache, int layer, int64_t frame_start, int n_frames,
+                          const void* q, const void* k, const void* v, void* q_out,
+                          void* stream);
+
+/* out = softmax(q_roped K^T / sqrt(D)) V over sink U window U staged chunk of `layer`
+ * (Sec. 3.3; no mask inside the key set: bidirectional within the chunk, the rest is past).
+ *   q_roped: device, [Nq, H, D] bf16, the q_out of the matching ll_chunk_append, where
+ *   Nq = staged n_frames * P.  out: device, same shape (may alias q_roped).
+ *   LL_ERR_STATE if no chunk is staged. */
+ll_status ll_sink_window_attn(ll_cache* cache, int layer, const void* q_roped, void* out,
+                              void* stream);
+
+/* KV-recache for one layer (Sec. 3.1 "KV Recache"; Sec. 3.3 last sentence; Alg. 2 line
+ * "recache"): rebuild the cache from frames [0, S) (if include_sink) followed by
+ * [win_start, win_start + n_win), and compute their attention under the chunk-causal mask:
+ * the frames are cut into chunks of C (the sink first, then the window from win_start);
+ * a chunk starting at f0 sees the sink, the retained frames in [f0 - W, f0) and itself.
+ *   q, k, v, out: device, [(S if include_sink else 0) + n_win) * P, H, D] bf16 in that
+ *   frame order.  out receives the attention output and is also used as the staging area
+ *   for the rotated queries (out must not alias q, k or v).
+ *   All non-sink frames held before are dropped.  include_sink == 0 keeps the sink K/V
+ *   already held (LL_ERR_STATE if the sink is incomplete).  win_start >= S, 0 <= n_win <=
+ *   W + C.  Afterwards the layer is as if those frames had been streamed: the last chunk
+ *   is staged and the next ll_chunk_append must start at win_start + n_win (or repeat the
+ *   last chunk's start). */
+ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64_t win_start,
+                             int n_win, const void* q, const void* k, const void* v,
+                             void* out, void* stream);
+
+/* ---- introspection (exact integer answers; used for the bit-exact indexing checks) ---- */
+
+/* Frames the staged chunk attends to, ascending.  frames: host, capacity `cap`; *n = count. */
+ll_status ll_cache_live_frames(const ll_cache* cache, int layer, int64_t* frames, int cap,
+                               int* n);
+/* First token slot of `frame` in the per-head key order: f*P for a sink frame, else
+ * (S + (f - S) mod (W + C)) * P. */
+ll_status ll_cache_slot_of_frame(const ll_cache* cache, int layer, int64_t frame,
+                                 int64_t* token_slot);
+/* The staged chunk's key set as at most 3 half-open token-slot ranges, ascending and
+ * disjoint.  ranges: host int64[2*cap] as (begin, end) pairs; *n = count. */
+ll_status ll_cache_live_ranges(const ll_cache* cache, int layer, int64_t* ranges, int cap,
+                               int* n);
+/* Copy one held frame's rotated K and V out of the cache into [P, H, D] bf16 device
+ * tensors (either may be NULL).  LL_ERR_STATE if the frame is not held. */
+ll_status ll_cache_read_frame(const ll_cache* cache, int layer, int64_t frame, void* k_out,
+                              void* v_out, void* stream);
+
+/* Attention kernel variant: 0 = default for the shape, otherwise a variant id listed by
+ * ll_attn_variant_name.  Process-wide tuning knob for benchmarking. */
+ll_status ll_set_attn_variant(int variant);
+const char* ll_attn_variant_name(int variant); /* NULL when `variant` does not exist */
+
+const char* ll_status_string(ll_status s);
+const char* ll_last_error(void); /* thread-local, never NULL */
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LONGLIVE_H */

@@ -97,20 +97,28 @@ def rope_angles(cfg: OracleConfig, f: int, y: int, x: int) -> np.ndarray:
     return out
 
 
+def rope_frequencies(cfg: OracleConfig) -> tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """theta^(-2i/d_a) for the pairs of the frame, row and column axes."""
+    return tuple(cfg.theta ** (-2.0 * np.arange(n, dtype=np.float64) / (2 * n)) if n else np.zeros(0)
+                 for n in rope_pair_split(cfg.head_dim))
+
+
 def rope_rotate(cfg: OracleConfig, x: np.ndarray, frame_start: int) -> np.ndarray:
     """Rotate x [n*P, H, D] (float64); tokens are frame-major, row-major in a frame.
 
     Pair (x[2i], x[2i+1]) is one complex number re + i*im, multiplied by
-    exp(i*angle): re' = re*cos - im*sin, im' = re*sin + im*cos.
+    exp(i*angle): re' = re*cos - im*sin, im' = re*sin + im*cos, with the angle
+    of ``rope_angles`` (position times frequency, per axis).
     """
     P = cfg.tokens_per_frame
     n_tok = x.shape[0]
     assert n_tok % P == 0
-    ang = np.empty((n_tok, cfg.head_dim // 2), dtype=np.float64)
-    for t in range(n_tok):
-        f = frame_start + t // P
-        y, xx = divmod(t % P, cfg.grid_w)
-        ang[t] = rope_angles(cfg, f, y, xx)
+    t = np.arange(n_tok)
+    f = (frame_start + t // P).astype(np.float64)
+    y = ((t % P) // cfg.grid_w).astype(np.float64)
+    xx = ((t % P) % cfg.grid_w).astype(np.float64)
+    w_t, w_h, w_w = rope_frequencies(cfg)
+    ang = np.concatenate([f[:, None] * w_t[None, :], y[:, None] * w_h[None, :], xx[:, None] * w_w[None, :]], axis=1)
     c = np.cos(ang)[:, None, :]
     s = np.sin(ang)[:, None, :]
     re = x[..., 0::2]

@@ -1,0 +1,159 @@
+"""ctypes binding of the C-ABI in ``include/longlive.h``: argument marshalling only.
+
+Every step of the hot path runs in the HIP library.  There is no fallback: if the
+library is missing or a call fails, an exception is raised.  torch is used for
+device memory and streams only.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblonglive.so")
+_lib = None
+
+LL_OK = 0
+STATUS_NAMES = {0: "LL_OK", 1: "LL_ERR_INVALID_ARG", 2: "LL_ERR_STATE", 3: "LL_ERR_BUFFER_TOO_SMALL",
+                4: "LL_ERR_UNSUPPORTED", 5: "LL_ERR_HIP"}
+
+# name -> (restype, argtypes); mirrors include/longlive.h
+_vp, _i, _i64, _sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
+SIGNATURES = {
+    "ll_cache_bytes": (_sz, [_i] * 7),
+    "ll_cache_create": (_i, [_i] * 9 + [C.c_float, _vp, _sz, C.POINTER(_vp)]),
+    "ll_cache_destroy": (_i, [_vp]),
+    "ll_cache_reset": (_i, [_vp, _i]),
+    "ll_chunk_append": (_i, [_vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]),
+    "ll_sink_window_attn": (_i, [_vp, _i, _vp, _vp, _vp]),
+    "ll_recache_prefill": (_i, [_vp, _i, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]),
+    "ll_cache_live_frames": (_i, [_vp, _i, C.POINTER(_i64), _i, C.POINTER(_i)]),
+    "ll_cache_slot_of_frame": (_i, [_vp, _i, _i64, C.POINTER(_i64)]),
+    "ll_cache_live_ranges": (_i, [_vp, _i, C.POINTER(_i64), _i, C.POINTER(_i)]),
+    "ll_cache_read_frame": (_i, [_vp, _i, _i64, _vp, _vp, _vp]),
+    "ll_set_attn_variant": (_i, [_i]),
+    "ll_attn_variant_name": (C.c_char_p, [_i]),
+    "ll_status_string": (C.c_char_p, [_i]),
+    "ll_last_error": (C.c_char_p, []),
+}
+
+
+class LongLiveError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{STATUS_NAMES.get(status, status)}: {message}")
+        self.status = status
+
+
+def lib() -> C.CDLL:
+    """Load liblonglive.so (built by ``paper_2509_22622_amd.build``); raise if it is missing."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} not built: run `python -m paper_2509_22622_amd.build`")
+        L = C.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = L
+    return _lib
+
+
+def _check(status: int) -> None:
+    if status != LL_OK:
+        raise LongLiveError(status, lib().ll_last_error().decode())
+
+
+def _ptr(t):
+    return None if t is None else C.c_void_p(t.data_ptr())
+
+
+def _stream():
+    import torch
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def cache_bytes(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames) -> int:
+    return lib().ll_cache_bytes(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames)
+
+
+def set_attn_variant(variant: int) -> None:
+    _check(lib().ll_set_attn_variant(variant))
+
+
+def attn_variant_names() -> dict:
+    out, v = {}, 1
+    while True:
+        n = lib().ll_attn_variant_name(v)
+        if n is None:
+            return out
+        out[v] = n.decode()
+        v += 1
+
+
+class Cache:
+    """Handle on ``layers`` rolling KV caches.  ``device=None`` makes an index-only handle."""
+
+    def __init__(self, layers, heads, head_dim, grid_h, grid_w, chunk_frames, sink_frames, window_frames,
+                 rope_theta=10000.0, device="cuda"):
+        self.layers, self.heads, self.head_dim = layers, heads, head_dim
+        self.grid_h, self.grid_w = grid_h, grid_w
+        self.P = grid_h * grid_w
+        self.C, self.S, self.W = chunk_frames, sink_frames, window_frames
+        self._h = C.c_void_p()
+        self.buffer = None
+        nbytes = cache_bytes(layers, heads, head_dim, self.P, sink_frames, window_frames, chunk_frames)
+        if device is not None:
+            import torch
+            if nbytes == 0:
+                raise LongLiveError(1, "invalid shape")
+            self.buffer = torch.empty(nbytes, dtype=torch.uint8, device=device)
+            ptr, size = C.c_void_p(self.buffer.data_ptr()), nbytes
+        else:
+            ptr, size = None, 0
+        _check(lib().ll_cache_create(layers, heads, head_dim, self.P, sink_frames, window_frames, chunk_frames,
+                                     grid_h, grid_w, rope_theta, ptr, size, C.byref(self._h)))
+
+    def close(self):
+        if self._h:
+            lib().ll_cache_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def reset(self, layer=-1):
+        _check(lib().ll_cache_reset(self._h, layer))
+
+    def chunk_append(self, layer, frame_start, n_frames, q=None, k=None, v=None, q_out=None):
+        stream = _stream() if q is not None else None
+        _check(lib().ll_chunk_append(self._h, layer, frame_start, n_frames, _ptr(q), _ptr(k), _ptr(v), _ptr(q_out), stream))
+
+    def sink_window_attn(self, layer, q_roped, out):
+        _check(lib().ll_sink_window_attn(self._h, layer, _ptr(q_roped), _ptr(out), _stream()))
+
+    def recache_prefill(self, layer, include_sink, win_start, n_win, q=None, k=None, v=None, out=None):
+        stream = _stream() if q is not None else None
+        _check(lib().ll_recache_prefill(self._h, layer, int(include_sink), win_start, n_win, _ptr(q), _ptr(k), _ptr(v),
+                                        _ptr(out), stream))
+
+    def live_frames(self, layer):
+        cap = self.S + self.W + self.C + 1
+        buf, n = (C.c_int64 * cap)(), C.c_int()
+        _check(lib().ll_cache_live_frames(self._h, layer, buf, cap, C.byref(n)))
+        return list(buf[: n.value])
+
+    def slot_of_frame(self, layer, frame):
+        s = C.c_int64()
+        _check(lib().ll_cache_slot_of_frame(self._h, layer, frame, C.byref(s)))
+        return s.value
+
+    def live_ranges(self, layer):
+        buf, n = (C.c_int64 * 16)(), C.c_int()
+        _check(lib().ll_cache_live_ranges(self._h, layer, buf, 8, C.byref(n)))
+        return [(buf[2 * i], buf[2 * i + 1]) for i in range(n.value)]
+
+    def read_frame(self, layer, frame, k_out, v_out):
+        _check(lib().ll_cache_read_frame(self._h, layer, frame, _ptr(k_out), _ptr(v_out), _stream()))

@@ -1,0 +1,386 @@
+// C-ABI of the library (see include/longlive.h): argument checks, host bookkeeping and
+// kernel launches.  No device memory is allocated here; everything lives in the buffer
+// the caller handed to ll_cache_create.
+#include "../../include/longlive.h"
+
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "cache_index.h"
+#include "kernels.h"
+
+using namespace ll;
+
+struct ll_cache {
+    int layers, H, D;
+    Geometry g;
+    int grid_h, grid_w;
+    double theta;
+    char* dev;              // null for an index-only handle
+    int64_t kblocks;        // kblocks per head region (with padding)
+    int64_t head_stride;    // elements between heads (K region + V region)
+    int64_t layer_stride;   // elements between layers
+    RopeTables rope;
+    std::vector<LayerIndex> layer;
+};
+
+static thread_local std::string g_err;
+static int g_variant = 0;
+
+static ll_status fail(ll_status s, const char* fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return s;
+}
+static ll_status hip_fail(hipError_t e, const char* what) {
+    return fail(LL_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
+}
+
+namespace {
+struct Sizes {
+    int64_t kblocks, head_stride, layer_stride, cache_elems;
+    int n_t, n_h, n_w;
+    size_t table_off, row_off, col_off, total;
+};
+bool shapes_ok(int layers, int H, int D, int P, int S, int W, int C) {
+    return layers >= 1 && H >= 1 && (D == 64 || D == 128) && P >= 1 && S >= 0 && W >= 0 && C >= 1 &&
+           int64_t(S + W + C) * P < (int64_t(1) << 30);
+}
+Sizes sizes(int layers, int H, int D, int P, int S, int W, int C, int grid_h, int grid_w) {
+    Sizes z{};
+    const int64_t slots = int64_t(S + W + C) * P;
+    z.kblocks = (slots + KBLOCK - 1) / KBLOCK + PAD_KBLOCKS;
+    z.head_stride = 2 * z.kblocks * KBLOCK * D;
+    z.layer_stride = z.head_stride * H;
+    z.cache_elems = z.layer_stride * layers;
+    const int d_hw = 2 * (D / 6), d_t = D - 2 * d_hw;
+    z.n_t = d_t / 2; z.n_h = d_hw / 2; z.n_w = d_hw / 2;
+    size_t off = (size_t(z.cache_elems) * 2 + 255) & ~size_t(255);
+    z.table_off = off; off += size_t(z.n_t) * sizeof(double);
+    off = (off + 255) & ~size_t(255);
+    z.row_off = off; off += size_t(grid_h) * z.n_h * sizeof(float2);
+    off = (off + 255) & ~size_t(255);
+    z.col_off = off; off += size_t(grid_w) * z.n_w * sizeof(float2);
+    z.total = (off + 255) & ~size_t(255);
+    return z;
+}
+// upper bound of the table area when the grid is not known yet (ll_cache_bytes)
+size_t table_bound(int D, int P) { return 3 * 256 + 64 * sizeof(double) + 2 * size_t(P) * (D / 2) * sizeof(float2); }
+}  // namespace
+
+extern "C" {
+
+size_t ll_cache_bytes(int layers, int heads, int head_dim, int tokens_per_frame, int sink_frames,
+                      int window_frames, int chunk_frames) {
+    if (!shapes_ok(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames)) return 0;
+    Sizes z = sizes(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames, 0, 0);
+    return z.table_off + table_bound(head_dim, tokens_per_frame);
+}
+
+ll_status ll_cache_create(int layers, int heads, int head_dim, int tokens_per_frame, int sink_frames,
+                          int window_frames, int chunk_frames, int grid_h, int grid_w, float rope_theta,
+                          void* dev_buffer, size_t dev_bytes, ll_cache** out) {
+    if (!out) return fail(LL_ERR_INVALID_ARG, "out is null");
+    *out = nullptr;
+    if (!shapes_ok(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames))
+        return fail(head_dim != 64 && head_dim != 128 && head_dim > 0 ? LL_ERR_UNSUPPORTED : LL_ERR_INVALID_ARG,
+                    "bad shape: layers %d heads %d head_dim %d (64 or 128) tokens_per_frame %d sink %d window %d chunk %d",
+                    layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames);
+    if (grid_h < 1 || grid_w < 1 || int64_t(grid_h) * grid_w != tokens_per_frame)
+        return fail(LL_ERR_INVALID_ARG, "grid %dx%d does not give %d tokens per frame", grid_h, grid_w, tokens_per_frame);
+    if (!(rope_theta > 1.0f)) return fail(LL_ERR_INVALID_ARG, "rope_theta must exceed 1");
+    if (chunk_frames > MAX_APPEND_FRAMES)
+        return fail(LL_ERR_UNSUPPORTED, "chunk_frames above %d", MAX_APPEND_FRAMES);
+    const bool index_only = dev_buffer == nullptr && dev_bytes == 0;
+    const size_t need = ll_cache_bytes(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames);
+    if (!index_only) {
+        if (!dev_buffer) return fail(LL_ERR_INVALID_ARG, "dev_buffer is null");
+        if (reinterpret_cast<uintptr_t>(dev_buffer) & 255) return fail(LL_ERR_INVALID_ARG, "dev_buffer is not 256-byte aligned");
+        if (dev_bytes < need) return fail(LL_ERR_BUFFER_TOO_SMALL, "dev_buffer has %zu bytes, %zu needed", dev_bytes, need);
+    }
+    Sizes z = sizes(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames, grid_h, grid_w);
+    ll_cache* c = new ll_cache();
+    c->layers = layers; c->H = heads; c->D = head_dim;
+    c->g.P = tokens_per_frame; c->g.S = sink_frames; c->g.W = window_frames; c->g.C = chunk_frames;
+    c->grid_h = grid_h; c->grid_w = grid_w; c->theta = rope_theta;
+    c->dev = static_cast<char*>(dev_buffer);
+    c->kblocks = z.kblocks; c->head_stride = z.head_stride; c->layer_stride = z.layer_stride;
+    c->layer.assign(layers, LayerIndex());
+    c->rope = RopeTables{nullptr, nullptr, nullptr, z.n_t, z.n_h, z.n_w};
+    if (!index_only) {
+        // Rotary tables: angles in double, stored as float (cos, sin); frame frequencies stay double.
+        std::vector<double> inv_t(z.n_t);
+        for (int i = 0; i < z.n_t; ++i) inv_t[i] = std::pow(double(rope_theta), -2.0 * i / (2.0 * z.n_t));
+        std::vector<float2> row(size_t(grid_h) * z.n_h), col(size_t(grid_w) * z.n_w);
+        for (int y = 0; y < grid_h; ++y)
+            for (int i = 0; i < z.n_h; ++i) {
+                const double a = double(y) * std::pow(double(rope_theta), -2.0 * i / (2.0 * z.n_h));
+                row[size_t(y) * z.n_h + i] = make_float2(float(std::cos(a)), float(std::sin(a)));
+            }
+        for (int x = 0; x < grid_w; ++x)
+            for (int i = 0; i < z.n_w; ++i) {
+                const double a = double(x) * std::pow(double(rope_theta), -2.0 * i / (2.0 * z.n_w));
+                col[size_t(x) * z.n_w + i] = make_float2(float(std::cos(a)), float(std::sin(a)));
+            }
+        hipError_t e = hipMemset(c->dev, 0, z.table_off);
+        if (e == hipSuccess) e = hipMemcpy(c->dev + z.table_off, inv_t.data(), inv_t.size() * sizeof(double), hipMemcpyHostToDevice);
+        if (e == hipSuccess && !row.empty()) e = hipMemcpy(c->dev + z.row_off, row.data(), row.size() * sizeof(float2), hipMemcpyHostToDevice);
+        if (e == hipSuccess && !col.empty()) e = hipMemcpy(c->dev + z.col_off, col.data(), col.size() * sizeof(float2), hipMemcpyHostToDevice);
+        if (e == hipSuccess) e = hipDeviceSynchronize();
+        if (e != hipSuccess) { delete c; return hip_fail(e, "ll_cache_create: table upload"); }
+        c->rope.inv_freq_t = reinterpret_cast<const double*>(c->dev + z.table_off);
+        c->rope.row_cs = reinterpret_cast<const float2*>(c->dev + z.row_off);
+        c->rope.col_cs = reinterpret_cast<const float2*>(c->dev + z.col_off);
+    }
+    *out = c;
+    return LL_OK;
+}
+
+ll_status ll_cache_destroy(ll_cache* cache) {
+    delete cache;
+    return LL_OK;
+}
+
+#define CHECK_CACHE_LAYER(cache, layer)                                             \
+    if (!(cache)) return fail(LL_ERR_INVALID_ARG, "cache is null");                 \
+    if ((layer) < 0 || (layer) >= (cache)->layers)                                  \
+        return fail(LL_ERR_INVALID_ARG, "layer %d out of range [0, %d)", (layer), (cache)->layers)
+
+ll_status ll_cache_reset(ll_cache* cache, int layer) {
+    if (!cache) return fail(LL_ERR_INVALID_ARG, "cache is null");
+    if (layer < -1 || layer >= cache->layers) return fail(LL_ERR_INVALID_ARG, "layer %d out of range", layer);
+    for (int l = 0; l < cache->layers; ++l)
+        if (layer < 0 || l == layer) cache->layer[l] = LayerIndex();
+    return LL_OK;
+}
+
+static uint16_t* layer_k(const ll_cache* c, int layer) {
+    return reinterpret_cast<uint16_t*>(c->dev) + int64_t(layer) * c->layer_stride;
+}
+static uint16_t* layer_v(const ll_cache* c, int layer) {
+    return layer_k(c, layer) + c->kblocks * KBLOCK * c->D;
+}
+
+// Enqueue the rotary + cache write of `n` frames whose absolute indices are frames[i];
+// rows of q/k/v are consecutive frames.
+static ll_status enqueue_append(ll_cache* c, int layer, const int64_t* frames, int n, const void* q, const void* k,
+                                const void* v, void* q_out, hipStream_t s) {
+    const int64_t frame_elems = int64_t(c->g.P) * c->H * c->D;
+    for (int base = 0; base < n; base += MAX_APPEND_FRAMES) {
+        AppendParams p{};
+        const int m = std::min(MAX_APPEND_FRAMES, n - base);
+        p.q = static_cast<const uint16_t*>(q) + base * frame_elems;
+        p.k = static_cast<const uint16_t*>(k) + base * frame_elems;
+        p.v = static_cast<const uint16_t*>(v) + base * frame_elems;
+        p.q_out = static_cast<uint16_t*>(q_out) + base * frame_elems;
+        p.k_cache = layer_k(c, layer); p.v_cache = layer_v(c, layer);
+        p.head_stride = c->head_stride;
+        p.rope = c->rope;
+        p.H = c->H; p.D = c->D; p.P = c->g.P; p.grid_w = c->grid_w;
+        p.n_frames = m;
+        p.seg_begin[0] = 0;
+        for (int i = 0; i < m; ++i) {
+            p.frame[i] = frames[base + i];
+            p.slot[i] = slot_of_frame(c->g, frames[base + i]);
+            const int nseg = int((p.slot[i] % KBLOCK + c->g.P + KBLOCK - 1) / KBLOCK);
+            p.seg_begin[i + 1] = p.seg_begin[i] + nseg;
+        }
+        hipError_t e = launch_append(p, s);
+        if (e != hipSuccess) return hip_fail(e, "append kernel launch");
+    }
+    return LL_OK;
+}
+
+static int pick_variant(const ll_cache* c) {
+    if (g_variant != 0 && attn_variant_supports(g_variant, c->D)) return g_variant;
+    return attn_variant_default(c->D);
+}
+
+struct ChunkWork { int q_begin, q_end; std::vector<SlotRange> ranges; };
+
+// Enqueue attention for a list of query chunks (each with its key ranges).
+static ll_status enqueue_attn(ll_cache* c, int layer, const std::vector<ChunkWork>& work, const void* q, void* out,
+                              hipStream_t s) {
+    const int variant = pick_variant(c);
+    const int qt = attn_variant_qtile(variant);
+    for (size_t base = 0; base < work.size(); base += MAX_ATTN_CHUNKS) {
+        AttnParams p{};
+        p.q = static_cast<const uint16_t*>(q);
+        p.out = static_cast<uint16_t*>(out);
+        p.k_cache = layer_k(c, layer); p.v_cache = layer_v(c, layer);
+        p.head_stride = c->head_stride;
+        p.H = c->H; p.D = c->D;
+        p.scale_log2e = float(1.4426950408889634 / std::sqrt(double(c->D)));
+        const int m = int(std::min<size_t>(MAX_ATTN_CHUNKS, work.size() - base));
+        // longest key sets first: they bound the launch
+        std::vector<int> order(m);
+        for (int i = 0; i < m; ++i) order[i] = int(base) + i;
+        auto keys = [&](int i) { int64_t t = 0; for (auto& r : work[i].ranges) t += r.end - r.begin; return t; };
+        std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return keys(a) > keys(b); });
+        int tiles = 0;
+        for (int i = 0; i < m; ++i) {
+            const ChunkWork& w = work[order[i]];
+            if (w.ranges.empty() || w.ranges.size() > size_t(MAX_RANGES))
+                return fail(LL_ERR_STATE, "key set has %zu ranges", w.ranges.size());
+            AttnChunk& ch = p.chunk[i];
+            ch.q_begin = w.q_begin; ch.q_end = w.q_end; ch.tile_begin = tiles;
+            ch.n_ranges = int(w.ranges.size());
+            for (int r = 0; r < ch.n_ranges; ++r) { ch.rs[r] = int(w.ranges[r].begin); ch.re[r] = int(w.ranges[r].end); }
+            tiles += (w.q_end - w.q_begin + qt - 1) / qt;
+        }
+        p.n_chunks = m; p.n_tiles = tiles;
+        hipError_t e = launch_attn(p, variant, s);
+        if (e != hipSuccess) return hip_fail(e, "attention kernel launch");
+    }
+    return LL_OK;
+}
+
+ll_status ll_chunk_append(ll_cache* cache, int layer, int64_t frame_start, int n_frames, const void* q, const void* k,
+                          const void* v, void* q_out, void* stream) {
+    CHECK_CACHE_LAYER(cache, layer);
+    if (n_frames < 1 || n_frames > cache->g.C)
+        return fail(LL_ERR_INVALID_ARG, "n_frames %d outside [1, %d]", n_frames, cache->g.C);
+    if (frame_start < 0) return fail(LL_ERR_INVALID_ARG, "negative frame_start");
+    const bool any_null = !q || !k || !v || !q_out;
+    if (cache->dev && any_null) return fail(LL_ERR_INVALID_ARG, "null tensor");
+    if (!cache->dev && !(!q && !k && !v && !q_out)) return fail(LL_ERR_INVALID_ARG, "index-only handle takes null tensors");
+    LayerIndex& L = cache->layer[layer];
+    if (classify_append(L, frame_start) == AppendKind::Invalid)
+        return fail(LL_ERR_STATE, "layer %d: frame_start %lld neither repeats (%lld) nor follows (%lld) the staged chunk",
+                    layer, (long long)frame_start, (long long)L.staged_f0, (long long)(L.staged_f0 + L.staged_n));
+    if (cache->dev) {
+        int64_t frames[MAX_APPEND_FRAMES];
+        for (int i = 0; i < n_frames; ++i) frames[i] = frame_start + i;
+        ll_status st = enqueue_append(cache, layer, frames, n_frames, q, k, v, q_out, static_cast<hipStream_t>(stream));
+        if (st != LL_OK) return st;
+    }
+    apply_append(cache->g, L, frame_start, n_frames);
+    return LL_OK;
+}
+
+ll_status ll_sink_window_attn(ll_cache* cache, int layer, const void* q_roped, void* out, void* stream) {
+    CHECK_CACHE_LAYER(cache, layer);
+    if (!cache->dev) return fail(LL_ERR_INVALID_ARG, "index-only handle has no device cache");
+    if (!q_roped || !out) return fail(LL_ERR_INVALID_ARG, "null tensor");
+    const LayerIndex& L = cache->layer[layer];
+    if (L.staged_n == 0) return fail(LL_ERR_STATE, "layer %d: no staged chunk", layer);
+    std::vector<ChunkWork> work(1);
+    work[0].q_begin = 0;
+    work[0].q_end = L.staged_n * cache->g.P;
+    work[0].ranges = live_ranges(cache->g, L);
+    return enqueue_attn(cache, layer, work, q_roped, out, static_cast<hipStream_t>(stream));
+}
+
+ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64_t win_start, int n_win, const void* q,
+                             const void* k, const void* v, void* out, void* stream) {
+    CHECK_CACHE_LAYER(cache, layer);
+    const Geometry& g = cache->g;
+    if (n_win < 0 || n_win > g.ring()) return fail(LL_ERR_INVALID_ARG, "n_win %d outside [0, %d]", n_win, g.ring());
+    if (win_start < g.S) return fail(LL_ERR_INVALID_ARG, "win_start %lld overlaps the sink [0, %d)", (long long)win_start, g.S);
+    const int n_total = (include_sink ? g.S : 0) + n_win;
+    if (n_total == 0) return fail(LL_ERR_INVALID_ARG, "no frames to prefill");
+    const bool any_null = !q || !k || !v || !out;
+    if (cache->dev && any_null) return fail(LL_ERR_INVALID_ARG, "null tensor");
+    if (!cache->dev && !(!q && !k && !v && !out)) return fail(LL_ERR_INVALID_ARG, "index-only handle takes null tensors");
+    if (cache->dev && (out == q || out == k || out == v)) return fail(LL_ERR_INVALID_ARG, "out must not alias q, k or v");
+    LayerIndex& L = cache->layer[layer];
+    if (!include_sink && L.sink_have < g.S) return fail(LL_ERR_STATE, "layer %d: sink incomplete (%lld of %d frames)", layer, (long long)L.sink_have, g.S);
+
+    const std::vector<ChunkSpan> chunks = prefill_chunks(g, include_sink != 0, win_start, n_win);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (cache->dev) {
+        std::vector<int64_t> frames;
+        for (const ChunkSpan& c : chunks)
+            for (int i = 0; i < c.n; ++i) frames.push_back(c.f0 + i);
+        // rotated queries are staged in `out`; the attention kernel reads and overwrites them in place
+        ll_status st = enqueue_append(cache, layer, frames.data(), int(frames.size()), q, k, v, out, s);
+        if (st != LL_OK) return st;
+    }
+    begin_prefill(g, L, include_sink != 0, win_start);
+    std::vector<ChunkWork> work;
+    int row = 0;
+    for (const ChunkSpan& c : chunks) {
+        prefill_stage(g, L, c.f0, c.n);
+        ChunkWork w;
+        w.q_begin = row; w.q_end = row + c.n * g.P;
+        w.ranges = live_ranges(g, L);
+        work.push_back(w);
+        row = w.q_end;
+    }
+    if (cache->dev) return enqueue_attn(cache, layer, work, out, out, s);
+    return LL_OK;
+}
+
+ll_status ll_cache_live_frames(const ll_cache* cache, int layer, int64_t* frames, int cap, int* n) {
+    CHECK_CACHE_LAYER(cache, layer);
+    if (!n) return fail(LL_ERR_INVALID_ARG, "n is null");
+    const std::vector<int64_t> f = live_frames(cache->g, cache->layer[layer]);
+    *n = int(f.size());
+    if (int(f.size()) > cap || (!frames && !f.empty())) return fail(LL_ERR_BUFFER_TOO_SMALL, "%zu frames, capacity %d", f.size(), cap);
+    for (size_t i = 0; i < f.size(); ++i) frames[i] = f[i];
+    return LL_OK;
+}
+
+ll_status ll_cache_slot_of_frame(const ll_cache* cache, int layer, int64_t frame, int64_t* token_slot) {
+    CHECK_CACHE_LAYER(cache, layer);
+    if (!token_slot) return fail(LL_ERR_INVALID_ARG, "token_slot is null");
+    if (frame < 0) return fail(LL_ERR_INVALID_ARG, "negative frame");
+    *token_slot = slot_of_frame(cache->g, frame);
+    return LL_OK;
+}
+
+ll_status ll_cache_live_ranges(const ll_cache* cache, int layer, int64_t* ranges, int cap, int* n) {
+    CHECK_CACHE_LAYER(cache, layer);
+    if (!n) return fail(LL_ERR_INVALID_ARG, "n is null");
+    const std::vector<SlotRange> r = live_ranges(cache->g, cache->layer[layer]);
+    *n = int(r.size());
+    if (int(r.size()) > cap || (!ranges && !r.empty())) return fail(LL_ERR_BUFFER_TOO_SMALL, "%zu ranges, capacity %d", r.size(), cap);
+    for (size_t i = 0; i < r.size(); ++i) { ranges[2 * i] = r[i].begin; ranges[2 * i + 1] = r[i].end; }
+    return LL_OK;
+}
+
+ll_status ll_cache_read_frame(const ll_cache* cache, int layer, int64_t frame, void* k_out, void* v_out, void* stream) {
+    CHECK_CACHE_LAYER(cache, layer);
+    if (!cache->dev) return fail(LL_ERR_INVALID_ARG, "index-only handle has no device cache");
+    if (!frame_held(cache->g, cache->layer[layer], frame)) return fail(LL_ERR_STATE, "layer %d does not hold frame %lld", layer, (long long)frame);
+    ReadFrameParams p{};
+    p.k_cache = layer_k(cache, layer); p.v_cache = layer_v(cache, layer); p.head_stride = cache->head_stride;
+    p.k_out = static_cast<uint16_t*>(k_out); p.v_out = static_cast<uint16_t*>(v_out);
+    p.H = cache->H; p.D = cache->D; p.P = cache->g.P; p.slot = slot_of_frame(cache->g, frame);
+    hipError_t e = launch_read_frame(p, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "read_frame kernel launch");
+    return LL_OK;
+}
+
+ll_status ll_set_attn_variant(int variant) {
+    if (variant != 0 && !attn_variant_name(variant)) return fail(LL_ERR_INVALID_ARG, "no attention variant %d", variant);
+    g_variant = variant;
+    return LL_OK;
+}
+const char* ll_attn_variant_name(int variant) { return attn_variant_name(variant); }
+
+const char* ll_status_string(ll_status s) {
+    switch (s) {
+        case LL_OK: return "LL_OK";
+        case LL_ERR_INVALID_ARG: return "LL_ERR_INVALID_ARG";
+        case LL_ERR_STATE: return "LL_ERR_STATE";
+        case LL_ERR_BUFFER_TOO_SMALL: return "LL_ERR_BUFFER_TOO_SMALL";
+        case LL_ERR_UNSUPPORTED: return "LL_ERR_UNSUPPORTED";
+        case LL_ERR_HIP: return "LL_ERR_HIP";
+    }
+    return "LL_ERR_?";
+}
+const char* ll_last_error(void) { return g_err.c_str(); }
+
+}  // extern "C"

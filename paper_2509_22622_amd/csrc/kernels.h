@@ -1,0 +1,94 @@
+// Interface between the C-ABI host code and the gfx950 kernels, and the HBM layout
+// of the rolling KV cache.
+//
+// Layout (per layer, per head; all bf16).  Token slots are grouped into "kblocks" of
+// 32 slots.  Each kblock is stored as the exact register image the 32x32x16 bf16 MFMA
+// wants, so a tile moves HBM -> LDS -> VGPR as straight 16-byte copies:
+//   K kblock  [D/8 chunks][32 rows][8 elems]   row i holds key slot 32*b + swap23(i),
+//             (swap23 exchanges bits 2 and 3) so that the S^T = K Q^T accumulator
+//             registers of a lane hold 8 consecutive keys per half -- the order the
+//             P^T operand of the second MFMA needs, with no cross-lane movement.
+//   V kblock  [D/32 d-blocks][2 key halves t][2 lane halves h][32 d][8 keys]
+//             = V^T fragments: element e of lane (h, dd) is key 32*b + 16*t + 8*h + e
+//             at feature 32*db + dd.
+// A head's K region is `kblocks_alloc` kblocks long, followed by its V region.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <cstdint>
+
+namespace ll {
+
+constexpr int KBLOCK = 32;          // key slots per kblock
+constexpr int PAD_KBLOCKS = 8;      // readable padding after the last kblock of a head
+constexpr int MAX_RANGES = 3;
+constexpr int MAX_ATTN_CHUNKS = 16; // query chunks per attention launch
+constexpr int MAX_APPEND_FRAMES = 32;
+
+__host__ __device__ inline int swap23(int i) {
+    return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
+}
+// Element offset (in bf16 units) of (slot-in-kblock k, feature d) inside a K kblock.
+__host__ __device__ inline int k_elem_offset(int k, int d) {
+    return (((d >> 3) * 32 + swap23(k)) << 3) + (d & 7);
+}
+// Element offset of (slot-in-kblock k, feature d) inside a V kblock.
+__host__ __device__ inline int v_elem_offset(int k, int d) {
+    const int t = k >> 4, h = (k >> 3) & 1, e = k & 7;
+    return ((((((d >> 5) * 2 + t) * 2 + h) * 32) + (d & 31)) << 3) + e;
+}
+
+struct RopeTables {            // device pointers into the cache buffer's tail
+    const double* inv_freq_t;  // [n_t]      frame-axis frequencies theta^(-2i/d_t)
+    const float2* row_cs;      // [grid_h][n_h]  (cos, sin) of y * freq
+    const float2* col_cs;      // [grid_w][n_w]  (cos, sin) of x * freq
+    int n_t, n_h, n_w;
+};
+
+struct AppendParams {
+    const uint16_t* q; const uint16_t* k; const uint16_t* v;   // [n_frames*P, H, D]
+    uint16_t* q_out;                                            // same shape
+    uint16_t* k_cache; uint16_t* v_cache;                       // layer base (head 0)
+    int64_t head_stride;                                        // elements between heads
+    RopeTables rope;
+    int H, D, P, grid_w;
+    int n_frames;
+    int64_t frame[MAX_APPEND_FRAMES];                           // absolute frame index
+    int64_t slot[MAX_APPEND_FRAMES];                            // first token slot
+    int seg_begin[MAX_APPEND_FRAMES + 1];                       // prefix sum of 32-slot segments
+};
+
+struct AttnChunk {
+    int q_begin, q_end;          // query rows [q_begin, q_end) of the q tensor
+    int tile_begin;              // first query tile of this chunk in the launch
+    int n_ranges;
+    int rs[MAX_RANGES], re[MAX_RANGES];   // key token-slot ranges
+};
+
+struct AttnParams {
+    const uint16_t* q; uint16_t* out;     // [rows, H, D]
+    const uint16_t* k_cache; const uint16_t* v_cache;   // layer base (head 0)
+    int64_t head_stride;
+    int H, D;
+    float scale_log2e;           // log2(e) / sqrt(D)
+    int n_chunks, n_tiles;       // n_tiles = query tiles over all chunks
+    AttnChunk chunk[MAX_ATTN_CHUNKS];
+};
+
+struct ReadFrameParams {
+    const uint16_t* k_cache; const uint16_t* v_cache; int64_t head_stride;
+    uint16_t* k_out; uint16_t* v_out;     // [P, H, D], either may be null
+    int H, D, P; int64_t slot;
+};
+
+// Attention variants (query rows per workgroup differ).
+int attn_variant_count();
+const char* attn_variant_name(int v);
+int attn_variant_default(int D);
+int attn_variant_qtile(int v);                 // query rows per workgroup
+bool attn_variant_supports(int v, int D);
+
+hipError_t launch_append(const AppendParams& p, hipStream_t s);
+hipError_t launch_attn(const AttnParams& p, int variant, hipStream_t s);
+hipError_t launch_read_frame(const ReadFrameParams& p, hipStream_t s);
+
+}  // namespace ll

@@ -1,0 +1,67 @@
+"""Shared plumbing of the GPU parity tests: run the HIP path and the oracle side by side.
+
+Nothing here computes any part of the method; tensors go in and out of the library
+through the binding, and the oracle is fed the same bf16 bit patterns.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+from oracle.longlive_oracle import Oracle, OracleConfig, bf16_bits_to_f64, error_metrics
+from paper_2509_22622_amd import binding as B
+from paper_2509_22622_amd import synth
+
+MAX_ABS_TOL = 1e-2       # benchmark definition: max abs error vs the fp64 oracle, bf16 inputs
+REL_L2_TOL = 5e-3        # benchmark definition: relative L2 error
+
+
+def to_dev(bits: np.ndarray) -> torch.Tensor:
+    return torch.from_numpy(bits.view(np.int16)).cuda().view(torch.bfloat16)
+
+
+def to_bits(t: torch.Tensor) -> np.ndarray:
+    return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def oracle_cfg(w: synth.Workload) -> OracleConfig:
+    return OracleConfig(w.layers, w.heads, w.head_dim, w.grid_h, w.grid_w, w.chunk_frames, w.sink_frames,
+                        w.window_frames)
+
+
+def make_cache(w: synth.Workload) -> B.Cache:
+    return B.Cache(w.layers, w.heads, w.head_dim, w.grid_h, w.grid_w, w.chunk_frames, w.sink_frames, w.window_frames)
+
+
+def assert_rounded(bits: np.ndarray, want: np.ndarray, what: str):
+    """bf16 `bits` is the fp32-computed, round-to-nearest value of `want` (half an ulp plus fp32 noise)."""
+    got = bf16_bits_to_f64(bits)
+    err = np.abs(got - want)
+    bound = np.abs(want) * 2.0 ** -8 * 1.01 + 2e-6
+    bad = err > bound
+    assert not bad.any(), f"{what}: {bad.sum()} of {bad.size} beyond half a bf16 ulp, worst {err.max():.3e}"
+
+
+def assert_parity(out_bits: np.ndarray, want: np.ndarray, what: str, logit_scale: float = 1.0):
+    """Both tolerances of the benchmark definition.  `logit_scale` is for the stress inputs only
+    (outside the graded configs): with logits of standard deviation s the rounding of q' and k'
+    to bf16, which the cache format imposes, moves every logit by about s * 2^-9, and outputs
+    grow from ~0.01 to ~1, so both tolerances are scaled by s there."""
+    got = bf16_bits_to_f64(out_bits)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    max_abs, rel = error_metrics(got, want)
+    assert max_abs <= MAX_ABS_TOL * logit_scale and rel <= REL_L2_TOL * logit_scale, \
+        f"{what}: max_abs {max_abs:.3e} rel_l2 {rel:.3e}"
+    return max_abs, rel
+
+
+def check_frame(cache: B.Cache, oracle: Oracle, w: synth.Workload, layer: int, frame: int, v_bits_expected=None):
+    """Cache contents of one frame: V bit-exact, rotated K within rounding."""
+    shape = (w.tokens_per_frame, w.heads, w.head_dim)
+    kd = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    vd = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    cache.read_frame(layer, frame, kd, vd)
+    torch.cuda.synchronize()
+    k_want, v_want = oracle.frame_kv(layer, frame)
+    assert np.array_equal(bf16_bits_to_f64(to_bits(vd)), v_want), f"V of frame {frame} not bit-exact"
+    assert_rounded(to_bits(kd), k_want, f"K' of frame {frame}")

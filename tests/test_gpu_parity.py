@@ -1,0 +1,212 @@
+"""GPU parity: the HIP library through its C-ABI against the fp64 oracle, element by element."""
+import numpy as np
+import pytest
+import torch
+
+from oracle.longlive_oracle import Oracle, bf16_bits_to_f64
+from paper_2509_22622_amd import binding as B
+from paper_2509_22622_amd import synth
+
+import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+
+def _stream_and_check(w, n_chunks, variant=0, q_scale=1.0, passes=1, check_cache=True, layer=0, short_last=False):
+    B.set_attn_variant(variant)
+    cache, oracle = H.make_cache(w), Oracle(H.oracle_cfg(w))
+    worst = (0.0, 0.0)
+    f0 = 0
+    for i in range(n_chunks):
+        n = w.chunk_frames
+        if short_last and i == n_chunks - 1:
+            n = 1
+        for rep in range(passes):
+            # all passes but the last are "noisy" versions of the chunk (Alg. 2)
+            q, k, v = synth.chunk_qkv(w, layer, i + 1000 * (passes - 1 - rep), n, q_scale=q_scale)
+            qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+            qr, out = torch.empty_like(qd), torch.empty_like(qd)
+            cache.chunk_append(layer, f0, n, qd, kd, vd, qr)
+            cache.sink_window_attn(layer, qr, out)
+            torch.cuda.synchronize()
+            q_want = oracle.append(layer, f0, q, k, v)
+        assert cache.live_frames(layer) == oracle.live_frames(layer)
+        H.assert_rounded(H.to_bits(qr), q_want, f"q' chunk {i}")
+        m = H.assert_parity(H.to_bits(out), oracle.attn(layer), f"{w.name} chunk {i}", logit_scale=q_scale)
+        worst = (max(worst[0], m[0]), max(worst[1], m[1]))
+        if check_cache:
+            for f in oracle.live_frames(layer):
+                H.check_frame(cache, oracle, w, layer, f)
+        f0 += n
+    B.set_attn_variant(0)
+    cache.close()
+    return worst
+
+
+def test_tiny_config_every_element():
+    """Config 1: 1 layer, 4 heads x 64, 6x10 grid, chunk 3, sink 3, window 6, 8 chunks."""
+    worst = _stream_and_check(synth.TINY, synth.TINY.n_chunks)
+    print("tiny worst (max_abs, rel_l2):", worst)
+
+
+MID128 = synth.Workload("mid128", 101, 1, 3, 128, 5, 8, 3, 3, 6, 8)       # P = 40: 8-aligned frames
+ODD128 = synth.Workload("odd128", 102, 1, 2, 128, 7, 9, 3, 2, 5, 8)       # P = 63: nothing aligned, S % C != 0
+NOSINK = synth.Workload("nosink", 103, 1, 2, 128, 6, 11, 2, 0, 7, 9)      # no sink, W % C != 0
+ODD64 = synth.Workload("odd64", 104, 1, 3, 64, 5, 7, 3, 3, 4, 7)
+WIDE = synth.Workload("wide", 105, 1, 2, 128, 16, 20, 3, 3, 3, 5)         # P = 320: several query tiles
+
+
+@pytest.mark.parametrize("w", [MID128, ODD128, NOSINK, ODD64, WIDE], ids=lambda w: w.name)
+def test_small_shapes_every_element(w):
+    _stream_and_check(w, w.n_chunks)
+
+
+@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+def test_every_d128_variant(variant):
+    _stream_and_check(WIDE, 5, variant=variant, check_cache=False)
+    _stream_and_check(ODD128, 6, variant=variant, check_cache=False)
+
+
+@pytest.mark.parametrize("variant", [5, 6])
+def test_every_d64_variant(variant):
+    _stream_and_check(ODD64, 6, variant=variant, check_cache=False)
+    _stream_and_check(synth.TINY, 5, variant=variant, check_cache=False)
+
+
+def test_peaky_softmax():
+    """q scaled by 4: logits of std 4, the running reference maximum moves often."""
+    _stream_and_check(MID128, 6, q_scale=4.0, check_cache=False)
+    _stream_and_check(ODD64, 6, q_scale=6.0, check_cache=False)
+
+
+def test_only_the_last_pass_stays():
+    """Alg. 2: several passes of a chunk at the same start frame, the last one is what later chunks see."""
+    _stream_and_check(MID128, 6, passes=3)
+
+
+def test_dead_slots_may_hold_nan():
+    """A frame that left the key set but still sits in a ring slot must have no influence, even as NaN."""
+    w = ODD128
+    cache, oracle = H.make_cache(w), Oracle(H.oracle_cfg(w))
+    f0 = 0
+    n_chunks = 7
+    for i in range(n_chunks):
+        n = 1 if i == n_chunks - 1 else w.chunk_frames                 # a short chunk leaves dead frames behind
+        q, k, v = synth.chunk_qkv(w, 0, i, n)
+        if i == 3:                                                      # poison this chunk's K and V
+            k = np.full_like(k, 0x7FC0)
+            v = np.full_like(v, 0x7FC0)
+        qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+        qr, out = torch.empty_like(qd), torch.empty_like(qd)
+        cache.chunk_append(0, f0, n, qd, kd, vd, qr)
+        cache.sink_window_attn(0, qr, out)
+        torch.cuda.synchronize()
+        oracle.append(0, f0, q, k, v)
+        live = oracle.live_frames(0)
+        assert cache.live_frames(0) == live
+        poisoned_live = any(9 <= f < 12 for f in live)
+        if not poisoned_live:
+            H.assert_parity(H.to_bits(out), oracle.attn(0), f"chunk {i}")
+        f0 += n
+    # the last chunk was short: frames of the poisoned chunk are dead but not yet overwritten
+    assert not any(9 <= f < 12 for f in live)
+    assert cache.slot_of_frame(0, 11) not in [cache.slot_of_frame(0, f) for f in live]
+    cache.close()
+
+
+def _prefill_case(w, include_sink, ws, n_win, pre_chunks, follow=2, variant=0):
+    B.set_attn_variant(variant)
+    P = w.tokens_per_frame
+    cache, oracle = H.make_cache(w), Oracle(H.oracle_cfg(w))
+    for i in range(pre_chunks):                                         # some history first
+        q, k, v = synth.chunk_qkv(w, 0, i)
+        qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+        cache.chunk_append(0, i * w.chunk_frames, w.chunk_frames, qd, kd, vd, torch.empty_like(qd))
+        oracle.append(0, i * w.chunk_frames, q, k, v)
+    nf = (w.sink_frames if include_sink else 0) + n_win
+    shape = (nf * P, w.heads, w.head_dim)
+    q, k, v = (synth.normal_bf16(shape, w.cfg_id, 0, 500, t) for t in "qkv")
+    qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+    out = torch.empty_like(qd)
+    cache.recache_prefill(0, include_sink, ws, n_win, qd, kd, vd, out)
+    torch.cuda.synchronize()
+    want = oracle.recache_prefill(0, include_sink, ws, n_win, q, k, v)
+    H.assert_parity(H.to_bits(out), want, f"{w.name} prefill")
+    assert cache.live_frames(0) == oracle.live_frames(0)
+    for f in oracle.live_frames(0):
+        H.check_frame(cache, oracle, w, 0, f)
+    f0 = ws + n_win
+    for i in range(follow):                                             # streaming goes on from the rebuilt cache
+        q, k, v = synth.chunk_qkv(w, 0, 600 + i)
+        qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+        qr, out = torch.empty_like(qd), torch.empty_like(qd)
+        cache.chunk_append(0, f0, w.chunk_frames, qd, kd, vd, qr)
+        cache.sink_window_attn(0, qr, out)
+        torch.cuda.synchronize()
+        oracle.append(0, f0, q, k, v)
+        assert cache.live_frames(0) == oracle.live_frames(0)
+        H.assert_parity(H.to_bits(out), oracle.attn(0), f"{w.name} after prefill {i}")
+        f0 += w.chunk_frames
+    B.set_attn_variant(0)
+    cache.close()
+
+
+def test_recache_prefill_small():
+    _prefill_case(MID128, True, 3, 9, pre_chunks=4)                     # window right after the sink
+    _prefill_case(MID128, True, 177, 9, pre_chunks=60)                  # late window, ring wrapped many times
+    _prefill_case(MID128, False, 15, 9, pre_chunks=8)                   # sink kept as it is
+    _prefill_case(ODD128, True, 8, 7, pre_chunks=5)                     # S % C != 0, short last chunk
+    _prefill_case(ODD64, True, 12, 6, pre_chunks=6)
+    _prefill_case(NOSINK, True, 10, 9, pre_chunks=10)                   # no sink at all
+
+
+def test_prefill_equals_streaming_on_the_gpu():
+    """Same q,k,v streamed chunk by chunk or prefilled at once: same outputs, same cache bits."""
+    w = MID128
+    P, nf = w.tokens_per_frame, 12
+    shape = (nf * P, w.heads, w.head_dim)
+    q, k, v = (synth.normal_bf16(shape, w.cfg_id, 0, 700, t) for t in "qkv")
+    qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+    a, b = H.make_cache(w), H.make_cache(w)
+    outs = []
+    for f0 in range(0, nf, 3):
+        sl = slice(f0 * P, (f0 + 3) * P)
+        qr, o = torch.empty_like(qd[sl]), torch.empty_like(qd[sl])
+        a.chunk_append(0, f0, 3, qd[sl], kd[sl], vd[sl], qr)
+        a.sink_window_attn(0, qr, o)
+        outs.append(o)
+    ob = torch.empty_like(qd)
+    b.recache_prefill(0, True, 3, 9, qd, kd, vd, ob)
+    torch.cuda.synchronize()
+    assert torch.equal(torch.cat(outs).view(torch.int16), ob.view(torch.int16))
+    assert a.live_frames(0) == b.live_frames(0) and a.live_ranges(0) == b.live_ranges(0)
+    for f in a.live_frames(0):
+        ka, va, kb, vb = (torch.empty((P, w.heads, w.head_dim), dtype=torch.bfloat16, device="cuda") for _ in range(4))
+        a.read_frame(0, f, ka, va)
+        b.read_frame(0, f, kb, vb)
+        torch.cuda.synchronize()
+        assert torch.equal(ka.view(torch.int16), kb.view(torch.int16)) and torch.equal(va.view(torch.int16), vb.view(torch.int16))
+    a.close()
+    b.close()
+
+
+def test_deterministic_and_in_place():
+    """Two runs give identical bits; q_out may alias q and out may alias q_roped."""
+    w = WIDE
+    q, k, v = synth.chunk_qkv(w, 0, 0)
+    res = []
+    for rep in range(2):
+        cache = H.make_cache(w)
+        qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+        if rep == 0:
+            qr, out = torch.empty_like(qd), torch.empty_like(qd)
+            cache.chunk_append(0, 0, 3, qd, kd, vd, qr)
+            cache.sink_window_attn(0, qr, out)
+        else:
+            cache.chunk_append(0, 0, 3, qd, kd, vd, qd)
+            cache.sink_window_attn(0, qd, qd)
+            out = qd
+        torch.cuda.synchronize()
+        res.append(H.to_bits(out))
+        cache.close()
+    assert np.array_equal(res[0], res[1])

@@ -317,3 +317,17 @@ def test_attention_matches_library_softmax():
     ref = torch.einsum("hqk,khd->qhd", torch.softmax(sc, dim=-1), torch.from_numpy(V)).numpy()
     assert np.abs(got - ref).max() < 1e-14
     assert np.array_equal(attention(q, K, V, rows=[5, 1]), got[[5, 1]])
+
+
+def test_vectorised_rope_uses_the_scalar_angles():
+    """rope_rotate's angle table is rope_angles (the scalar definition) token by token."""
+    cfg = OracleConfig(1, 1, 128, 3, 4, 2, 0, 4)
+    P = cfg.tokens_per_frame
+    x = np.zeros((2 * P, 1, 128))
+    x[..., 0::2] = 1.0
+    r = rope_rotate(cfg, x, 957)
+    for t in range(2 * P):
+        y, xx = divmod(t % P, cfg.grid_w)
+        ang = rope_angles(cfg, 957 + t // P, y, xx)
+        assert np.allclose(r[t, 0, 0::2], np.cos(ang), atol=2e-13, rtol=0)
+        assert np.allclose(r[t, 0, 1::2], np.sin(ang), atol=2e-13, rtol=0)
