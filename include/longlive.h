@@ -76,7 +76,8 @@ ll_status ll_cache_reset(ll_cache* cache, int layer);
 /* Stage chunk [frame_start, frame_start + n_frames) of `layer`  (Appendix Alg. 2: every
  * denoising pass of a chunk runs with the chunk's own K/V, only the final clean pass stays).
  *   Rotates q and k by the 3D rotary embedding at (absolute frame, row, column) in fp32,
- *   writes rotated q to q_out (may alias q), rotated k and v into the layer's cache slots.
+ *   writes q_out = bf16(rotated q * log2(e)/sqrt(D)) (the softmax scale is folded in here, with
+ *   one rounding; q_out may alias q) and rotated k and v into the layer's cache slots.
  *   frame_start equal to the staged chunk's start  -> overwrite the same slots;
  *   frame_start equal to staged start + its length -> the staged chunk becomes permanent,
  *       frames older than frame_start - W (non-sink) stop being live, sink frames stay;
@@ -88,7 +89,7 @@ ll_status ll_chunk_append(ll_cache* cache, int layer, int64_t frame_start, int n
 
 /* out = softmax(q_roped K^T / sqrt(D)) V over sink U window U staged chunk of `layer`
  * (Sec. 3.3; no mask inside the key set: bidirectional within the chunk, the rest is past).
- *   q_roped: device, [Nq, H, D] bf16, the q_out of the matching ll_chunk_append, where
+ *   q_roped: device, [Nq, H, D] bf16, the (pre-scaled) q_out of the matching ll_chunk_append, where
  *   Nq = staged n_frames * P.  out: device, same shape (may alias q_roped).
  *   LL_ERR_STATE if no chunk is staged. */
 ll_status ll_sink_window_attn(ll_cache* cache, int layer, const void* q_roped, void* out,

@@ -184,6 +184,7 @@ static ll_status enqueue_append(ll_cache* c, int layer, const int64_t* frames, i
         p.k = static_cast<const uint16_t*>(k) + base * frame_elems;
         p.v = static_cast<const uint16_t*>(v) + base * frame_elems;
         p.q_out = static_cast<uint16_t*>(q_out) + base * frame_elems;
+        p.q_scale = float(1.4426950408889634 / std::sqrt(double(c->D)));
         p.k_cache = layer_k(c, layer); p.v_cache = layer_v(c, layer);
         p.head_stride = c->head_stride;
         p.rope = c->rope;
@@ -221,7 +222,7 @@ static ll_status enqueue_attn(ll_cache* c, int layer, const std::vector<ChunkWor
         p.k_cache = layer_k(c, layer); p.v_cache = layer_v(c, layer);
         p.head_stride = c->head_stride;
         p.H = c->H; p.D = c->D;
-        p.scale_log2e = float(1.4426950408889634 / std::sqrt(double(c->D)));
+        p.scale_log2e = 1.0f;          // ll_chunk_append already folded log2(e)/sqrt(D) into q
         const int m = int(std::min<size_t>(MAX_ATTN_CHUNKS, work.size() - base));
         // longest key sets first: they bound the launch
         std::vector<int> order(m);

@@ -7,6 +7,10 @@
 // exactly one K kblock and one V kblock and builds their images in LDS before storing
 // them with 16-byte stores.
 //
+// The rotated queries leave pre-multiplied by log2(e)/sqrt(D) (one rounding of the scaled
+// value, so no accuracy is lost): the attention kernel then works in the log2 domain with
+// no per-score multiply.
+//
 // The rotary convention (the paper defines none) is the factorised (frame, row,
 // column) form: the D/2 adjacent-element pairs are split n_t | n_h | n_w, pair i of
 // an axis turns by position * theta^(-2i/d_axis); frame positions are absolute.
@@ -74,8 +78,8 @@ __global__ __launch_bounds__(256) void ll_append_kernel(const AppendParams p) {
             else cs = p.rope.col_cs[x * p.rope.n_w + (pi - p.rope.n_t - p.rope.n_h)];
             const float qr = bf16_to_f32(qv[2 * e]), qi = bf16_to_f32(qv[2 * e + 1]);
             const float kr = bf16_to_f32(kv[2 * e]), ki = bf16_to_f32(kv[2 * e + 1]);
-            qo[2 * e] = f32_to_bf16(qr * cs.x - qi * cs.y);
-            qo[2 * e + 1] = f32_to_bf16(qr * cs.y + qi * cs.x);
+            qo[2 * e] = f32_to_bf16((qr * cs.x - qi * cs.y) * p.q_scale);
+            qo[2 * e + 1] = f32_to_bf16((qr * cs.y + qi * cs.x) * p.q_scale);
             ko[2 * e] = f32_to_bf16(kr * cs.x - ki * cs.y);
             ko[2 * e + 1] = f32_to_bf16(kr * cs.y + ki * cs.x);
         }

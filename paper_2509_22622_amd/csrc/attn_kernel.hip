@@ -249,18 +249,11 @@ __global__ __launch_bounds__(NW * 64) void ll_attn_kernel(const AttnParams p) {
     }
 }
 
-struct Variant {
-    const char* name;
-    int D, qtile, lds_bytes;
-    void (*kernel)(const AttnParams);
-    int threads;
-};
-
 #define LL_VARIANT(D, QB, NW, KT)                                                              \
     { "d" #D "_q" #QB "x" #NW "_k" #KT, D, NW * QB * 32, 2 * 2 * KT * KBLOCK * D * 2,          \
       ll_attn_kernel<D, QB, NW, KT>, NW * 64 }
 
-static const Variant kVariants[] = {
+static const AttnVariant kSimpleVariants[] = {
     LL_VARIANT(128, 2, 4, 2),   // 1: 256 queries, 64-key tiles
     LL_VARIANT(128, 2, 4, 4),   // 2: 256 queries, 128-key tiles
     LL_VARIANT(128, 1, 4, 2),   // 3: 128 queries
@@ -268,21 +261,27 @@ static const Variant kVariants[] = {
     LL_VARIANT(64, 2, 4, 2),    // 5
     LL_VARIANT(64, 1, 4, 2),    // 6
 };
-constexpr int kNumVariants = sizeof(kVariants) / sizeof(kVariants[0]);
+constexpr int kNumSimple = sizeof(kSimpleVariants) / sizeof(kSimpleVariants[0]);
 
-int attn_variant_count() { return kNumVariants; }
-const char* attn_variant_name(int v) { return (v >= 1 && v <= kNumVariants) ? kVariants[v - 1].name : nullptr; }
+// variant ids: 1..kNumSimple are the kernels of this file, then the software-pipelined kernels
+static const AttnVariant* variant(int v) {
+    if (v >= 1 && v <= kNumSimple) return &kSimpleVariants[v - 1];
+    if (v > kNumSimple && v <= kNumSimple + kNumStreamVariants) return &kStreamVariants[v - kNumSimple - 1];
+    return nullptr;
+}
+int attn_variant_count() { return kNumSimple + kNumStreamVariants; }
+const char* attn_variant_name(int v) { return variant(v) ? variant(v)->name : nullptr; }
 int attn_variant_default(int D) { return D == 128 ? 1 : 6; }
-int attn_variant_qtile(int v) { return kVariants[v - 1].qtile; }
-bool attn_variant_supports(int v, int D) { return v >= 1 && v <= kNumVariants && kVariants[v - 1].D == D; }
+int attn_variant_qtile(int v) { return variant(v)->qtile; }
+bool attn_variant_supports(int v, int D) { return variant(v) && variant(v)->D == D; }
 
 hipError_t launch_attn(const AttnParams& p, int variant, hipStream_t s) {
     if (!attn_variant_supports(variant, p.D)) return hipErrorInvalidValue;
-    const Variant& v = kVariants[variant - 1];
+    const AttnVariant& v = *ll::variant(variant);
     const int total = p.n_tiles * p.H;
     if (total <= 0) return hipSuccess;
     const int grid = ((total + 7) / 8) * 8;
-    static bool attr_set[kNumVariants] = {};
+    static bool attr_set[32] = {};
     if (!attr_set[variant - 1]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, v.lds_bytes);

@@ -46,7 +46,8 @@ struct RopeTables {            // device pointers into the cache buffer's tail
 
 struct AppendParams {
     const uint16_t* q; const uint16_t* k; const uint16_t* v;   // [n_frames*P, H, D]
-    uint16_t* q_out;                                            // same shape
+    uint16_t* q_out;                                            // same shape; rotated q times q_scale
+    float q_scale;                                              // log2(e) / sqrt(D), folded into q_out
     uint16_t* k_cache; uint16_t* v_cache;                       // layer base (head 0)
     int64_t head_stride;                                        // elements between heads
     RopeTables rope;
@@ -69,7 +70,7 @@ struct AttnParams {
     const uint16_t* k_cache; const uint16_t* v_cache;   // layer base (head 0)
     int64_t head_stride;
     int H, D;
-    float scale_log2e;           // log2(e) / sqrt(D)
+    float scale_log2e;           // factor still to apply to q.k in the log2 domain (1 when q is pre-scaled)
     int n_chunks, n_tiles;       // n_tiles = query tiles over all chunks
     AttnChunk chunk[MAX_ATTN_CHUNKS];
 };
@@ -79,6 +80,16 @@ struct ReadFrameParams {
     uint16_t* k_out; uint16_t* v_out;     // [P, H, D], either may be null
     int H, D, P; int64_t slot;
 };
+
+// One attention kernel instantiation.
+struct AttnVariant {
+    const char* name;
+    int D, qtile, lds_bytes;
+    void (*kernel)(const AttnParams);
+    int threads;
+};
+extern const AttnVariant kStreamVariants[];
+extern const int kNumStreamVariants;
 
 // Attention variants (query rows per workgroup differ).
 int attn_variant_count();

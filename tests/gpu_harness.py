@@ -5,6 +5,8 @@ through the binding, and the oracle is fed the same bf16 bit patterns.
 """
 from __future__ import annotations
 
+import math
+
 import numpy as np
 import torch
 
@@ -31,6 +33,11 @@ def oracle_cfg(w: synth.Workload) -> OracleConfig:
 
 def make_cache(w: synth.Workload) -> B.Cache:
     return B.Cache(w.layers, w.heads, w.head_dim, w.grid_h, w.grid_w, w.chunk_frames, w.sink_frames, w.window_frames)
+
+
+def q_prescale(w: synth.Workload) -> float:
+    """ll_chunk_append returns the rotated queries multiplied by log2(e)/sqrt(D) (see longlive.h)."""
+    return math.log2(math.e) / math.sqrt(w.head_dim)
 
 
 def assert_rounded(bits: np.ndarray, want: np.ndarray, what: str):

@@ -31,7 +31,7 @@ def _stream_and_check(w, n_chunks, variant=0, q_scale=1.0, passes=1, check_cache
             torch.cuda.synchronize()
             q_want = oracle.append(layer, f0, q, k, v)
         assert cache.live_frames(layer) == oracle.live_frames(layer)
-        H.assert_rounded(H.to_bits(qr), q_want, f"q' chunk {i}")
+        H.assert_rounded(H.to_bits(qr), q_want * H.q_prescale(w), f"q' chunk {i}")
         m = H.assert_parity(H.to_bits(out), oracle.attn(layer), f"{w.name} chunk {i}", logit_scale=q_scale)
         worst = (max(worst[0], m[0]), max(worst[1], m[1]))
         if check_cache:
@@ -61,13 +61,13 @@ def test_small_shapes_every_element(w):
     _stream_and_check(w, w.n_chunks)
 
 
-@pytest.mark.parametrize("variant", [1, 2, 3, 4])
+@pytest.mark.parametrize("variant", [1, 2, 3, 4, 7, 8])
 def test_every_d128_variant(variant):
     _stream_and_check(WIDE, 5, variant=variant, check_cache=False)
     _stream_and_check(ODD128, 6, variant=variant, check_cache=False)
 
 
-@pytest.mark.parametrize("variant", [5, 6])
+@pytest.mark.parametrize("variant", [5, 6, 9])
 def test_every_d64_variant(variant):
     _stream_and_check(ODD64, 6, variant=variant, check_cache=False)
     _stream_and_check(synth.TINY, 5, variant=variant, check_cache=False)
