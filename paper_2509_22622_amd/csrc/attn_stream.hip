@@ -18,6 +18,8 @@
 // the packed dot-product instruction.  The reference maximum moves only when a score
 // exceeds it by more than RESCALE_SLACK (then O, the row sum and the pending scores are
 // rescaled); the final division by the row sum makes the result independent of it.
+#include <type_traits>
+
 #include "kernels.h"
 
 namespace ll {
@@ -52,6 +54,15 @@ __device__ inline void sp_wait_vmcnt() {
 __device__ __forceinline__ int sp_pick(int v, int n0, int n01, int a0, int a1, int a2) {
     return v < n0 ? a0 : (v < n01 ? a1 : a2);
 }
+// Kblocks that may be cut by a range boundary are the first and last of each range; the one after v:
+__device__ __forceinline__ int sp_next_edge(int v, int n0, int n01, int T) {
+    const int cand[6] = {0, n0 - 1, n0, n01 - 1, n01, T - 1};
+    int best = 0x7FFFFFFF;
+#pragma unroll
+    for (int c = 0; c < 6; ++c)
+        if (cand[c] > v && cand[c] < best) best = cand[c];
+    return best;
+}
 // bit r set: the key held by accumulator register r of a lane in `half` is inside [rs, re)
 __device__ __forceinline__ unsigned sp_live_mask(int key0, int rs, int re, int half) {
     unsigned live = 0;
@@ -63,18 +74,24 @@ __device__ __forceinline__ unsigned sp_live_mask(int key0, int rs, int re, int h
     return live;
 }
 
-template <int D, int PF>
+template <int D, int PF, int QR>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_attn_sp_kernel(const AttnParams p) {
     constexpr int KS = D / 16;                  // k-steps of S^T = K Q^T, also fragments per K kblock
     constexpr int DB = D / 32;                  // 32-row blocks of O^T
     constexpr int KB_BYTES = KBLOCK * D * 2;
     constexpr int STAGE_BYTES = 2 * KB_BYTES;   // [K kblock | V kblock]
-    constexpr int NS = PF + 2;                  // ring stages: a stage is rewritten two barriers after its last read
+    constexpr int NS = 8;                       // ring stages (a power of two: stage = kblock & 7)
     constexpr int NF = 2 * KS;                  // 1 KB fragments per stage
     constexpr int LPW = NF / 8;                 // loads per wave per kblock
     constexpr int QT = 256;
     static_assert(NF % 8 == 0, "fragments must split over 8 waves");
     static_assert(PF >= 3, "kblock i + 2 must have landed when iteration i starts");
+    static_assert(PF + 2 <= NS, "a stage is rewritten two barriers after its last read");
+    // QR of the KS query fragments stay in registers, the others live in LDS behind the ring and are
+    // read again for every kblock (registers are the scarcer resource: 256 per wave at two waves per SIMD)
+    constexpr int QL = KS - QR;
+    constexpr int Q_LDS_OFF = NS * STAGE_BYTES;
+    static_assert(QR >= 0 && QR <= KS, "QR out of range");
 
     extern __shared__ __attribute__((aligned(16))) char lds[];
 
@@ -104,13 +121,23 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     const int q_end = ch.q_end;
     const int T = (ke0 - kb0) + (ke1 - kb1) + (ke2 - kb2);                // kblocks over all ranges
 
-    bf16x8 qf[KS];                               // Q^T fragments (pre-scaled by log2(e)/sqrt(D))
+    // Q^T fragments (pre-scaled by log2(e)/sqrt(D)): fragment ks holds features 16*ks + 8*half + 0..7
+    bf16x8 qf[QR > 0 ? QR : 1];
+    char* const q_lds = lds + Q_LDS_OFF + wave * (QL * 1024) + lane * 16;     // this wave's private area
     {
         const int row = min(q0 + col, q_end - 1);
         const uint16_t* src = p.q + (int64_t(row) * p.H + head) * D + half * 8;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(src + ks * 16);
+        for (int ks = 0; ks < KS; ++ks) {
+            const bf16x8 f = *reinterpret_cast<const bf16x8*>(src + ks * 16);
+            if (ks < QR) qf[ks] = f;
+            else *reinterpret_cast<bf16x8*>(q_lds + (ks - QR) * 1024) = f;
+        }
     }
+    auto q_frag = [&](int ks) -> bf16x8 {
+        if (ks < QR) return qf[ks];
+        return *reinterpret_cast<const bf16x8*>(q_lds + (ks - QR) * 1024);
+    };
 
     const char* kbase = reinterpret_cast<const char*>(p.k_cache + head * p.head_stride);
     const char* vbase = reinterpret_cast<const char*>(p.v_cache + head * p.head_stride);
@@ -120,7 +147,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     // range (only those can be cut by a range boundary; they take the slow path)
 #define SP_PHYS_KB(v) ((v) + sp_pick((v), n0, n01, kb0, kb1 - n0, kb2 - n01))
 #define SP_LIVE(v) sp_live_mask(SP_PHYS_KB(v) * KBLOCK, sp_pick((v), n0, n01, rs0, rs1, rs2), sp_pick((v), n0, n01, re0, re1, re2), half)
-#define SP_IS_EDGE(v) ((v) == 0 || (v) == n0 - 1 || (v) == n0 || (v) == n01 - 1 || (v) == n01 || (v) == T - 1)
 
     // direct-to-LDS loads of physical kblock kb into a ring stage
     const unsigned lane_off = lane * 16;
@@ -136,7 +162,6 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                                              (__attribute__((address_space(3))) void*)(dst), 16, 0, 0);
         }
     };
-    auto next_stage = [](int st) { return st + 1 == NS ? 0 : st + 1; };
 
 #pragma unroll
     for (int j = 0; j < PF; ++j) {
@@ -177,152 +202,148 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 #pragma unroll
         for (int r = 0; r < 16; ++r) o[db][r] = 0.f;
     float lsum0 = 0.f, lsum1 = 0.f;              // row sum of this lane's keys (two chains)
-    f32x16 negm;                                 // every element = -(reference maximum) of this lane's query
-    f32x16 s;                                    // scores of kblock i minus the reference, log2 domain
+    float mref;                                  // reference maximum of this lane's query (log2 domain)
+    f32x16 sA, sB;                               // scores minus the reference (log2 domain) of kblocks i and i + 1
     bf16x8 kfr[KS];                              // K fragments of kblock i + 1
-    u32x4 vfr[2][DB];                            // V^T fragments of kblock i - 1
-    unsigned pb[2][4];                           // P^T fragments of kblock i - 1 (bf16 pairs)
+    u32x4 vfr[2][DB];                            // V^T fragments of kblock i
+    float mx = -INFINITY;                        // largest score of kblock i among this lane's keys (kblock 0: reference already exact)
 
-    // ---- prologue: scores of kblock 0 with a zero reference, then the true first reference
-    read_k(0, kfr);
-#pragma unroll
-    for (int r = 0; r < 16; ++r) s[r] = 0.f;
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ks], qf[ks], s, 0, 0, 0);
-    auto mask_s = [&](unsigned live) {
+    auto mask_s = [&](f32x16& s, unsigned live) {
 #pragma unroll
         for (int r = 0; r < 16; ++r)
             if (!((live >> r) & 1)) s[r] = -INFINITY;
     };
-    auto max_s = [&]() {
-        float mx = fmaxf(fmaxf(s[0], s[1]), s[2]);
+    auto max_s = [&](const f32x16& s) {
+        float m = fmaxf(fmaxf(s[0], s[1]), s[2]);
 #pragma unroll
-        for (int r = 3; r < 15; r += 2) mx = fmaxf(fmaxf(mx, s[r]), s[r + 1]);
-        return fmaxf(mx, s[15]);
+        for (int r = 3; r < 15; r += 2) m = fmaxf(fmaxf(m, s[r]), s[r + 1]);
+        return fmaxf(m, s[15]);
     };
-    mask_s(SP_LIVE(0));
+
+    // ---- prologue: scores of kblock 0 against a zero reference, then the true first reference
+    read_k(0, kfr);
+#pragma unroll
+    for (int r = 0; r < 16; ++r) sA[r] = 0.f;
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ks], q_frag(ks), sA, 0, 0, 0);
+    mask_s(sA, SP_LIVE(0));
     {
-        float mx = s[0];
-#pragma unroll
-        for (int r = 1; r < 16; ++r) mx = fmaxf(mx, s[r]);
-        const float m0 = fmaxf(mx, __shfl_xor(mx, 32));   // a kblock of a range holds a live key: finite
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            negm[r] = -m0;
-            s[r] -= m0;
-        }
+        const float m = max_s(sA);
+        const float m0 = fmaxf(m, __shfl_xor(m, 32));     // a kblock of a range holds a live key: finite
+        mref = m0;
     }
     read_k(1 % NS, kfr);
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-#pragma unroll
-        for (int e = 0; e < 4; ++e) pb[t][e] = 0u;
-#pragma unroll
-        for (int db = 0; db < DB; ++db) vfr[t][db] = u32x4{0u, 0u, 0u, 0u};
+
+    // One kblock per step.  S_CUR holds the scores of kblock I on entry, S_NEXT those of kblock I + 1 on exit;
+    // the loop below alternates the two register sets so that no copy is needed.
+    //
+    // A step is NSLOT = KS + 2*DB slots, each opened by one MFMA: first the KS MFMAs of S^T = K Q^T for kblock
+    // I+1, then the 2*DB MFMAs of O^T += V^T P^T for kblock I.  The vector work of kblock I rides in their shadow
+    // as a skewed pipeline over the 8 score pairs of a lane, so that no instruction waits for the one before it:
+    //     slot w-1: subtract the reference from pair w      slot w+1: pack pair w to bf16 (one P^T word)
+    //     slot w  : exp2 of pair w                          slot w+2: add the packed pair to the row sum
+    // the last slots take the running maximum of the new scores, and every slot reads one fragment for later:
+    // V^T of kblock I during the first KS slots, K of kblock I+2 afterwards.  A scheduling fence after every
+    // slot keeps the compiler from regrouping the instructions and the empty asm statements pin each stage's
+    // results inside its slot.  Before the slots: the rare path (a score above the reference by more than the
+    // slack, or a kblock that may be cut by a range boundary: mask, move the reference, rescale O and the sums).
+    // After them: the wave waits for its own older loads and the workgroup barrier hands the ring stages over.
+    constexpr int NSLOT = KS + 2 * DB;
+    constexpr int MAX_FIRST = NSLOT - 4;         // slots that take the maximum (the S^T chain has drained by then)
+    // slot of each stage of score pair w; the packed pair must exist before the MFMA that consumes it
+    auto slot_cvt = [](int w) { const int dl = KS + (w >> 2) * DB - 1; return w + 1 < dl ? w + 1 : dl; };
+    auto slot_exp = [slot_cvt](int w) { return w < slot_cvt(w) ? w : slot_cvt(w); };
+    auto slot_sub = [slot_exp](int w) { const int a = w > 0 ? w - 1 : 0; return a < slot_exp(w) ? a : slot_exp(w); };
+    auto slot_sum = [](int w) { return w + 2 < NSLOT - 1 ? w + 2 : NSLOT - 1; };
+#define SP_PIN(x) asm volatile("" ::"v"(x))
+#define SP_STEP(I, S_CUR, S_NEXT)                                                                                  \
+    {                                                                                                               \
+        const bool edge = (I) == next_edge;                                                                         \
+        if (edge || __any(mx > thr)) {                                                                              \
+            if (edge) {                                                                                             \
+                mask_s(S_CUR, SP_LIVE(I));                                                                          \
+                mx = max_s(S_CUR);                                                                                  \
+                next_edge = sp_next_edge((I), n0, n01, T);                                                          \
+            }                                                                                                       \
+            const float mnew = fmaxf(fmaxf(mx, __shfl_xor(mx, 32)), mref);                                          \
+            const float alpha = __builtin_amdgcn_exp2f(mref - mnew);                                                \
+            mref = mnew;                                                                                            \
+            thr = mnew + SP_RESCALE_SLACK;                                                                          \
+            lsum0 *= alpha;                                                                                         \
+            lsum1 *= alpha;                                                                                         \
+            _Pragma("unroll") for (int db = 0; db < DB; ++db)                                                       \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) o[db][r] *= alpha;                                   \
+        }                                                                                                           \
+        const char* vt = lds + (((I)) & (NS - 1)) * STAGE_BYTES + KB_BYTES + lane_off;                              \
+        const char* kt = lds + (((I) + 2) & (NS - 1)) * STAGE_BYTES + lane_off;                                     \
+        float d0[8], d1[8];                                                                                         \
+        unsigned pb[2][4];                                                                                          \
+        float m_run = -INFINITY;                                                                                    \
+        _Pragma("unroll") for (int r = 0; r < 16; ++r) S_NEXT[r] = 0.f;                                             \
+        _Pragma("unroll") for (int k = 0; k < NSLOT; ++k) {                                                         \
+            if (k < KS) {                                                                                           \
+                S_NEXT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[k], q_frag(k), S_NEXT, 0, 0, 0);               \
+            } else {                                                                                                \
+                const int t = (k - KS) / DB, db = (k - KS) % DB;                                                    \
+                const u32x4 bv = {pb[t][0], pb[t][1], pb[t][2], pb[t][3]};                                          \
+                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vfr[t][db]),             \
+                                                                 __builtin_bit_cast(bf16x8, bv), o[db], 0, 0, 0);   \
+            }                                                                                                       \
+            if (k == 0) {                                                                                           \
+                const int v = min((I) + PF, T - 1);                                                                 \
+                issue_loads(SP_PHYS_KB(v), ((I) + PF) & (NS - 1));                                                  \
+            }                                                                                                       \
+            _Pragma("unroll") for (int w = 0; w < 8; ++w) {                                                         \
+                if (k == slot_sub(w)) {                                                                             \
+                    d0[w] = S_CUR[2 * w] - mref;                                                                    \
+                    d1[w] = S_CUR[2 * w + 1] - mref;                                                                \
+                    SP_PIN(d0[w]);                                                                                  \
+                    SP_PIN(d1[w]);                                                                                  \
+                }                                                                                                   \
+                if (k == slot_exp(w)) {                                                                             \
+                    d0[w] = __builtin_amdgcn_exp2f(d0[w]);                                                          \
+                    d1[w] = __builtin_amdgcn_exp2f(d1[w]);                                                          \
+                    SP_PIN(d0[w]);                                                                                  \
+                    SP_PIN(d1[w]);                                                                                  \
+                }                                                                                                   \
+                if (k == slot_cvt(w)) {                                                                             \
+                    pb[w >> 2][w & 3] = sp_pack_bf16(d0[w], d1[w]);                                                 \
+                    SP_PIN(pb[w >> 2][w & 3]);                                                                      \
+                }                                                                                                   \
+                if (k == slot_sum(w)) {                                                                             \
+                    if (w < 4) lsum0 = sp_pair_sum(pb[w >> 2][w & 3], lsum0);                                       \
+                    else lsum1 = sp_pair_sum(pb[w >> 2][w & 3], lsum1);                                             \
+                }                                                                                                   \
+            }                                                                                                       \
+            if (k >= MAX_FIRST) {                                                                                   \
+                const int r = (k - MAX_FIRST) * 4;                                                                  \
+                m_run = fmaxf(fmaxf(m_run, S_NEXT[r]), S_NEXT[r + 1]);                                              \
+                m_run = fmaxf(fmaxf(m_run, S_NEXT[r + 2]), S_NEXT[r + 3]);                                          \
+            }                                                                                                       \
+            if (k < KS) {                                                                                           \
+                _Pragma("unroll") for (int f = k * 2 * DB / KS; f < (k + 1) * 2 * DB / KS; ++f)                     \
+                    vfr[f / DB][f % DB] = *reinterpret_cast<const u32x4*>(vt + ((f % DB) * 2 + f / DB) * 1024);     \
+            } else {                                                                                                \
+                _Pragma("unroll") for (int f = (k - KS) * KS / (2 * DB); f < (k - KS + 1) * KS / (2 * DB); ++f)     \
+                    kfr[f] = *reinterpret_cast<const bf16x8*>(kt + f * 1024);                                       \
+            }                                                                                                       \
+            __builtin_amdgcn_sched_barrier(0);                                                                      \
+            if (k == KS - 1 && edge) mask_v(vfr, SP_LIVE(I));                                                       \
+        }                                                                                                           \
+        mx = m_run;                                                                                                 \
+        sp_wait_vmcnt<(PF - 3) * LPW>();                                                                            \
+        __builtin_amdgcn_s_barrier();                                                                               \
     }
-    int st_v = 0;                                // stage of kblock i
-    int st_k = 2 % NS;                           // stage of kblock i + 2
-    int st_ld = PF % NS;                         // stage the next loads go to
 
-    bool edge_prev = false;                      // kblock i - 1 (whose V fragments are in vfr) is cut by a range boundary
-    for (int i = 0; i < T; ++i) {
-        // ---- rare path: a kblock cut by a range boundary, or a score above the reference by more than the slack
-        {
-            const bool edge_cur = i > 0 && SP_IS_EDGE(i);      // kblock 0 was masked in the prologue
-            float mx = max_s();
-            if (__any(mx > SP_RESCALE_SLACK) || edge_cur || edge_prev) {
-                if (edge_prev) mask_v(vfr, SP_LIVE(i - 1));
-                if (edge_cur) {
-                    mask_s(SP_LIVE(i));
-                    mx = max_s();
-                }
-                const float delta = fmaxf(fmaxf(mx, __shfl_xor(mx, 32)), 0.f);
-                const float alpha = __builtin_amdgcn_exp2f(-delta);
-                lsum0 *= alpha;
-                lsum1 *= alpha;
-                // P^T of kblock i-1 is still waiting for its MFMA: bring it to the new reference too
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int e = 0; e < 4; ++e)
-                        pb[t][e] = sp_pack_bf16(__uint_as_float(pb[t][e] << 16) * alpha,
-                                                __uint_as_float(pb[t][e] & 0xFFFF0000u) * alpha);
-#pragma unroll
-                for (int db = 0; db < DB; ++db)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) o[db][r] *= alpha;
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    negm[r] -= delta;
-                    s[r] -= delta;
-                }
-            }
-            edge_prev = SP_IS_EDGE(i);
-        }
-
-        // ---- memory strand: loads PF kblocks ahead
-        {
-            const int v = min(i + PF, T - 1);
-            issue_loads(SP_PHYS_KB(v), st_ld);
-        }
-
-        // ---- first half: p = 2^s on the vector pipe while O^T += V^T P^T (kblock i-1) runs on the matrix pipe
-        float pr[16];
-#pragma unroll
-        for (int r = 0; r < 16; ++r) pr[r] = __builtin_amdgcn_exp2f(s[r]);
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const u32x4 bv = {pb[t][0], pb[t][1], pb[t][2], pb[t][3]};
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-                o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vfr[t][db]),
-                                                                 __builtin_bit_cast(bf16x8, bv), o[db], 0, 0, 0);
-        }
-#pragma unroll
-        for (int g = 0; g < 2 * DB; ++g) {       // one MFMA, then its share of the exponentials
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 16 / (2 * DB), 0);
-        }
-        read_v(st_v, vfr);                       // kblock i, consumed by the next iteration
-        __builtin_amdgcn_sched_group_barrier(0x100, 2 * DB, 0);
-
-        // ---- second half: S^T = K Q^T - m (kblock i+1) on the matrix pipe, bf16 packing and row sums beside it
-        s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[0], qf[0], negm, 0, 0, 0);
-#pragma unroll
-        for (int ks = 1; ks < KS; ++ks) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ks], qf[ks], s, 0, 0, 0);
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-            for (int e = 0; e < 4; ++e) pb[t][e] = sp_pack_bf16(pr[8 * t + 2 * e], pr[8 * t + 2 * e + 1]);
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            lsum0 = sp_pair_sum(pb[0][e], lsum0);
-            lsum1 = sp_pair_sum(pb[1][e], lsum1);
-        }
-#pragma unroll
-        for (int g = 0; g < KS; ++g) {           // one MFMA, then its share of the pack / sum instructions
-            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-            __builtin_amdgcn_sched_group_barrier(0x002, 16 / KS, 0);
-        }
-        read_k(st_k, kfr);                       // kblock i + 2, consumed by the next iteration
-        __builtin_amdgcn_sched_group_barrier(0x100, KS, 0);
-
-        st_ld = next_stage(st_ld);
-        st_v = next_stage(st_v);
-        st_k = next_stage(st_k);
-        sp_wait_vmcnt<(PF - 3) * LPW>();         // this wave's loads of kblocks up to i + 3 have landed
-        __builtin_amdgcn_s_barrier();
+    int next_edge = 0;                           // next kblock that may be cut by a range boundary
+    float thr = mref + SP_RESCALE_SLACK;         // a score above this moves the reference
+    for (int i = 0; i < T; i += 2) {
+        SP_STEP(i, sA, sB)
+        if (i + 1 >= T) break;
+        SP_STEP(i + 1, sB, sA)
     }
-    // ---- epilogue: O^T += V^T P^T of the last kblock
-    if (edge_prev) mask_v(vfr, SP_LIVE(T - 1));
-#pragma unroll
-    for (int t = 0; t < 2; ++t) {
-        const u32x4 bv = {pb[t][0], pb[t][1], pb[t][2], pb[t][3]};
-#pragma unroll
-        for (int db = 0; db < DB; ++db)
-            o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vfr[t][db]),
-                                                             __builtin_bit_cast(bf16x8, bv), o[db], 0, 0, 0);
-    }
+#undef SP_STEP
+#undef SP_PIN
     sp_wait_vmcnt<0>();                          // nothing may still be writing LDS when the wave ends
 
     const float lsum = lsum0 + lsum1;
@@ -344,12 +365,14 @@ __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 
 #undef SP_PHYS_KB
 #undef SP_LIVE
-#undef SP_IS_EDGE
 
+#define SP_VARIANT(D, PF, QR)                                                                         \
+    { "d" #D "_sp_pf" #PF "_qr" #QR, D, 256, 8 * 2 * KBLOCK * D * 2 + (D / 16 - QR) * 8 * 1024,         \
+      ll_attn_sp_kernel<D, PF, QR>, 512 }
 const AttnVariant kStreamVariants[] = {
-    {"d128_sp_pf4", 128, 256, 6 * 2 * KBLOCK * 128 * 2, ll_attn_sp_kernel<128, 4>, 512},
-    {"d128_sp_pf6", 128, 256, 8 * 2 * KBLOCK * 128 * 2, ll_attn_sp_kernel<128, 6>, 512},
-    {"d64_sp_pf4", 64, 256, 6 * 2 * KBLOCK * 64 * 2, ll_attn_sp_kernel<64, 4>, 512},
+    SP_VARIANT(128, 4, 8),
+    SP_VARIANT(128, 6, 8),
+    SP_VARIANT(64, 4, 4),
 };
 const int kNumStreamVariants = sizeof(kStreamVariants) / sizeof(kStreamVariants[0]);
 
