@@ -271,7 +271,8 @@ static const AttnVariant* variant(int v) {
 }
 int attn_variant_count() { return kNumSimple + kNumStreamVariants; }
 const char* attn_variant_name(int v) { return variant(v) ? variant(v)->name : nullptr; }
-int attn_variant_default(int D) { return D == 128 ? 1 : 6; }
+// the software-pipelined kernels are the default
+int attn_variant_default(int D) { return D == 128 ? kNumSimple + 1 : kNumSimple + 3; }
 int attn_variant_qtile(int v) { return variant(v)->qtile; }
 bool attn_variant_supports(int v, int D) { return variant(v) && variant(v)->D == D; }
 
