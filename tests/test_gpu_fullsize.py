@@ -1,0 +1,163 @@
+"""GPU parity at the full benchmark sizes, in the launch configuration bench.py times.
+
+The oracle cannot produce a whole 4680 x 12 x 128 output for every chunk in reasonable time, so
+most checks compare a fixed random sample of query rows (each query's softmax is independent of
+the others, so sampled rows are exact oracle values), plus one full-tensor comparison.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle.longlive_oracle import Oracle, bf16_bits_to_f64, error_metrics
+from paper_2509_22622_amd import binding as B
+from paper_2509_22622_amd import synth
+
+import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+N_SAMPLE = 64
+
+
+def _sample_rows(n_rows, seed):
+    # always include the first and last rows (first and last query tile, ragged tail)
+    rnd = np.random.default_rng(seed).choice(n_rows, size=N_SAMPLE - 4, replace=False)
+    return np.unique(np.concatenate([rnd, [0, 1, n_rows - 2, n_rows - 1]]))
+
+
+def _check_sampled(out, oracle, layer, rows, what):
+    got = bf16_bits_to_f64(H.to_bits(out[torch.from_numpy(rows).cuda()]))
+    assert np.isfinite(got).all(), what
+    max_abs, rel = error_metrics(got, oracle.attn(layer, rows=rows))
+    assert max_abs <= H.MAX_ABS_TOL and rel <= H.REL_L2_TOL, f"{what}: max_abs {max_abs:.3e} rel_l2 {rel:.3e}"
+    return max_abs, rel
+
+
+def _trim(oracle, layer, keep_from, sink):
+    """Drop frames the key-set rule can never select again (memory only; see the eviction pin)."""
+    com = oracle.layer[layer].committed
+    for f in [f for f in com if sink <= f < keep_from]:
+        del com[f]
+
+
+def test_wan_layer_streaming():
+    """Config 2: 12 heads x 128, 1560 tokens/frame, chunk 3, sink 3, window 9; warm-up, steady state, ring wrap."""
+    w = synth.WAN_LAYER
+    cache, oracle = H.make_cache(w), Oracle(H.oracle_cfg(w))
+    worst = (0.0, 0.0)
+    for i in range(7):
+        f0 = 3 * i
+        q, k, v = synth.chunk_qkv(w, 0, i)
+        qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+        qr, out = torch.empty_like(qd), torch.empty_like(qd)
+        cache.chunk_append(0, f0, 3, qd, kd, vd, qr)
+        cache.sink_window_attn(0, qr, out)
+        torch.cuda.synchronize()
+        q_want = oracle.append(0, f0, q, k, v)
+        assert cache.live_frames(0) == oracle.live_frames(0)
+        assert sum(b - a for a, b in cache.live_ranges(0)) == len(oracle.live_frames(0)) * w.tokens_per_frame
+        rows = _sample_rows(w.chunk_tokens, 100 + i)
+        H.assert_rounded(H.to_bits(qr)[rows], q_want[rows] * H.q_prescale(w), f"q' chunk {i}")
+        m = _check_sampled(out, oracle, 0, rows, f"cfg2 chunk {i}")
+        worst = (max(worst[0], m[0]), max(worst[1], m[1]))
+        H.check_frame(cache, oracle, w, 0, f0 + (i % 3))          # one frame of the new chunk
+        if i == 5:                                                 # steady state after the first wrap: every element
+            H.assert_parity(H.to_bits(out), oracle.attn(0), "cfg2 chunk 5 full tensor")
+            H.check_frame(cache, oracle, w, 0, 1)                  # a sink frame is still intact
+        _trim(oracle, 0, f0 - w.window_frames, w.sink_frames)
+    print("cfg2 worst sampled (max_abs, rel_l2):", worst)
+    cache.close()
+
+
+def test_long_window():
+    """Config 4: no sink, window 21 frames (37440 keys in steady state)."""
+    w = synth.LONG_WINDOW
+    cache, oracle = H.make_cache(w), Oracle(H.oracle_cfg(w))
+    for i in range(w.n_chunks):
+        f0 = 3 * i
+        q, k, v = synth.chunk_qkv(w, 0, i)
+        qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+        qr, out = torch.empty_like(qd), torch.empty_like(qd)
+        cache.chunk_append(0, f0, 3, qd, kd, vd, qr)
+        cache.sink_window_attn(0, qr, out)
+        torch.cuda.synchronize()
+        oracle.append(0, f0, q, k, v)
+        assert cache.live_frames(0) == oracle.live_frames(0)
+        if i in (0, 4, 7, 8):
+            _check_sampled(out, oracle, 0, _sample_rows(w.chunk_tokens, 200 + i), f"cfg4 chunk {i}")
+        _trim(oracle, 0, f0 - w.window_frames, 0)
+    assert len(oracle.live_frames(0)) == 24
+    cache.close()
+
+
+def test_recache_prefill_full_size():
+    """Config 5 (one layer): sink 3 + 12 window frames at a late position, 23400 queries, chunk-causal."""
+    w = synth.RECACHE
+    P = w.tokens_per_frame
+    cache, oracle = H.make_cache(w), Oracle(H.oracle_cfg(w))
+    layer, ws, n_win = 7, 165, 12
+    # the sink must exist on both sides only if it is not re-prefilled; here it is (include_sink = 1)
+    shape = ((3 + n_win) * P, w.heads, w.head_dim)
+    q, k, v = (synth.normal_bf16(shape, w.cfg_id, layer, 0, t) for t in "qkv")
+    qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+    out = torch.empty_like(qd)
+    cache.recache_prefill(layer, True, ws, n_win, qd, kd, vd, out)
+    torch.cuda.synchronize()
+    rows = _sample_rows(3 * P, 300)
+    want = oracle.recache_prefill(layer, True, ws, n_win, q, k, v, rows_per_chunk=rows)
+    idx = np.concatenate([c * 3 * P + rows for c in range(5)])
+    got = bf16_bits_to_f64(H.to_bits(out[torch.from_numpy(idx).cuda()]))
+    max_abs, rel = error_metrics(got, want)
+    assert max_abs <= H.MAX_ABS_TOL and rel <= H.REL_L2_TOL, f"cfg5: max_abs {max_abs:.3e} rel_l2 {rel:.3e}"
+    assert cache.live_frames(layer) == oracle.live_frames(layer) == [0, 1, 2] + list(range(ws, ws + 12))
+    for f in (0, 2, ws + 3, ws + 11):
+        H.check_frame(cache, oracle, w, layer, f)
+    # streaming goes on from the rebuilt cache
+    q, k, v = synth.chunk_qkv(w, layer, 1)
+    qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+    qr, o2 = torch.empty_like(qd), torch.empty_like(qd)
+    cache.chunk_append(layer, ws + n_win, 3, qd, kd, vd, qr)
+    cache.sink_window_attn(layer, qr, o2)
+    torch.cuda.synchronize()
+    oracle.append(layer, ws + n_win, q, k, v)
+    _check_sampled(o2, oracle, layer, _sample_rows(w.chunk_tokens, 301), "cfg5 next chunk")
+    cache.close()
+
+
+def test_thirty_layer_loop():
+    """Config 3: 30 independent layer caches, 60 consecutive chunks (the ring wraps 14 times).
+
+    Inputs are drawn on the GPU (seeded) for all layers; the oracle replays layers 0 and 29 from the
+    same bits copied back, checking sampled rows at a spread of chunks, the live sets at every chunk
+    and that the cache footprint never changes.
+    """
+    w = synth.WAN_LOOP
+    L, n_chunks = w.layers, w.n_chunks
+    checked_layers, checked_chunks = (0, 29), (0, 1, 3, 4, 5, 8, 17, 33, 59)
+    cache = H.make_cache(w)
+    nbytes = cache.buffer.numel()
+    oracles = {l: Oracle(H.oracle_cfg(synth.WAN_LAYER)) for l in checked_layers}
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.MASTER_SEED + 3)
+    shape = (w.chunk_tokens, w.heads, w.head_dim)
+    qr = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    out = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    for i in range(n_chunks):
+        f0 = 3 * i
+        for l in range(L):
+            q, k, v = (torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+                       for _ in range(3))
+            cache.chunk_append(l, f0, 3, q, k, v, qr)
+            cache.sink_window_attn(l, qr, out)
+            if l in oracles:
+                torch.cuda.synchronize()
+                o = oracles[l]
+                o.append(0, f0, H.to_bits(q), H.to_bits(k), H.to_bits(v))
+                assert cache.live_frames(l) == o.live_frames(0)
+                if i in checked_chunks:
+                    _check_sampled(out, o, 0, _sample_rows(w.chunk_tokens, 1000 * l + i), f"cfg3 layer {l} chunk {i}")
+                _trim(o, 0, f0 - w.window_frames, w.sink_frames)
+        if i >= 4:
+            assert sum(b - a for a, b in cache.live_ranges(L - 1)) == 15 * w.tokens_per_frame
+    torch.cuda.synchronize()
+    assert cache.buffer.numel() == nbytes                       # resident size independent of video length
+    cache.close()
