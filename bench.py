@@ -17,6 +17,9 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
+# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/attn_wan_layer_pmc.txt):
+# fetch 118371 KiB x 2.0 (scale from a 1 GiB device copy) + write 14118 KiB x 1.0
+ATTN_HBM_TRAFFIC_BYTES = int(118371 * 1024 * 2.0 + 14118 * 1024 * 1.0)
 
 
 def attn_flops(nq, nk, d, h):
@@ -65,6 +68,8 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="attention kernel variant (0 = default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-recache", action="store_true")
+    ap.add_argument("--probe-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (--gpus 1); the path shards by head, see DESIGN.md")
@@ -116,7 +121,12 @@ def main():
         chunk += 1
 
     n_fill = (w.sink_frames + w.window_frames) // Cf + 1      # chunks until every ring slot is live
-    for _ in range(n_fill + args.warmup):
+    for _ in range(n_fill):                                    # fill the caches: appends only, so that every
+        f0, i = chunk * Cf, chunk % pool                       # attention launch of this run has the steady shape
+        for l in range(L):
+            cache.chunk_append(l, f0, Cf, q[i, l], k[i, l], v[i, l], qr[l])
+        chunk += 1
+    for _ in range(args.warmup):
         step()
     assert sum(b - a for a, b in cache.live_ranges(0)) == nk
     torch.cuda.synchronize()
@@ -144,8 +154,10 @@ def main():
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "attn_ms_per_layer": round(attn_ms, 4), "append_ms_per_layer": round(append_ms, 4),
         "append_GBps": round(append_bytes / (append_ms * 1e-3) / 1e9, 1),
-        "roofline": {"bound": "mfma", "kernel": "ll_attn_kernel", "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS,
-                     "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": None},
+        "roofline": {"bound": "mfma", "kernel": "ll_attn_sp1_kernel<128,4>", "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS,
+                     "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": ATTN_HBM_TRAFFIC_BYTES,
+                     "flops_per_launch": fl_layer, "avg_launch_ms": round(attn_ms, 4),
+                     "algorithmic_bytes": (2 * nq + 2 * nk) * Hh * D * 2},
     }
 
     if not args.no_recache:
@@ -172,6 +184,14 @@ def main():
         r_fl = attn_flops(nq, nq, D, Hh) * pairs * L
         res["recache_prefill"] = {"ms_30_layers": round(r_ms, 3), "TFLOP/s": round(r_fl / (r_ms * 1e-3) / 1e12, 2),
                                   "workload": f"{nf} frames = {n_ch} chunks, chunk-causal, {nf * P} queries, 30 layers"}
+
+    if args.probe_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(3)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        res["probe_copy_bytes"] = int(src.numel())
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(synth.WAN_LAYER)
