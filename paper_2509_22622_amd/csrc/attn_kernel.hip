@@ -15,6 +15,8 @@
 // row sum makes the result independent of the reference chosen.
 #include "kernels.h"
 
+#include <algorithm>
+
 namespace ll {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -272,16 +274,23 @@ static const AttnVariant* variant(int v) {
 int attn_variant_count() { return kNumSimple + kNumStreamVariants; }
 const char* attn_variant_name(int v) { return variant(v) ? variant(v)->name : nullptr; }
 // the software-pipelined kernels are the default
-int attn_variant_default(int D) { return D == 128 ? kNumSimple + 1 : kNumSimple + 3; }
+int attn_variant_default(int D) { return D == 128 ? kNumSimple + 1 : kNumSimple + 2; }
 int attn_variant_qtile(int v) { return variant(v)->qtile; }
 bool attn_variant_supports(int v, int D) { return variant(v) && variant(v)->D == D; }
 
-hipError_t launch_attn(const AttnParams& p, int variant, hipStream_t s) {
-    if (!attn_variant_supports(variant, p.D)) return hipErrorInvalidValue;
+hipError_t launch_attn(const AttnParams& p_in, int variant, hipStream_t s) {
+    if (!attn_variant_supports(variant, p_in.D)) return hipErrorInvalidValue;
+    AttnParams p = p_in;
     const AttnVariant& v = *ll::variant(variant);
     const int total = p.n_tiles * p.H;
     if (total <= 0) return hipSuccess;
-    const int grid = ((total + 7) / 8) * 8;
+    for (int c = 0; c < p.n_chunks; ++c) {
+        AttnChunk& ch = p.chunk[c];
+        ch.n_kblocks = 0;
+        for (int r = 0; r < ch.n_ranges; ++r) ch.n_kblocks += (ch.re[r] + KBLOCK - 1) / KBLOCK - ch.rs[r] / KBLOCK;
+        if (ch.n_kblocks < 1) return hipErrorInvalidValue;
+    }
+    const int grid = ((total + 7) / 8) * 8;     // the kernels spread their workgroups over the 8 XCDs
     static bool attr_set[32] = {};
     if (!attr_set[variant - 1]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.kernel),

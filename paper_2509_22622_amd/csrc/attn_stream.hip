@@ -1,31 +1,36 @@
-// Software-pipelined sink+window attention kernel (same mathematics and cache layout as
+// Software-pipelined sink+window attention kernels (same mathematics and cache layout as
 // attn_kernel.hip; see there and kernels.h).
 //
-// A workgroup owns 256 queries of one head and streams the live kblocks of that head's
-// K and V through an 8-stage LDS ring filled by direct-to-LDS loads.  Each wave owns
-// QB blocks of 32 queries (QB = 1: 8 waves, two per SIMD; QB = 2: 4 waves, one per SIMD,
-// every K/V fragment read from LDS feeds two MFMAs).
+// A workgroup of 8 waves (two per SIMD) owns 256 queries of one head, 32 per wave, and
+// streams the live kblocks of that head's K and V through an 8-stage LDS ring filled by
+// direct-to-LDS loads.  The workgroups of a head start together and walk its K/V in
+// phase, so one copy of the stream in the XCD's L2 serves all of them.  (Cutting the
+// launch into equal spans of kblocks per compute unit, to use the compute units that a
+// tile count below their number leaves idle, was tried: workgroups at unrelated kblocks
+// of a head each pull their own copy from HBM and the launch becomes bandwidth-bound;
+// keeping the first kblocks of all tiles in phase and handing only the tails to the idle
+// compute units costs more in partial results and merges than it gains.)
 //
-// Measured on gfx950: a 32x32x16 bf16 MFMA holds the matrix pipe for ~32 cycles; a lone
-// wave issues a plain VALU instruction every ~5 cycles (two waves: one per ~2.5), exp2
-// every ~9, packed bf16 convert / dot / max3 every ~4.5.  Both pipes stay busy only if
-// every wave's own instruction stream mixes them finely, so a step (one kblock) is laid
-// out as slots, each opened by one MFMA, with the vector work of the previous kblock in
-// its shadow:
-//     first  QB*KS   slots: S^T = K Q^T for kblock i+1
-//     then   QB*2*DB slots: O^T += V^T P^T for kblock i
+// Measured on gfx950 (two waves per SIMD, each an in-order stream): a 32x32x16 bf16 MFMA
+// holds the matrix pipe for ~32 cycles; plain vector instructions issued behind an MFMA
+// are free up to about two per MFMA and cost ~1 cycle each of matrix time beyond that;
+// exp2 costs ~1 cycle; the packed dot-product instructions run on the matrix pipe and
+// cost ~10 cycles each, so they are not used.  A step (one kblock) is laid out as slots,
+// each opened by one MFMA, with the vector work of the previous kblock behind them:
+//     first  KS   slots: S^T = K Q^T for kblock i+1
+//     then   2*DB slots: O^T += V^T P^T for kblock i
 //     softmax numerators of kblock i as a skewed pipeline over the score pairs of a lane
-//     (subtract reference | exp2 | pack to bf16 | add to row sum, one slot apart), the
-//     running maximum of the new scores in the last slots, one LDS fragment read for
-//     later use in every slot or every other slot.
-// One workgroup barrier per step hands the ring stages over.
+//     (exp2 | pack to bf16 and add to the row sum, one slot apart), the running maximum
+//     of the new scores in the last slots, LDS fragment reads for later slots, and the
+//     direct-to-LDS loads of a kblock six steps ahead.
+// One workgroup barrier per two steps hands the ring stages over.
 //
-// VALU work is kept minimal: queries arrive pre-scaled by log2(e)/sqrt(D) (the append
-// kernel folds that factor into the rotary epilogue) so p = exp2(s - m) with no
-// multiply; row sums are taken over the bf16-rounded p (the values the second MFMA
-// consumes) with the packed dot-product instruction.  The reference m moves only when
-// a score exceeds it by more than RESCALE_SLACK (then O and the row sums are rescaled);
-// the final division by the row sum makes the result independent of the reference.
+// Vector work is kept minimal: queries arrive pre-scaled by log2(e)/sqrt(D) (the append
+// kernel folds that factor into the rotary epilogue) and the score accumulator starts at
+// minus the reference, so p = exp2(s) with no subtract or multiply; row sums add the fp32
+// p.  The reference m moves only when a score exceeds it by more than RESCALE_SLACK (then
+// O and the row sums are rescaled); the final division by the row sum makes the result
+// independent of the reference.
 #include "kernels.h"
 
 namespace ll {
@@ -38,20 +43,48 @@ typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float SP_RESCALE_SLACK = 6.0f;         // log2 units: p stays below 2^6 between rescales
+constexpr int SP_THREADS = 512;
 
 __device__ __forceinline__ unsigned sp_pack_bf16(float a, float b) {
     f32x2 v = {a, b};
     return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
 }
-// acc + lo + hi of a packed bf16 pair
-__device__ __forceinline__ float sp_pair_sum(unsigned pair, float acc) {
-    const bf16x2 one = {(__bf16)1.0f, (__bf16)1.0f};
-    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, pair), one, acc, false);
-}
 // s_waitcnt that only waits for vector-memory loads: at most N outstanding.
 template <int N>
 __device__ __forceinline__ void sp_wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+// LDS reads the compiler does not see (it would wait for every outstanding read before the first use of any
+// of them).  The read leaves `dst` pending; sp_lds_wait<N>(dst) must run before dst is used, N = reads issued
+// after it by then (the LDS returns data in order, so "at most N outstanding" means this one has arrived).
+__device__ __forceinline__ void sp_lds_read(u32x4& dst, unsigned addr, int offset) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(offset));
+}
+template <int N>
+__device__ __forceinline__ void sp_lds_wait(u32x4& x) {
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(N));
+}
+// the same for a count that is a constant only after unrolling; counts above the counter's range wait for 15
+__device__ __forceinline__ void sp_lds_wait_n(u32x4& x, int n) {
+    switch (n < 15 ? n : 15) {
+        case 0: sp_lds_wait<0>(x); break;
+        case 1: sp_lds_wait<1>(x); break;
+        case 2: sp_lds_wait<2>(x); break;
+        case 3: sp_lds_wait<3>(x); break;
+        case 4: sp_lds_wait<4>(x); break;
+        case 5: sp_lds_wait<5>(x); break;
+        case 6: sp_lds_wait<6>(x); break;
+        case 7: sp_lds_wait<7>(x); break;
+        case 8: sp_lds_wait<8>(x); break;
+        case 9: sp_lds_wait<9>(x); break;
+        case 10: sp_lds_wait<10>(x); break;
+        case 11: sp_lds_wait<11>(x); break;
+        case 12: sp_lds_wait<12>(x); break;
+        case 13: sp_lds_wait<13>(x); break;
+        case 14: sp_lds_wait<14>(x); break;
+        default: sp_lds_wait<15>(x); break;
+    }
 }
 
 // Up to three token-slot ranges are walked as one virtual list of kblocks: virtual index v lies
@@ -80,39 +113,42 @@ __device__ __forceinline__ unsigned sp_live_mask(int key0, int rs, int re, int h
     return live;
 }
 
-template <int D, int PF, int QB>
-__device__ __forceinline__ void sp_attn_body(const AttnParams& p) {
+// Softmax state of the 32 queries of a wave after some of their kblocks: lane (col, half) holds, for query
+// col, O^T rows 32*db + 8*(r/4) + 4*half + r%4 (unnormalised), the row sum over the keys this lane saw (the
+// two halves of a column add up to the query's sum) and the reference both halves share.
+template <int D>
+struct SpState {
+    f32x16 o[D / 32];
+    float l, m;
+};
+
+// Virtual kblocks [vb, ve) of chunk `ch` for the 32 queries starting at row q0 of head `head`.
+template <int D>
+__device__ __forceinline__ void sp_segment(const AttnParams& p, const AttnChunk& ch, int head, int q0, int vb, int ve,
+                                           char* lds, SpState<D>& st) {
     constexpr int KS = D / 16;                  // k-steps of S^T = K Q^T, also fragments per K kblock
     constexpr int DB = D / 32;                  // 32-row blocks of O^T
+    constexpr int NV = 2 * DB;                  // V^T fragments per kblock
     constexpr int KB_BYTES = KBLOCK * D * 2;
     constexpr int STAGE_BYTES = 2 * KB_BYTES;   // [K kblock | V kblock]
     constexpr int NS = 8;                       // ring stages (a power of two: stage = kblock & 7)
-    constexpr int NF = 2 * KS;                  // 1 KB fragments per stage
-    constexpr int NW = 8 / QB;                  // waves per workgroup
-    constexpr int LPW = NF / NW;                // loads per wave per kblock
-    constexpr int QT = 256;
+    constexpr int NF = KS + NV;                 // 1 KB fragments per stage
+    constexpr int NW = 8;                       // waves per workgroup
+    constexpr int LPW = NF / NW;                // direct-to-LDS loads per wave per kblock
+    constexpr int PF = 6;                       // kblocks the loads run ahead
+    constexpr int LAND = 4;                     // kblocks that have landed when a pair of steps starts
     static_assert(NF % NW == 0, "fragments must split over the waves");
-    static_assert(PF >= 3, "kblock i + 2 must have landed when step i starts");
-    static_assert(PF + 2 <= NS, "a stage is rewritten two barriers after its last read");
-
-    extern __shared__ __attribute__((aligned(16))) char lds[];
+    // A pair of steps (i, i+1) reads kblocks i .. i+3; the barrier before it is passed only after every wave
+    // has waited for its own loads of those kblocks.  The load issued in step j overwrites the stage of
+    // kblock j + PF - NS, last read in step j + PF - NS, which lies before the barrier that precedes step j's pair.
+    static_assert(PF >= LAND && PF + 2 <= NS, "ring too short for the prefetch distance");
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform, kept in a scalar register
     const int col = lane & 31, half = lane >> 5;
 
-    const int total = p.n_tiles * p.H;
-    const int per_xcd = (total + 7) >> 3;
-    const int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (item >= total) return;                  // uniform over the workgroup
-    const int head = item / p.n_tiles;
-    const int tile = item % p.n_tiles;
-    int ci = 0;
-    while (ci + 1 < p.n_chunks && tile >= p.chunk[ci + 1].tile_begin) ++ci;
-    const AttnChunk& ch = p.chunk[ci];
-    const int q0 = ch.q_begin + (tile - ch.tile_begin) * QT + wave * (QB * 32);
-    const int n_ranges = ch.n_ranges;
     // ranges in scalar registers (no kernel-argument loads inside the loop)
+    const int n_ranges = ch.n_ranges;
     const int rs0 = ch.rs[0], re0 = ch.re[0];
     int rs1 = ch.rs[1], re1 = ch.re[1], rs2 = ch.rs[2], re2 = ch.re[2];   // loaded unconditionally, then blanked
     if (n_ranges < 2) rs1 = re1 = 0;
@@ -126,41 +162,38 @@ __device__ __forceinline__ void sp_attn_body(const AttnParams& p) {
 #define SP_PHYS_KB(v) ((v) + sp_pick((v), n0, n01, kb0, kb1 - n0, kb2 - n01))
 #define SP_LIVE(v) sp_live_mask(SP_PHYS_KB(v) * KBLOCK, sp_pick((v), n0, n01, rs0, rs1, rs2), sp_pick((v), n0, n01, re0, re1, re2), half)
 
-    // Q^T fragments (pre-scaled by log2(e)/sqrt(D)): fragment ks of block n holds features
-    // 16*ks + 8*half + 0..7 of query q0 + 32n + col
-    bf16x8 qf[QB][KS];
-#pragma unroll
-    for (int n = 0; n < QB; ++n) {
-        const int row = min(q0 + n * 32 + col, q_end - 1);
+    // Q^T fragments (pre-scaled by log2(e)/sqrt(D)): fragment ks holds features 16*ks + 8*half + 0..7 of query q0 + col
+    bf16x8 qf[KS];
+    {
+        const int row = min(q0 + col, q_end - 1);
         const uint16_t* src = p.q + (int64_t(row) * p.H + head) * D + half * 8;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[n][ks] = *reinterpret_cast<const bf16x8*>(src + ks * 16);
+        for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(src + ks * 16);
     }
 
     const char* kbase = reinterpret_cast<const char*>(p.k_cache + head * p.head_stride);
     const char* vbase = reinterpret_cast<const char*>(p.v_cache + head * p.head_stride);
 
-    // direct-to-LDS loads of physical kblock kb into a ring stage: one 1 KB fragment per instruction
+    // direct-to-LDS load l of this wave for physical kblock kb into a ring stage: one 1 KB fragment
     const unsigned lane_off = lane * 16;
-    auto issue_loads = [&](int kb, int stage) {
+    const unsigned lds_a = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds + lane_off;   // LDS byte address
+    auto issue_load = [&](int kb, int stage, int l) {
         const int64_t kb_off = int64_t(kb) * KB_BYTES;
-#pragma unroll
-        for (int l = 0; l < LPW; ++l) {
-            const int f = wave + NW * l;        // fragment of the stage this wave fetches
-            const char* sbase = (f < KS ? kbase + f * 1024 : vbase + (f - KS) * 1024) + kb_off;   // wave-uniform
-            const char* src = sbase + lane_off;
-            char* dst = lds + stage * STAGE_BYTES + f * 1024;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),
-                                             (__attribute__((address_space(3))) void*)(dst), 16, 0, 0);
-        }
+        const int f = wave + NW * l;            // fragment of the stage this wave fetches
+        const char* sbase = (f < KS ? kbase + f * 1024 : vbase + (f - KS) * 1024) + kb_off;   // wave-uniform
+        const char* src = sbase + lane_off;
+        char* dst = lds + stage * STAGE_BYTES + f * 1024;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),
+                                         (__attribute__((address_space(3))) void*)(dst), 16, 0, 0);
     };
 
 #pragma unroll
     for (int j = 0; j < PF; ++j) {
-        const int v = min(j, T - 1);             // past the end the last kblock is fetched again, never used
-        issue_loads(SP_PHYS_KB(v), j);
+        const int v = min(vb + j, ve - 1);       // past the end the last kblock is fetched again, never used
+#pragma unroll
+        for (int l = 0; l < LPW; ++l) issue_load(SP_PHYS_KB(v), (vb + j) & (NS - 1), l);
     }
-    sp_wait_vmcnt<(PF - 3) * LPW>();            // this wave's loads of kblocks 0..2 have landed
+    sp_wait_vmcnt<(PF - LAND) * LPW>();         // this wave's loads of the first LAND kblocks have landed
     __builtin_amdgcn_s_barrier();
 
     // dead slots may hold anything, even NaN: zero the V elements of keys outside the range
@@ -187,192 +220,236 @@ __device__ __forceinline__ void sp_attn_body(const AttnParams& p) {
         return fmaxf(m, s[15]);
     };
 
-    f32x16 o[QB][DB];
-    float lsum[QB][2];                           // row sum of this lane's keys (two chains)
-    float mref[QB];                              // reference maximum of this lane's query (log2 domain)
-    f32x16 negm[QB];                             // every element = -mref: the score accumulators start from it
-    float mx[QB];                                // largest score of kblock i among this lane's keys
-    f32x16 sA[QB], sB[QB];                       // scores (log2 domain) of kblocks i and i + 1
-    bf16x8 kfr[KS];                              // K fragments of kblock i + 1
+    float lsum0, lsum1;                          // row sum of this lane's keys (two chains)
+    float mref;                                  // reference maximum of this lane's query (log2 domain)
+    f32x16 negm;                                 // every element = -mref: the score accumulators start from it
+    float mx;                                    // largest score of kblock i among this lane's keys
+    f32x16 sA, sB;                               // scores (log2 domain) of kblocks i and i + 1
+    u32x4 kfr[KS];                               // K fragments of kblock i + 1
     u32x4 vfr[2][DB];                            // V^T fragments of kblock i
 
-    // ---- prologue: scores of kblock 0, the first reference, K fragments of kblock 1
+    // ---- prologue: scores of kblock vb, the first reference, K fragments of kblock vb + 1
     {
-        const char* kt = lds + lane_off;
+        const char* kt = lds + (vb & (NS - 1)) * STAGE_BYTES + lane_off;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) kfr[ks] = *reinterpret_cast<const bf16x8*>(kt + ks * 1024);
+        for (int ks = 0; ks < KS; ++ks) kfr[ks] = *reinterpret_cast<const u32x4*>(kt + ks * 1024);
     }
 #pragma unroll
-    for (int n = 0; n < QB; ++n) {
+    for (int db = 0; db < DB; ++db)
 #pragma unroll
-        for (int db = 0; db < DB; ++db)
+        for (int r = 0; r < 16; ++r) st.o[db][r] = 0.f;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) o[n][db][r] = 0.f;
+    for (int r = 0; r < 16; ++r) sA[r] = 0.f;
 #pragma unroll
-        for (int r = 0; r < 16; ++r) sA[n][r] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) sA[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ks], qf[n][ks], sA[n], 0, 0, 0);
-        mask_s(sA[n], SP_LIVE(0));
-        const float m = max_s(sA[n]);
-        mref[n] = fmaxf(m, __shfl_xor(m, 32));  // a kblock of a range holds a live key: finite
-#pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            negm[n][r] = -mref[n];
-            sA[n][r] -= mref[n];
-        }
-        mx[n] = -INFINITY;
-        lsum[n][0] = lsum[n][1] = 0.f;
-    }
+    for (int ks = 0; ks < KS; ++ks) sA = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kfr[ks]), qf[ks], sA, 0, 0, 0);
+    mask_s(sA, SP_LIVE(vb));
     {
-        const char* kt = lds + (1 % NS) * STAGE_BYTES + lane_off;
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) kfr[ks] = *reinterpret_cast<const bf16x8*>(kt + ks * 1024);
+        const float m = max_s(sA);
+        mref = fmaxf(m, __shfl_xor(m, 32));     // a kblock of a range holds a live key: finite
     }
+#pragma unroll
+    for (int r = 0; r < 16; ++r) {
+        negm[r] = -mref;
+        sA[r] -= mref;
+    }
+    mx = -INFINITY;
+    lsum0 = lsum1 = 0.f;
+    // the loop's first slots wait for these with the same counts as for the reads of a step before (reads the
+    // compiler tracks would make it wait for everything at the loop head, in every iteration)
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) sp_lds_read(kfr[ks], lds_a + ((vb + 1) & (NS - 1)) * STAGE_BYTES, ks * 1024);
 
     // ---- main loop, one kblock per step.  S_CUR holds the scores of kblock I on entry, S_NEXT those of
     // kblock I + 1 on exit; the loop alternates the two register sets so that no copy is needed.
     // Before the slots: the rare path (a score above the reference by more than the slack, or a kblock that
     // may be cut by a range boundary: mask, move the reference, rescale O and the sums).  A scheduling fence
     // after every slot keeps the compiler from regrouping the instructions and the empty asm statements pin
-    // each stage's results inside its slot.  After the slots the wave waits for its own older loads and the
-    // workgroup barrier hands the ring stages over.
-    constexpr int QK_SLOTS = KS * QB, PV_SLOTS = 2 * DB * QB, NSLOT = QK_SLOTS + PV_SLOTS;
-    constexpr int NPAIR = 8 * QB;                // score pairs per lane, in the order the second MFMA needs them
-    constexpr int MAX_FIRST = NSLOT - 4 * QB;    // slots that take the maximum (the S^T chains have drained by then)
-    // Pair j is word j % 4 of P^T fragment (query block (j / 4) % QB, key half j / (4 * QB)): the order in which
-    // the second MFMA needs them.  The pairs are spread evenly over the slots before the last MFMA group that
-    // needs them: pair j has its exp2 in slot j * SPAN / NPAIR, is packed one slot later and summed two slots
-    // later, so every packed pair exists before the MFMA that consumes it.
-    constexpr int SPAN = QK_SLOTS + DB * QB - 2;
-    static_assert(((4 * QB - 1) * SPAN) / NPAIR + 1 <= QK_SLOTS - 1, "a packed pair would be late for its MFMA");
+    // each stage's results inside its slot.  After every second step (odd index counted from vb) the wave waits
+    // for its own older loads and the workgroup barrier hands the ring stages over.
+    constexpr int NSLOT = KS + NV;
+    constexpr int NPAIR = 8;                     // score pairs per lane, in the order the second MFMA needs them
+    constexpr int MAX_FIRST = NSLOT - 4;         // slots that take the maximum (the S^T chain has drained by then)
+    // Pair j is word j % 4 of the P^T fragment of key half j / 4.  The pairs are spread evenly over the slots
+    // before the last MFMA group that needs them: pair j has its exp2 in slot j * SPAN / NPAIR and is packed and
+    // summed one slot later, so every packed pair exists before the MFMA that consumes it.
+    constexpr int SPAN = KS + DB - 2;
+    static_assert((3 * SPAN) / NPAIR + 1 <= KS - 1, "a packed pair would be late for its MFMA");
+    // The direct-to-LDS loads of a step are spread over its slots (back-to-back they stall the wave).
+    constexpr int DMA_STEP = NSLOT / LPW, DMA_FIRST = DMA_STEP / 2;
+    // Fragment reads, in issue order: V^T fragment f of kblock I in slot f / 2 (before the second MFMA group needs
+    // it, after the group of the step before has used the register), K fragment f of kblock I + 1 in slot
+    // KS + f / 2 (after the first MFMA group has used the register).  Within a slot the reads follow the MFMA.
+    auto lds_vslot = [](int f) constexpr { return f / 2; };
+    auto lds_kslot = [](int f) constexpr { return KS + f / 2; };
+    // reads issued after V^T fragment g when slot KS + g starts: the later V^T reads and the K reads of earlier slots
+    auto lds_wait_v = [=](int g) constexpr {
+        int c = 0;
+        for (int f = 0; f < NV; ++f) c += lds_vslot(f) > lds_vslot(g) || (lds_vslot(f) == lds_vslot(g) && f > g);
+        for (int f = 0; f < KS; ++f) c += lds_kslot(f) < KS + g;
+        return c;
+    };
+    // reads issued after K fragment ks (read in the step before) when slot ks starts: the later K reads of that
+    // step and the V^T reads of this step's earlier slots
+    auto lds_wait_k = [=](int ks) constexpr {
+        int c = 0;
+        for (int f = 0; f < KS; ++f) c += lds_kslot(f) > lds_kslot(ks) || (lds_kslot(f) == lds_kslot(ks) && f > ks);
+        for (int f = 0; f < NV; ++f) c += lds_vslot(f) < ks;
+        return c;
+    };
 #define SP_PIN(x) asm volatile("" ::"v"(x))
-#define SP_STEP(I, S_CUR, S_NEXT)                                                                                  \
+#define SP_STEP(I, S_CUR, S_NEXT, EDGE, BAR)                                                                       \
     {                                                                                                               \
-        const bool edge = (I) == next_edge;                                                                         \
-        bool above = false;                                                                                         \
-        _Pragma("unroll") for (int n = 0; n < QB; ++n) above = above || mx[n] > SP_RESCALE_SLACK;                   \
-        if (edge || __any(above)) {                                                                                 \
-            if (edge) next_edge = sp_next_edge((I), n0, n01, T);                                                    \
-            _Pragma("unroll") for (int n = 0; n < QB; ++n) {                                                        \
-                if (edge) {                                                                                         \
-                    mask_s(S_CUR[n], SP_LIVE(I));                                                                   \
-                    mx[n] = max_s(S_CUR[n]);                                                                        \
-                }                                                                                                   \
-                const float delta = fmaxf(fmaxf(mx[n], __shfl_xor(mx[n], 32)), 0.f);                                \
-                const float alpha = __builtin_amdgcn_exp2f(-delta);                                                 \
-                mref[n] += delta;                                                                                   \
-                lsum[n][0] *= alpha;                                                                                \
-                lsum[n][1] *= alpha;                                                                                \
-                _Pragma("unroll") for (int db = 0; db < DB; ++db)                                                   \
-                    _Pragma("unroll") for (int r = 0; r < 16; ++r) o[n][db][r] *= alpha;                            \
-                _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                    \
-                    negm[n][r] -= delta;                                                                            \
-                    S_CUR[n][r] -= delta;                                                                           \
-                }                                                                                                   \
+        const bool edge = EDGE && (I) == next_edge;                                                                 \
+        if (__builtin_expect(edge || vote, 0)) {                                                                    \
+            if (edge) {                                                                                             \
+                next_edge = sp_next_edge((I), n0, n01, T);                                                          \
+                mask_s(S_CUR, SP_LIVE(I));                                                                          \
+                mx = max_s(S_CUR);                                                                                  \
+            }                                                                                                       \
+            const float delta = fmaxf(fmaxf(mx, __shfl_xor(mx, 32)), 0.f);                                          \
+            const float alpha = __builtin_amdgcn_exp2f(-delta);                                                     \
+            mref += delta;                                                                                          \
+            lsum0 *= alpha;                                                                                         \
+            lsum1 *= alpha;                                                                                         \
+            _Pragma("unroll") for (int db = 0; db < DB; ++db)                                                       \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;                                \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                        \
+                negm[r] -= delta;                                                                                   \
+                S_CUR[r] -= delta;                                                                                  \
             }                                                                                                       \
         }                                                                                                           \
-        const char* vt = lds + (((I)) & (NS - 1)) * STAGE_BYTES + KB_BYTES + lane_off;                              \
-        const char* kt = lds + (((I) + 2) & (NS - 1)) * STAGE_BYTES + lane_off;                                     \
+        const unsigned vt_a = lds_a + (((I)) & (NS - 1)) * STAGE_BYTES + KB_BYTES;                                  \
+        const unsigned kt_a = lds_a + (((I) + 2) & (NS - 1)) * STAGE_BYTES;                                         \
         float d0[NPAIR], d1[NPAIR];                                                                                 \
-        unsigned pb[QB][2][4];                                                                                      \
-        float m_run[QB];                                                                                            \
-        _Pragma("unroll") for (int n = 0; n < QB; ++n) m_run[n] = -INFINITY;                                        \
+        unsigned pb[2][4];                                                                                          \
+        float m_run = -INFINITY;                                                                                    \
         _Pragma("unroll") for (int k = 0; k < NSLOT; ++k) {                                                         \
-            if (k < QK_SLOTS) {                                                                                     \
-                const int ks = k / QB, n = k % QB;                                                                  \
-                S_NEXT[n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kfr[ks], qf[n][ks], ks == 0 ? negm[n] : S_NEXT[n], 0, 0, 0); \
+            if (k < KS) {                                                                                           \
+                sp_lds_wait_n(kfr[k], lds_wait_k(k));                                                               \
+                S_NEXT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kfr[k]), qf[k],         \
+                                                                  k == 0 ? negm : S_NEXT, 0, 0, 0);                 \
             } else {                                                                                                \
-                const int g = (k - QK_SLOTS) / QB, n = (k - QK_SLOTS) % QB, t = g / DB, db = g % DB;                \
-                const u32x4 bv = {pb[n][t][0], pb[n][t][1], pb[n][t][2], pb[n][t][3]};                              \
-                o[n][db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vfr[t][db]),          \
-                                                                    __builtin_bit_cast(bf16x8, bv), o[n][db], 0, 0, 0); \
+                const int g = k - KS, t = g / DB, db = g % DB;                                                      \
+                const u32x4 bv = {pb[t][0], pb[t][1], pb[t][2], pb[t][3]};                                          \
+                sp_lds_wait_n(vfr[t][db], lds_wait_v(g));                                                           \
+                st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vfr[t][db]),          \
+                                                                    __builtin_bit_cast(bf16x8, bv), st.o[db], 0, 0, 0); \
             }                                                                                                       \
-            if (k == 0) {                                                                                           \
-                const int v = min((I) + PF, T - 1);                                                                 \
-                issue_loads(SP_PHYS_KB(v), ((I) + PF) & (NS - 1));                                                  \
+            if (k >= DMA_FIRST && (k - DMA_FIRST) % DMA_STEP == 0 && (k - DMA_FIRST) / DMA_STEP < LPW) {            \
+                const int v = min((I) + PF, ve - 1);                                                                \
+                issue_load(SP_PHYS_KB(v), ((I) + PF) & (NS - 1), (k - DMA_FIRST) / DMA_STEP);                       \
             }                                                                                                       \
             _Pragma("unroll") for (int j = 0; j < NPAIR; ++j) {                                                     \
-                const int n = (j / 4) % QB, t = j / (4 * QB), w = t * 4 + j % 4, e = (j * SPAN) / NPAIR;            \
+                const int t = j / 4, e = (j * SPAN) / NPAIR;                                                        \
                 if (k == e) {                                                                                       \
-                    d0[j] = __builtin_amdgcn_exp2f(S_CUR[n][2 * w]);                                                \
-                    d1[j] = __builtin_amdgcn_exp2f(S_CUR[n][2 * w + 1]);                                            \
+                    d0[j] = __builtin_amdgcn_exp2f(S_CUR[2 * j]);                                                   \
+                    d1[j] = __builtin_amdgcn_exp2f(S_CUR[2 * j + 1]);                                               \
                     SP_PIN(d0[j]);                                                                                  \
                     SP_PIN(d1[j]);                                                                                  \
                 }                                                                                                   \
                 if (k == e + 1) {                                                                                   \
-                    pb[n][t][j % 4] = sp_pack_bf16(d0[j], d1[j]);                                                   \
-                    SP_PIN(pb[n][t][j % 4]);                                                                        \
+                    pb[t][j % 4] = sp_pack_bf16(d0[j], d1[j]);                                                      \
+                    SP_PIN(pb[t][j % 4]);                                                                           \
+                    lsum0 += d0[j];                                                                                 \
+                    lsum1 += d1[j];                                                                                 \
+                    SP_PIN(lsum0);                                                                                  \
+                    SP_PIN(lsum1);                                                                                  \
                 }                                                                                                   \
-                if (k == e + 2) lsum[n][t] = sp_pair_sum(pb[n][t][j % 4], lsum[n][t]);                              \
             }                                                                                                       \
             if (k >= MAX_FIRST) {                                                                                   \
-                const int n = (k - MAX_FIRST) / 4, r = ((k - MAX_FIRST) % 4) * 4;                                   \
-                m_run[n] = fmaxf(fmaxf(m_run[n], S_NEXT[n][r]), S_NEXT[n][r + 1]);                                  \
-                m_run[n] = fmaxf(fmaxf(m_run[n], S_NEXT[n][r + 2]), S_NEXT[n][r + 3]);                              \
+                const int r = (k - MAX_FIRST) * 4;                                                                  \
+                m_run = fmaxf(fmaxf(m_run, S_NEXT[r]), S_NEXT[r + 1]);                                              \
+                m_run = fmaxf(fmaxf(m_run, S_NEXT[r + 2]), S_NEXT[r + 3]);                                          \
             }                                                                                                       \
-            if (k < QK_SLOTS) {                                                                                     \
-                _Pragma("unroll") for (int f = 2 * k; f < 2 * k + 2; ++f)                                           \
-                    if (f < 2 * DB)                                                                                 \
-                        vfr[f / DB][f % DB] = *reinterpret_cast<const u32x4*>(vt + ((f % DB) * 2 + f / DB) * 1024); \
-            } else {                                                                                                \
-                _Pragma("unroll") for (int f = 2 * (k - QK_SLOTS); f < 2 * (k - QK_SLOTS) + 2; ++f)                 \
-                    if (f < KS) kfr[f] = *reinterpret_cast<const bf16x8*>(kt + f * 1024);                           \
-            }                                                                                                       \
+            _Pragma("unroll") for (int f = 0; f < NV; ++f)                                                          \
+                if (lds_vslot(f) == k) sp_lds_read(vfr[f / DB][f % DB], vt_a, ((f % DB) * 2 + f / DB) * 1024);      \
+            _Pragma("unroll") for (int f = 0; f < KS; ++f)                                                          \
+                if (lds_kslot(f) == k) sp_lds_read(kfr[f], kt_a, f * 1024);                                         \
             __builtin_amdgcn_sched_barrier(0);                                                                      \
-            if (k == QK_SLOTS - 1 && edge) mask_v(vfr, SP_LIVE(I));                                                 \
+            if (EDGE && k == KS - 1 && edge) {                                                                      \
+                _Pragma("unroll") for (int f = 0; f < NV; ++f) sp_lds_wait<0>(vfr[f / DB][f % DB]);                 \
+                mask_v(vfr, SP_LIVE(I));                                                                            \
+            }                                                                                                       \
         }                                                                                                           \
-        _Pragma("unroll") for (int n = 0; n < QB; ++n) mx[n] = m_run[n];                                            \
-        sp_wait_vmcnt<(PF - 3) * LPW>();                                                                            \
-        __builtin_amdgcn_s_barrier();                                                                               \
+        mx = m_run;                                                                                                 \
+        vote = __any(mx > SP_RESCALE_SLACK);     /* decided here so that the next step opens with a scalar branch */ \
+        if (BAR == 1 || (BAR == 2 && (((I) - vb) & 1))) {                                                           \
+            sp_wait_vmcnt<(PF - LAND) * LPW>();                                                                     \
+            __builtin_amdgcn_s_barrier();                                                                           \
+        }                                                                                                           \
     }
 
-    int next_edge = 0;                           // next kblock that may be cut by a range boundary
-    for (int i = 0; i < T; i += 2) {
-        SP_STEP(i, sA, sB)
-        if (i + 1 >= T) break;
-        SP_STEP(i + 1, sB, sA)
+    // Kblocks that a range boundary may cut (at most six per tile) take the general step, one at a time: it masks,
+    // ends with the barrier when its index is odd, and hands the scores back in sA.  All others run in aligned
+    // pairs through a step without any of that, so that the hot loop has one taken branch per two kblocks.
+    int next_edge = sp_next_edge(vb - 1, n0, n01, T);   // next kblock that may be cut by a range boundary
+    bool vote = false;                                   // some lane of the wave holds a score above the slack
+    int i = vb;
+    while (i < ve) {
+        while (i < ve && (((i - vb) & 1) || i + 1 >= ve || i == next_edge || i + 1 == next_edge)) {
+            SP_STEP(i, sA, sB, 1, 2)
+            sA = sB;
+            ++i;
+        }
+        for (int n = (min(ve, next_edge) - i) >> 1; n > 0; --n) {
+            SP_STEP(i, sA, sB, 0, 0)
+            SP_STEP(i + 1, sB, sA, 0, 1)
+            i += 2;
+        }
     }
 #undef SP_STEP
 #undef SP_PIN
-    sp_wait_vmcnt<0>();                          // nothing may still be writing LDS when the wave ends
-
-    // out[row][head][32*db + 8*g + 4*half + i] = O^T register 4*g + i, divided by the row sum
-#pragma unroll
-    for (int n = 0; n < QB; ++n) {
-        const float ls = lsum[n][0] + lsum[n][1];
-        const float l = ls + __shfl_xor(ls, 32);
-        const float inv = 1.0f / l;
-        const int row = q0 + n * 32 + col;
-        if (row < q_end) {
-            uint16_t* dst = p.out + (int64_t(row) * p.H + head) * D + half * 4;
-#pragma unroll
-            for (int db = 0; db < DB; ++db)
-#pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    u32x2 w = {sp_pack_bf16(o[n][db][4 * g] * inv, o[n][db][4 * g + 1] * inv),
-                               sp_pack_bf16(o[n][db][4 * g + 2] * inv, o[n][db][4 * g + 3] * inv)};
-                    *reinterpret_cast<u32x2*>(dst + db * 32 + g * 8) = w;
-                }
-        }
-    }
 #undef SP_PHYS_KB
 #undef SP_LIVE
+    __builtin_amdgcn_s_waitcnt(0);               // no load may still be writing LDS or registers past this point
+    st.l = lsum0 + lsum1;
+    st.m = mref;
 }
 
-// QB = 1: 8 waves, two per SIMD (at most 256 VGPRs each).  QB = 2: 4 waves, one per SIMD (512 VGPRs).
-template <int D, int PF>
-__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_attn_sp1_kernel(const AttnParams p) {
-    sp_attn_body<D, PF, 1>(p);
+// out[row][head][32*db + 8*g + 4*half + i] = O^T register 4*g + i, divided by the row sum
+template <int D>
+__device__ __forceinline__ void sp_store_out(const AttnParams& p, int head, int q0, int q_end, const SpState<D>& st) {
+    constexpr int DB = D / 32;
+    const int lane = threadIdx.x & 63, col = lane & 31, half = lane >> 5;
+    const float l = st.l + __shfl_xor(st.l, 32);
+    const float inv = 1.0f / l;
+    const int row = q0 + col;
+    if (row < q_end) {
+        uint16_t* dst = p.out + (int64_t(row) * p.H + head) * D + half * 4;
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                u32x2 w = {sp_pack_bf16(st.o[db][4 * g] * inv, st.o[db][4 * g + 1] * inv),
+                           sp_pack_bf16(st.o[db][4 * g + 2] * inv, st.o[db][4 * g + 3] * inv)};
+                *reinterpret_cast<u32x2*>(dst + db * 32 + g * 8) = w;
+            }
+    }
 }
-template <int D, int PF>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1))) void ll_attn_sp2_kernel(const AttnParams p) {
-    sp_attn_body<D, PF, 2>(p);
+
+// ---- one workgroup per (head, query tile)
+template <int D>
+__global__ __launch_bounds__(SP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_attn_stream_kernel(const AttnParams p) {
+    extern __shared__ __attribute__((aligned(16))) char lds[];
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int total = p.n_tiles * p.H;
+    const int per_xcd = (total + 7) >> 3;        // workgroups are dealt round-robin to the 8 XCDs: keep a head on one
+    const int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
+    if (item >= total) return;                  // uniform over the workgroup
+    const int head = item / p.n_tiles;
+    const int tile = item % p.n_tiles;
+    int ci = 0;
+    while (ci + 1 < p.n_chunks && tile >= p.chunk[ci + 1].tile_begin) ++ci;
+    const AttnChunk& ch = p.chunk[ci];
+    const int q0 = ch.q_begin + (tile - ch.tile_begin) * 256 + wave * 32;
+    SpState<D> st;
+    sp_segment<D>(p, ch, head, q0, 0, ch.n_kblocks, lds, st);
+    sp_store_out<D>(p, head, q0, ch.q_end, st);
 }
 
 const AttnVariant kStreamVariants[] = {
-    {"d128_sp1_pf4", 128, 256, 8 * 2 * KBLOCK * 128 * 2, ll_attn_sp1_kernel<128, 4>, 512},
-    {"d128_sp1_pf6", 128, 256, 8 * 2 * KBLOCK * 128 * 2, ll_attn_sp1_kernel<128, 6>, 512},
-    {"d64_sp1_pf4", 64, 256, 8 * 2 * KBLOCK * 64 * 2, ll_attn_sp1_kernel<64, 4>, 512},
+    {"d128_stream", 128, 256, 8 * 2 * KBLOCK * 128 * 2, ll_attn_stream_kernel<128>, SP_THREADS},
+    {"d64_stream", 64, 256, 8 * 2 * KBLOCK * 64 * 2, ll_attn_stream_kernel<64>, SP_THREADS},
 };
 const int kNumStreamVariants = sizeof(kStreamVariants) / sizeof(kStreamVariants[0]);
 

@@ -23,7 +23,6 @@ constexpr int PAD_KBLOCKS = 8;      // readable padding after the last kblock of
 constexpr int MAX_RANGES = 3;
 constexpr int MAX_ATTN_CHUNKS = 16; // query chunks per attention launch
 constexpr int MAX_APPEND_FRAMES = 32;
-
 __host__ __device__ inline int swap23(int i) {
     return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
 }
@@ -63,6 +62,7 @@ struct AttnChunk {
     int tile_begin;              // first query tile of this chunk in the launch
     int n_ranges;
     int rs[MAX_RANGES], re[MAX_RANGES];   // key token-slot ranges
+    int n_kblocks;               // kblocks the ranges touch        (filled in by launch_attn)
 };
 
 struct AttnParams {
