@@ -406,6 +406,54 @@ __device__ __forceinline__ void sp_segment(const AttnParams& p, const AttnChunk&
     st.m = mref;
 }
 
+// The part of sp_segment a wave without queries still owes its workgroup (the last tile of a chunk may have fewer
+// than 256 rows): its share of the direct-to-LDS loads, with the same waits and the same number of barriers, and
+// no arithmetic, which would only burn power on rows nobody reads.
+template <int D>
+__device__ __forceinline__ void sp_segment_loads_only(const AttnParams& p, const AttnChunk& ch, int head, int vb, int ve, char* lds) {
+    constexpr int KS = D / 16, NV = D / 16;
+    constexpr int KB_BYTES = KBLOCK * D * 2, STAGE_BYTES = 2 * KB_BYTES;
+    constexpr int NS = 8, NW = 8, LPW = (KS + NV) / NW, PF = 6, LAND = 4;     // as in sp_segment
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n_ranges = ch.n_ranges;
+    const int rs0 = ch.rs[0], re0 = ch.re[0];
+    int rs1 = ch.rs[1], re1 = ch.re[1], rs2 = ch.rs[2];
+    if (n_ranges < 2) rs1 = re1 = 0;
+    if (n_ranges < 3) rs2 = 0;
+    const int kb0 = rs0 / KBLOCK, ke0 = (re0 + KBLOCK - 1) / KBLOCK;
+    const int kb1 = rs1 / KBLOCK, ke1 = (re1 + KBLOCK - 1) / KBLOCK;
+    const int kb2 = rs2 / KBLOCK;
+    const int n0 = ke0 - kb0, n01 = n0 + (ke1 - kb1);
+    const char* kbase = reinterpret_cast<const char*>(p.k_cache + head * p.head_stride);
+    const char* vbase = reinterpret_cast<const char*>(p.v_cache + head * p.head_stride);
+    const unsigned lane_off = lane * 16;
+    auto issue_loads = [&](int v, int stage) {
+        const int kb = v + sp_pick(v, n0, n01, kb0, kb1 - n0, kb2 - n01);
+        const int64_t kb_off = int64_t(kb) * KB_BYTES;
+#pragma unroll
+        for (int l = 0; l < LPW; ++l) {
+            const int f = wave + NW * l;
+            const char* src = (f < KS ? kbase + f * 1024 : vbase + (f - KS) * 1024) + kb_off + lane_off;
+            char* dst = lds + stage * STAGE_BYTES + f * 1024;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),
+                                             (__attribute__((address_space(3))) void*)(dst), 16, 0, 0);
+        }
+    };
+#pragma unroll
+    for (int j = 0; j < PF; ++j) issue_loads(min(vb + j, ve - 1), (vb + j) & (NS - 1));
+    sp_wait_vmcnt<(PF - LAND) * LPW>();
+    __builtin_amdgcn_s_barrier();
+    for (int i = vb; i < ve; ++i) {
+        issue_loads(min(i + PF, ve - 1), (i + PF) & (NS - 1));
+        if ((i - vb) & 1) {                      // the barrier that ends every second step of sp_segment
+            sp_wait_vmcnt<(PF - LAND) * LPW>();
+            __builtin_amdgcn_s_barrier();
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0);
+}
+
 // out[row][head][32*db + 8*g + 4*half + i] = O^T register 4*g + i, divided by the row sum
 template <int D>
 __device__ __forceinline__ void sp_store_out(const AttnParams& p, int head, int q0, int q_end, const SpState<D>& st) {
@@ -442,6 +490,10 @@ __global__ __launch_bounds__(SP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
     while (ci + 1 < p.n_chunks && tile >= p.chunk[ci + 1].tile_begin) ++ci;
     const AttnChunk& ch = p.chunk[ci];
     const int q0 = ch.q_begin + (tile - ch.tile_begin) * 256 + wave * 32;
+    if (q0 >= ch.q_end) {                        // wave-uniform: this wave has no rows in the chunk's last tile
+        sp_segment_loads_only<D>(p, ch, head, 0, ch.n_kblocks, lds);
+        return;
+    }
     SpState<D> st;
     sp_segment<D>(p, ch, head, q0, 0, ch.n_kblocks, lds, st);
     sp_store_out<D>(p, head, q0, ch.q_end, st);

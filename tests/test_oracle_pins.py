@@ -5,6 +5,7 @@ loops, a library masked softmax, closed forms and invariants that follow from
 Sec. 3.3 (key-set rule) and Alg. 2 (stage then commit) of the paper.
 """
 import math
+import os
 
 import numpy as np
 import pytest
@@ -331,3 +332,46 @@ def test_vectorised_rope_uses_the_scalar_angles():
         ang = rope_angles(cfg, 957 + t // P, y, xx)
         assert np.allclose(r[t, 0, 0::2], np.cos(ang), atol=2e-13, rtol=0)
         assert np.allclose(r[t, 0, 1::2], np.sin(ang), atol=2e-13, rtol=0)
+
+
+# ---- P12: the window settings the paper prints (tests/golden/paper_window_settings.txt) ----
+
+def _paper_settings():
+    vals = {}
+    for line in open(os.path.join(os.path.dirname(__file__), "golden", "paper_window_settings.txt")):
+        line = line.split("#")[0].strip()
+        if line:
+            k, v = (x.strip() for x in line.split("="))
+            vals[k] = v
+    return vals
+
+
+def _kf(f0, C, S, W):
+    """Key frames of chunk [f0, f0 + C) when every earlier frame has been streamed."""
+    return key_frames(OracleConfig(1, 1, 64, 1, 1, C, S, W), f0, C, set(range(f0 + C)))
+
+
+def test_paper_effective_window():
+    """With the paper's chunk 3 / window 9 / sink 3 the oracle's steady-state key set holds exactly the "effective
+    window" of 12 past frames the paper quotes (sink + local), plus the chunk itself; the sink is the first chunk;
+    and its past-frame count equals that of the sink-less window-12 setting of the same figure."""
+    g = _paper_settings()
+    S, W, C = int(g["sink_frames"]), int(g["window_frames"]), int(g["chunk_frames"])
+    eff = int(g["effective_window_frames"])
+    assert S == C                                              # "the first chunk serves as the sink"
+    for f0 in range(S + W, S + W + 10 * C, C):                 # steady state: the window no longer touches the sink
+        frames = _kf(f0, C, S, W)
+        past = [f for f in frames if f < f0]
+        assert len(past) == eff
+        assert past[:S] == list(range(S))                      # the sink frames, never evicted
+        assert past[S:] == list(range(f0 - W, f0))             # the last W frames
+        assert [f for f in frames if f >= f0] == list(range(f0, f0 + C))
+    w_short, s_short = (int(x) for x in g["short_window"].split("/"))
+    w_sink, s_sink = (int(x) for x in g["short_window_with_sink"].split("/"))
+    assert (w_sink, s_sink) == (W, S) and s_short == 0
+    f0 = 60
+    n_with_sink = len([f for f in _kf(f0, C, s_sink, w_sink) if f < f0])
+    n_short = len([f for f in _kf(f0, C, s_short, w_short) if f < f0])
+    assert n_with_sink == n_short == eff                       # same cost, different frames
+    w_long, s_long = (int(x) for x in g["long_window"].split("/"))
+    assert len([f for f in _kf(f0, C, s_long, w_long) if f < f0]) == w_long > eff
