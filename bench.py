@@ -19,7 +19,7 @@ PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk 
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/attn_wan_layer_pmc.txt):
 # fetch 118371 KiB x 2.0 (scale from a 1 GiB device copy) + write 14118 KiB x 1.0
-ATTN_HBM_TRAFFIC_BYTES = int(118371 * 1024 * 2.0 + 14118 * 1024 * 1.0)
+ATTN_HBM_TRAFFIC_BYTES = int(172706 * 1024 * 2.0 + 14228 * 1024 * 1.0)
 
 
 def attn_flops(nq, nk, d, h):
@@ -184,6 +184,15 @@ def main():
         r_fl = attn_flops(nq, nq, D, Hh) * pairs * L
         res["recache_prefill"] = {"ms_30_layers": round(r_ms, 3), "TFLOP/s": round(r_fl / (r_ms * 1e-3) / 1e12, 2),
                                   "workload": f"{nf} frames = {n_ch} chunks, chunk-causal, {nf * P} queries, 30 layers"}
+
+    # What a pure MFMA stream sustains on this GPU right now (diagnostic kernel of the library): the chip is
+    # power-limited under a full matrix load, far below the boost clock when the operand bits toggle.
+    pr_t, pr_c = binding.probe_mfma_rate(256, 20000, True)
+    pc_t, pc_c = binding.probe_mfma_rate(256, 20000, False)
+    res["mfma_probe"] = {"random_operands": {"TFLOP/s": round(pr_t, 1), "clock_GHz": round(pr_c, 3)},
+                         "constant_operands": {"TFLOP/s": round(pc_t, 1), "clock_GHz": round(pc_c, 3)},
+                         "workload": "256 workgroups x 8 waves, 32x32x16 bf16 MFMAs back to back",
+                         "attn_kernel_vs_random_operand_probe": round(attn_tflops / pr_t, 4)}
 
     if args.probe_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(3)

@@ -135,6 +135,18 @@ ll_status ll_cache_read_frame(const ll_cache* cache, int layer, int64_t frame, v
 ll_status ll_set_attn_variant(int variant);
 const char* ll_attn_variant_name(int variant); /* NULL when `variant` does not exist */
 
+/* Diagnostic, not part of the method: the dense bf16 MFMA rate this GPU sustains when every wave issues nothing
+ * but 32x32x16 MFMAs (two waves per SIMD, `workgroups` workgroups of 8 waves, iters * 16 MFMAs per wave), and the
+ * core clock it settles at while doing so.  random_operands != 0 fills the operand registers with random bf16
+ * mantissas and signs, 0 with the constant 1.0: under a full matrix load the chip is power-limited and the clock
+ * depends on how many operand bits toggle, so the two differ by about a third.  bench.py reports the attention
+ * kernel's rate next to the random-operand figure.
+ *   dev_scratch: device, at least workgroups * 2048 + 16 bytes, contents overwritten.
+ *   The kernel runs twice on `stream` (the first run lets the clock settle, the second is timed with events);
+ *   the call returns after the stream has finished.  tflops, clock_ghz: host. */
+ll_status ll_probe_mfma_rate(void* dev_scratch, size_t scratch_bytes, int workgroups, int iters,
+                             int random_operands, double* tflops, double* clock_ghz, void* stream);
+
 const char* ll_status_string(ll_status s);
 const char* ll_last_error(void); /* thread-local, never NULL */
 

@@ -33,6 +33,7 @@ SIGNATURES = {
     "ll_cache_read_frame": (_i, [_vp, _i, _i64, _vp, _vp, _vp]),
     "ll_set_attn_variant": (_i, [_i]),
     "ll_attn_variant_name": (C.c_char_p, [_i]),
+    "ll_probe_mfma_rate": (_i, [C.c_void_p, C.c_size_t, _i, _i, _i, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
     "ll_status_string": (C.c_char_p, [_i]),
     "ll_last_error": (C.c_char_p, []),
 }
@@ -78,6 +79,16 @@ def cache_bytes(layers, heads, head_dim, tokens_per_frame, sink_frames, window_f
 
 def set_attn_variant(variant: int) -> None:
     _check(lib().ll_set_attn_variant(variant))
+
+
+def probe_mfma_rate(workgroups: int = 256, iters: int = 20000, random_operands: bool = True):
+    """(TFLOP/s, core clock in GHz) of a pure 32x32x16 bf16 MFMA stream on the current device."""
+    import torch
+    scratch = torch.empty(workgroups * 2048 + 16, dtype=torch.uint8, device="cuda")
+    tflops, ghz = C.c_double(), C.c_double()
+    _check(lib().ll_probe_mfma_rate(C.c_void_p(scratch.data_ptr()), scratch.numel(), workgroups, iters,
+                                    int(random_operands), C.byref(tflops), C.byref(ghz), _stream()))
+    return tflops.value, ghz.value
 
 
 def attn_variant_names() -> dict:

@@ -371,6 +371,37 @@ ll_status ll_set_attn_variant(int variant) {
 }
 const char* ll_attn_variant_name(int variant) { return attn_variant_name(variant); }
 
+ll_status ll_probe_mfma_rate(void* dev_scratch, size_t scratch_bytes, int workgroups, int iters, int random_operands,
+                             double* tflops, double* clock_ghz, void* stream) {
+    if (!dev_scratch || !tflops || !clock_ghz) return fail(LL_ERR_INVALID_ARG, "null pointer");
+    if (workgroups < 1 || workgroups > 4096 || iters < 1 || iters > (1 << 22))
+        return fail(LL_ERR_INVALID_ARG, "workgroups %d or iters %d out of range", workgroups, iters);
+    const size_t sink_bytes = size_t(workgroups) * 512 * sizeof(float);
+    if (scratch_bytes < sink_bytes + 16) return fail(LL_ERR_BUFFER_TOO_SMALL, "scratch has %zu bytes, %zu needed", scratch_bytes, sink_bytes + 16);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    float* sink = static_cast<float*>(dev_scratch);
+    unsigned long long* counters = reinterpret_cast<unsigned long long*>(static_cast<char*>(dev_scratch) + sink_bytes);
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipError_t e = hipEventCreate(&e0);
+    if (e == hipSuccess) e = hipEventCreate(&e1);
+    if (e == hipSuccess) e = launch_probe_mfma(sink, counters, workgroups, iters, random_operands, s);   // clocks settle
+    if (e == hipSuccess) e = hipEventRecord(e0, s);
+    if (e == hipSuccess) e = launch_probe_mfma(sink, counters, workgroups, iters, random_operands, s);
+    if (e == hipSuccess) e = hipEventRecord(e1, s);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0.f;
+    unsigned long long host[2] = {0, 0};
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e == hipSuccess) e = hipMemcpy(host, counters, sizeof host, hipMemcpyDeviceToHost);
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    if (e != hipSuccess) return hip_fail(e, "ll_probe_mfma_rate");
+    // 8 waves per workgroup, 16 MFMAs of 32x32x16 (2 * 32 * 32 * 16 flops) per iteration and wave
+    *tflops = double(workgroups) * 8 * iters * 16 * 32768.0 / (double(ms) * 1e9);
+    *clock_ghz = host[1] ? double(host[0]) / (double(host[1]) * 10.0) : 0.0;
+    return LL_OK;
+}
+
 const char* ll_status_string(ll_status s) {
     switch (s) {
         case LL_OK: return "LL_OK";

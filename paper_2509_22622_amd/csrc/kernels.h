@@ -101,5 +101,8 @@ bool attn_variant_supports(int v, int D);
 hipError_t launch_append(const AppendParams& p, hipStream_t s);
 hipError_t launch_attn(const AttnParams& p, int variant, hipStream_t s);
 hipError_t launch_read_frame(const ReadFrameParams& p, hipStream_t s);
+// diagnostic (probe_kernels.hip): sink holds workgroups * 512 floats, counters two 64-bit words
+hipError_t launch_probe_mfma(float* sink, unsigned long long* counters, int workgroups, int iters, int random_operands,
+                             hipStream_t s);
 
 }  // namespace ll
