@@ -18,7 +18,7 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/attn_wan_layer_pmc.txt):
-# fetch 118371 KiB x 2.0 (scale from a 1 GiB device copy) + write 14118 KiB x 1.0
+# fetch 172706 KiB x 2.0 (scale from a 1 GiB device copy) + write 14228 KiB x 1.0
 ATTN_HBM_TRAFFIC_BYTES = int(172706 * 1024 * 2.0 + 14228 * 1024 * 1.0)
 
 
