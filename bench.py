@@ -60,6 +60,36 @@ def cpu_baseline(w, rows=2048):
             "seconds": t_attn, "affinity_cores": len(os.sched_getaffinity(0)), "os_cpu_count": os.cpu_count()}
 
 
+def single_layer_stats(w, gen, warmup=10, iters=50):
+    """Attention launch times of one layer in steady state: median, p10, p90 over `iters` launches (HIP events)."""
+    import torch
+    from paper_2509_22622_amd import binding
+    Hh, D, Cf = w.heads, w.head_dim, w.chunk_frames
+    nq = w.chunk_tokens
+    nk = (w.sink_frames + w.window_frames + Cf) * w.tokens_per_frame
+    cache = binding.Cache(1, Hh, D, w.grid_h, w.grid_w, Cf, w.sink_frames, w.window_frames)
+    q, k, v = (torch.randn((nq, Hh, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16) for _ in range(3))
+    qr, out = torch.empty_like(q), torch.empty_like(q)
+    for c in range((w.sink_frames + w.window_frames) // Cf + 2):
+        cache.chunk_append(0, c * Cf, Cf, q, k, v, qr)
+    assert sum(b - a for a, b in cache.live_ranges(0)) == nk
+    for _ in range(warmup):
+        cache.sink_window_attn(0, qr, out)
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(iters)]
+    for a, b in ev:
+        a.record()
+        cache.sink_window_attn(0, qr, out)
+        b.record()
+    torch.cuda.synchronize()
+    ms = sorted(a.elapsed_time(b) for a, b in ev)
+    med = ms[len(ms) // 2]
+    fl = attn_flops(nq, nk, D, Hh)
+    cache.close()
+    return {"workload": f"{w.name}: {nq} queries x {nk} keys x {Hh} heads x {D}", "launches": iters,
+            "ms_median": round(med, 4), "ms_p10": round(ms[len(ms) // 10], 4), "ms_p90": round(ms[(len(ms) * 9) // 10], 4),
+            "TFLOP/s": round(fl / (med * 1e-3) / 1e12, 1), "pct_of_bf16_mfma_peak": round(100 * fl / (med * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2)}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -184,6 +214,9 @@ def main():
         r_fl = attn_flops(nq, nq, D, Hh) * pairs * L
         res["recache_prefill"] = {"ms_30_layers": round(r_ms, 3), "TFLOP/s": round(r_fl / (r_ms * 1e-3) / 1e12, 2),
                                   "workload": f"{nf} frames = {n_ch} chunks, chunk-causal, {nf * P} queries, 30 layers"}
+
+    # single-layer launches back to back (no appends in between): the Wan layer and the long window it replaces
+    res["single_layer"] = {"cfg2": single_layer_stats(synth.WAN_LAYER, gen), "cfg4": single_layer_stats(synth.LONG_WINDOW, gen)}
 
     # What a pure MFMA stream sustains on this GPU right now (diagnostic kernel of the library): the chip is
     # power-limited under a full matrix load, far below the boost clock when the operand bits toggle.
