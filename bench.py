@@ -190,6 +190,28 @@ def main():
                      "algorithmic_bytes": (2 * nq + 2 * nk) * Hh * D * 2},
     }
 
+    # The repeated denoising passes of one chunk (same frames, new contents) as one captured HIP graph: the
+    # 60 launches of a step replayed without per-launch host work.
+    f0g, ig = (chunk - 1) * Cf, (chunk - 1) % pool
+    def repass():
+        for l in range(L):
+            cache.chunk_append(l, f0g, Cf, q[ig, l], k[ig, l], v[ig, l], qr[l])
+            cache.sink_window_attn(l, qr[l], out[l])
+    repass()
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        repass()
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        graph.replay()
+    torch.cuda.synchronize()
+    g_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    res["graph_replay"] = {"ms_per_step": round(g_ms, 4), "TFLOP/s": round(fl_layer * L / (g_ms * 1e-3) / 1e12, 2),
+                           "what": "one captured graph = 30 x (append of the staged chunk again, attention); a denoising re-pass"}
+
     if not args.no_recache:
         # KV-recache prefill, config 5: sink 3 + 12 window frames at a late position, per layer, 30 layers
         wr = synth.RECACHE
