@@ -61,6 +61,30 @@ def test_small_shapes_every_element(w):
     _stream_and_check(w, w.n_chunks)
 
 
+def _random_workload(rng, idx):
+    """A random small geometry: nothing aligned on purpose (P from 17 to 130, any S, W, C, short last chunks)."""
+    D = int(rng.choice([64, 128]))
+    gh, gw = int(rng.integers(3, 11)), int(rng.integers(5, 14))
+    C = int(rng.integers(1, 5))
+    S = int(rng.integers(0, 6))
+    Wn = int(rng.integers(0, 9))
+    return synth.Workload(f"rand{idx}", 300 + idx, 1, int(rng.integers(1, 4)), D, gh, gw, C, S, Wn, int(rng.integers(4, 10)))
+
+
+@pytest.mark.parametrize("idx", range(12))
+def test_random_geometries_every_element(idx):
+    """Seeded random (grid, chunk, sink, window, heads, head_dim): streaming with a short last chunk, every output
+    element and every cached frame against the oracle, then a re-prefill of what the ring holds and two more chunks."""
+    rng = np.random.default_rng(4200 + idx)
+    w = _random_workload(rng, idx)
+    _stream_and_check(w, w.n_chunks, short_last=bool(idx % 2))
+    if w.window_frames + w.chunk_frames >= 2:
+        n_win = int(rng.integers(1, w.window_frames + w.chunk_frames + 1))
+        ws = w.sink_frames + int(rng.integers(0, 40))
+        pre = (w.sink_frames + w.chunk_frames - 1) // w.chunk_frames + 1
+        _prefill_case(w, bool(idx % 3), ws, n_win, pre_chunks=pre)
+
+
 @pytest.mark.parametrize("variant", [1, 2, 3, 4, 7])
 def test_every_d128_variant(variant):
     _stream_and_check(WIDE, 5, variant=variant, check_cache=False)
