@@ -98,6 +98,8 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="attention kernel variant (0 = default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-recache", action="store_true")
+    ap.add_argument("--full-loop", action="store_true",
+                    help="also run 60 consecutive chunks from an empty cache (30 layers), with a time per chunk")
     ap.add_argument("--probe-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
@@ -236,6 +238,25 @@ def main():
         r_fl = attn_flops(nq, nq, D, Hh) * pairs * L
         res["recache_prefill"] = {"ms_30_layers": round(r_ms, 3), "TFLOP/s": round(r_fl / (r_ms * 1e-3) / 1e12, 2),
                                   "workload": f"{nf} frames = {n_ch} chunks, chunk-causal, {nf * P} queries, 30 layers"}
+
+    if args.full_loop:
+        # config 3 as a whole: warm-up chunks included, the ring of 4 chunk slots wraps 14 times
+        for l in range(L):
+            cache.reset(l)
+        torch.cuda.synchronize()
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(61)]
+        marks[0].record()
+        for c in range(60):
+            i = c % pool
+            for l in range(L):
+                cache.chunk_append(l, c * Cf, Cf, q[i, l], k[i, l], v[i, l], qr[l])
+                cache.sink_window_attn(l, qr[l], out[l])
+            marks[c + 1].record()
+        torch.cuda.synchronize()
+        per_chunk = [marks[c].elapsed_time(marks[c + 1]) for c in range(60)]
+        steady = sorted(per_chunk[4:])
+        res["full_loop"] = {"ms_per_chunk": [round(x, 3) for x in per_chunk], "median_ms_chunks_4_to_59": round(steady[len(steady) // 2], 3),
+                            "total_ms": round(sum(per_chunk), 2)}
 
     # single-layer launches back to back (no appends in between): the Wan layer and the long window it replaces
     res["single_layer"] = {"cfg2": single_layer_stats(synth.WAN_LAYER, gen), "cfg4": single_layer_stats(synth.LONG_WINDOW, gen)}
