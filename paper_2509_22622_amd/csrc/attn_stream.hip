@@ -274,8 +274,9 @@ __device__ __forceinline__ void sp_segment(const AttnParams& p, const AttnChunk&
     // summed one slot later, so every packed pair exists before the MFMA that consumes it.
     constexpr int SPAN = KS + DB - 2;
     static_assert((3 * SPAN) / NPAIR + 1 <= KS - 1, "a packed pair would be late for its MFMA");
-    // The direct-to-LDS loads of a step are spread over its slots (back-to-back they stall the wave).
-    constexpr int DMA_STEP = NSLOT / LPW, DMA_FIRST = DMA_STEP / 2;
+    // The direct-to-LDS loads of a step are spread over its slots (back-to-back they stall the wave); the last
+    // slot of each half measured best.
+    constexpr int DMA_STEP = NSLOT / LPW, DMA_FIRST = DMA_STEP - 1;
     // Fragment reads, in issue order: V^T fragment f of kblock I in slot f / 2 (before the second MFMA group needs
     // it, after the group of the step before has used the register), K fragment f of kblock I + 1 in slot
     // KS + f / 2 (after the first MFMA group has used the register).  Within a slot the reads follow the MFMA.
@@ -324,6 +325,9 @@ __device__ __forceinline__ void sp_segment(const AttnParams& p, const AttnChunk&
         unsigned pb[2][4];                                                                                          \
         float m_run = -INFINITY;                                                                                    \
         _Pragma("unroll") for (int k = 0; k < NSLOT; ++k) {                                                         \
+            /* the wave in its chain of dependent S^T MFMAs wins the issue arbitration against its SIMD partner */  \
+            if (k == 0) __builtin_amdgcn_s_setprio(1);                                                              \
+            if (k == KS) __builtin_amdgcn_s_setprio(0);                                                             \
             if (k < KS) {                                                                                           \
                 sp_lds_wait_n(kfr[k], lds_wait_k(k));                                                               \
                 S_NEXT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kfr[k]), qf[k],         \
