@@ -32,6 +32,7 @@
 // O and the row sums are rescaled); the final division by the row sum makes the result
 // independent of the reference.
 #include "kernels.h"
+#include "lds_plan.h"
 
 namespace ll {
 
@@ -277,26 +278,9 @@ __device__ __forceinline__ void sp_segment(const AttnParams& p, const AttnChunk&
     // The direct-to-LDS loads of a step are spread over its slots (back-to-back they stall the wave); the last
     // slot of each half measured best.
     constexpr int DMA_STEP = NSLOT / LPW, DMA_FIRST = DMA_STEP - 1;
-    // Fragment reads, in issue order: V^T fragment f of kblock I in slot f / 2 (before the second MFMA group needs
-    // it, after the group of the step before has used the register), K fragment f of kblock I + 1 in slot
-    // KS + f / 2 (after the first MFMA group has used the register).  Within a slot the reads follow the MFMA.
-    auto lds_vslot = [](int f) constexpr { return f / 2; };
-    auto lds_kslot = [](int f) constexpr { return KS + f / 2; };
-    // reads issued after V^T fragment g when slot KS + g starts: the later V^T reads and the K reads of earlier slots
-    auto lds_wait_v = [=](int g) constexpr {
-        int c = 0;
-        for (int f = 0; f < NV; ++f) c += lds_vslot(f) > lds_vslot(g) || (lds_vslot(f) == lds_vslot(g) && f > g);
-        for (int f = 0; f < KS; ++f) c += lds_kslot(f) < KS + g;
-        return c;
-    };
-    // reads issued after K fragment ks (read in the step before) when slot ks starts: the later K reads of that
-    // step and the V^T reads of this step's earlier slots
-    auto lds_wait_k = [=](int ks) constexpr {
-        int c = 0;
-        for (int f = 0; f < KS; ++f) c += lds_kslot(f) > lds_kslot(ks) || (lds_kslot(f) == lds_kslot(ks) && f > ks);
-        for (int f = 0; f < NV; ++f) c += lds_vslot(f) < ks;
-        return c;
-    };
+    // Fragment reads and the waits before their use follow lds_plan.h.
+    using Plan = LdsPlan<D>;
+    static_assert(Plan::KS == KS && Plan::NV == NV, "plan and kernel disagree on the step's shape");
 #define SP_PIN(x) asm volatile("" ::"v"(x))
 #define SP_STEP(I, S_CUR, S_NEXT, EDGE, BAR)                                                                       \
     {                                                                                                               \
@@ -329,13 +313,13 @@ __device__ __forceinline__ void sp_segment(const AttnParams& p, const AttnChunk&
             if (k == 0) __builtin_amdgcn_s_setprio(1);                                                              \
             if (k == KS) __builtin_amdgcn_s_setprio(0);                                                             \
             if (k < KS) {                                                                                           \
-                sp_lds_wait_n(kfr[k], lds_wait_k(k));                                                               \
+                sp_lds_wait_n(kfr[k], Plan::wait_k(k));                                                             \
                 S_NEXT = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, kfr[k]), qf[k],         \
                                                                   k == 0 ? negm : S_NEXT, 0, 0, 0);                 \
             } else {                                                                                                \
                 const int g = k - KS, t = g / DB, db = g % DB;                                                      \
                 const u32x4 bv = {pb[t][0], pb[t][1], pb[t][2], pb[t][3]};                                          \
-                sp_lds_wait_n(vfr[t][db], lds_wait_v(g));                                                           \
+                sp_lds_wait_n(vfr[t][db], Plan::wait_v(g));                                                         \
                 st.o[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, vfr[t][db]),          \
                                                                     __builtin_bit_cast(bf16x8, bv), st.o[db], 0, 0, 0); \
             }                                                                                                       \
@@ -366,9 +350,9 @@ __device__ __forceinline__ void sp_segment(const AttnParams& p, const AttnChunk&
                 m_run = fmaxf(fmaxf(m_run, S_NEXT[r + 2]), S_NEXT[r + 3]);                                          \
             }                                                                                                       \
             _Pragma("unroll") for (int f = 0; f < NV; ++f)                                                          \
-                if (lds_vslot(f) == k) sp_lds_read(vfr[f / DB][f % DB], vt_a, ((f % DB) * 2 + f / DB) * 1024);      \
+                if (Plan::vslot(f) == k) sp_lds_read(vfr[f / DB][f % DB], vt_a, ((f % DB) * 2 + f / DB) * 1024);      \
             _Pragma("unroll") for (int f = 0; f < KS; ++f)                                                          \
-                if (lds_kslot(f) == k) sp_lds_read(kfr[f], kt_a, f * 1024);                                         \
+                if (Plan::kslot(f) == k) sp_lds_read(kfr[f], kt_a, f * 1024);                                         \
             __builtin_amdgcn_sched_barrier(0);                                                                      \
             if (EDGE && k == KS - 1 && edge) {                                                                      \
                 _Pragma("unroll") for (int f = 0; f < NV; ++f) sp_lds_wait<0>(vfr[f / DB][f % DB]);                 \

@@ -1,0 +1,39 @@
+// Issue plan of the LDS fragment reads of one kblock step of the streaming attention kernel, and the
+// s_waitcnt counts that go with it.  Plain constexpr C++ so that a host test can replay the plan.
+//
+// A step has KS + NV slots (KS = D/16 MFMAs of S^T = K Q^T for the next kblock, then NV = D/16 MFMAs of
+// O^T += V^T P^T for this one).  Each slot issues its MFMA first, then its reads, V^T reads before K reads, each
+// kind in fragment order.  The LDS returns data in issue order, so "at most N reads outstanding" means that every
+// read but the N youngest has arrived.
+#pragma once
+
+namespace ll {
+
+template <int D>
+struct LdsPlan {
+    static constexpr int KS = D / 16;    // K fragments per kblock = slots of the first MFMA group
+    static constexpr int NV = D / 16;    // V^T fragments per kblock = slots of the second MFMA group
+    // V^T fragment f of this step's kblock is read in slot f / 2: before slot KS + f needs it, after the step
+    // before has used the register (its slot KS + f).
+    static constexpr int vslot(int f) { return f / 2; }
+    // K fragment f of the next kblock is read in slot KS + f / 2: after slot f of this step has used the register.
+    static constexpr int kslot(int f) { return KS + f / 2; }
+    // Reads issued after V^T fragment g when slot KS + g starts (its MFMA consumes the fragment): the later V^T
+    // reads and the K reads of earlier slots.
+    static constexpr int wait_v(int g) {
+        int c = 0;
+        for (int f = 0; f < NV; ++f) c += vslot(f) > vslot(g) || (vslot(f) == vslot(g) && f > g);
+        for (int f = 0; f < KS; ++f) c += kslot(f) < KS + g;
+        return c;
+    }
+    // Reads issued after K fragment ks (read in the step before) when slot ks starts: the later K reads of that
+    // step and the V^T reads of this step's earlier slots.
+    static constexpr int wait_k(int ks) {
+        int c = 0;
+        for (int f = 0; f < KS; ++f) c += kslot(f) > kslot(ks) || (kslot(f) == kslot(ks) && f > ks);
+        for (int f = 0; f < NV; ++f) c += vslot(f) < ks;
+        return c;
+    }
+};
+
+}  // namespace ll
