@@ -132,12 +132,12 @@ __device__ __forceinline__ void sp_segment(const AttnParams& p, const AttnChunk&
     constexpr int NV = 2 * DB;                  // V^T fragments per kblock
     constexpr int KB_BYTES = KBLOCK * D * 2;
     constexpr int STAGE_BYTES = 2 * KB_BYTES;   // [K kblock | V kblock]
-    constexpr int NS = 8;                       // ring stages (a power of two: stage = kblock & 7)
+    constexpr int NS = RingPlan::STAGES;        // ring stages (a power of two: stage = kblock & 7)
     constexpr int NF = KS + NV;                 // 1 KB fragments per stage
     constexpr int NW = 8;                       // waves per workgroup
     constexpr int LPW = NF / NW;                // direct-to-LDS loads per wave per kblock
-    constexpr int PF = 6;                       // kblocks the loads run ahead
-    constexpr int LAND = 4;                     // kblocks that have landed when a pair of steps starts
+    constexpr int PF = RingPlan::AHEAD;         // kblocks the loads run ahead
+    constexpr int LAND = RingPlan::LANDED;      // kblocks that have landed when a pair of steps starts
     static_assert(NF % NW == 0, "fragments must split over the waves");
     // A pair of steps (i, i+1) reads kblocks i .. i+3; the barrier before it is passed only after every wave
     // has waited for its own loads of those kblocks.  The load issued in step j overwrites the stage of
@@ -361,7 +361,7 @@ __device__ __forceinline__ void sp_segment(const AttnParams& p, const AttnChunk&
         }                                                                                                           \
         mx = m_run;                                                                                                 \
         vote = __any(mx > SP_RESCALE_SLACK);     /* decided here so that the next step opens with a scalar branch */ \
-        if (BAR == 1 || (BAR == 2 && (((I) - vb) & 1))) {                                                           \
+        if (BAR == 1 || (BAR == 2 && RingPlan::barrier_after((I) - vb))) {                                                           \
             sp_wait_vmcnt<(PF - LAND) * LPW>();                                                                     \
             __builtin_amdgcn_s_barrier();                                                                           \
         }                                                                                                           \
@@ -401,7 +401,7 @@ template <int D>
 __device__ __forceinline__ void sp_segment_loads_only(const AttnParams& p, const AttnChunk& ch, int head, int vb, int ve, char* lds) {
     constexpr int KS = D / 16, NV = D / 16;
     constexpr int KB_BYTES = KBLOCK * D * 2, STAGE_BYTES = 2 * KB_BYTES;
-    constexpr int NS = 8, NW = 8, LPW = (KS + NV) / NW, PF = 6, LAND = 4;     // as in sp_segment
+    constexpr int NS = RingPlan::STAGES, NW = 8, LPW = (KS + NV) / NW, PF = RingPlan::AHEAD, LAND = RingPlan::LANDED;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_ranges = ch.n_ranges;
@@ -434,7 +434,7 @@ __device__ __forceinline__ void sp_segment_loads_only(const AttnParams& p, const
     __builtin_amdgcn_s_barrier();
     for (int i = vb; i < ve; ++i) {
         issue_loads(min(i + PF, ve - 1), (i + PF) & (NS - 1));
-        if ((i - vb) & 1) {                      // the barrier that ends every second step of sp_segment
+        if (RingPlan::barrier_after(i - vb)) {   // the barrier that ends every second step of sp_segment
             sp_wait_vmcnt<(PF - LAND) * LPW>();
             __builtin_amdgcn_s_barrier();
         }

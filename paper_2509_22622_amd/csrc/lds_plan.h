@@ -36,4 +36,17 @@ struct LdsPlan {
     }
 };
 
+// The ring of K/V stages in LDS and its hand-over between the waves of a workgroup.
+//   Kblock v lives in stage v % STAGES.  The prologue issues the loads of the first AHEAD kblocks; step i issues
+//   those of kblock i + AHEAD, and reads kblock i (V^T) and kblock i + 2 (K for the scores of the step after next;
+//   the prologue reads kblocks 0 and 1).  Every wave loads its own fragments of a stage.  Before each barrier a wave
+//   waits until all but its youngest (AHEAD - LANDED) kblocks of loads have arrived; barriers stand after the
+//   prologue's loads and after every step with an odd index.
+struct RingPlan {
+    static constexpr int STAGES = 8;   // a power of two
+    static constexpr int AHEAD = 6;    // kblocks the loads run ahead of the step that issues them
+    static constexpr int LANDED = 4;   // kblocks, counted from the next step, that have arrived at a barrier
+    static constexpr bool barrier_after(int step) { return step & 1; }
+};
+
 }  // namespace ll
