@@ -126,13 +126,14 @@ def test_recache_prefill_full_size():
 def test_thirty_layer_loop():
     """Config 3: 30 independent layer caches, 60 consecutive chunks (the ring wraps 14 times).
 
-    Inputs are drawn on the GPU (seeded) for all layers; the oracle replays layers 0 and 29 from the
-    same bits copied back, checking sampled rows at a spread of chunks, the live sets at every chunk
-    and that the cache footprint never changes.
+    Inputs are drawn on the GPU (seeded) for all layers; the oracle replays layers 0, 14 and 29 from the
+    same bits copied back and checks 64 sampled query rows (all heads) at every one of the 60 chunks, the whole
+    output tensor of layer 0 at chunks 0, 1, 3, 4, 5, 8 and 59, the live sets at every chunk, and that the cache
+    footprint never changes.
     """
     w = synth.WAN_LOOP
     L, n_chunks = w.layers, w.n_chunks
-    checked_layers, checked_chunks = (0, 29), (0, 1, 3, 4, 5, 8, 17, 33, 59)
+    checked_layers, full_chunks = (0, 14, 29), (0, 1, 3, 4, 5, 8, 59)
     cache = H.make_cache(w)
     nbytes = cache.buffer.numel()
     oracles = {l: Oracle(H.oracle_cfg(synth.WAN_LAYER)) for l in checked_layers}
@@ -153,8 +154,9 @@ def test_thirty_layer_loop():
                 o = oracles[l]
                 o.append(0, f0, H.to_bits(q), H.to_bits(k), H.to_bits(v))
                 assert cache.live_frames(l) == o.live_frames(0)
-                if i in checked_chunks:
-                    _check_sampled(out, o, 0, _sample_rows(w.chunk_tokens, 1000 * l + i), f"cfg3 layer {l} chunk {i}")
+                _check_sampled(out, o, 0, _sample_rows(w.chunk_tokens, 1000 * l + i), f"cfg3 layer {l} chunk {i}")
+                if l == 0 and i in full_chunks:
+                    H.assert_parity(H.to_bits(out), o.attn(0), f"cfg3 layer 0 chunk {i}, whole tensor")
                 _trim(o, 0, f0 - w.window_frames, w.sink_frames)
         if i >= 4:
             assert sum(b - a for a, b in cache.live_ranges(L - 1)) == 15 * w.tokens_per_frame
