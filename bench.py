@@ -18,8 +18,8 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/attn_wan_layer_pmc.txt):
-# fetch 172706 KiB x 2.0 (scale from a 1 GiB device copy) + write 14228 KiB x 1.0
-ATTN_HBM_TRAFFIC_BYTES = int(172706 * 1024 * 2.0 + 14228 * 1024 * 1.0)
+# fetch 170282 KiB x 2.0 (scale from a 1 GiB device copy) + write 14210 KiB x 1.0
+ATTN_HBM_TRAFFIC_BYTES = int(170282 * 1024 * 2.0 + 14210 * 1024 * 1.0)
 
 
 def attn_flops(nq, nk, d, h):
@@ -98,6 +98,8 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="attention kernel variant (0 = default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-recache", action="store_true")
+    ap.add_argument("--no-extras", action="store_true",
+                    help="skip the graph replay, the single-layer statistics and the MFMA probe (for profiler runs)")
     ap.add_argument("--full-loop", action="store_true",
                     help="also run 60 consecutive chunks from an empty cache (30 layers), with a time per chunk")
     ap.add_argument("--probe-copy", action="store_true",
@@ -193,6 +195,17 @@ def main():
                      "flops_per_launch": fl_layer, "avg_launch_ms": round(attn_ms, 4),
                      "algorithmic_bytes": (2 * nq + 2 * nk) * Hh * D * 2},
     }
+
+    if args.no_extras:
+        if args.probe_copy:
+            src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(3)
+            dst = torch.empty_like(src)
+            for _ in range(3):
+                dst.copy_(src)
+            torch.cuda.synchronize()
+            res["probe_copy_bytes"] = int(src.numel())
+        print(json.dumps(res))
+        return
 
     # The repeated denoising passes of one chunk (same frames, new contents) as one captured HIP graph: the
     # 60 launches of a step replayed without per-launch host work.
