@@ -26,10 +26,9 @@ def attn_flops(nq, nk, d, h):
     return 4.0 * nq * nk * d * h
 
 
-def cpu_baseline(w, rows=2048):
-    """Time the fp64 oracle as it stands on a bounded sample of the same workload: one layer in
-    steady state, all heads, `rows` of the 4680 query rows (key-set build + attention)."""
-    import numpy as np
+def cpu_baseline(w, chunks=3):
+    """Time the fp64 oracle as it stands on a bounded sample of the same workload: one layer in steady state,
+    all heads, every query row, `chunks` consecutive chunks (append + key-set build + attention each)."""
     from oracle.longlive_oracle import Oracle, OracleConfig
     from paper_2509_22622_amd import synth
     try:
@@ -38,26 +37,29 @@ def cpu_baseline(w, rows=2048):
     except Exception:
         threads = len(os.sched_getaffinity(0))
     o = Oracle(OracleConfig(1, w.heads, w.head_dim, w.grid_h, w.grid_w, w.chunk_frames, w.sink_frames, w.window_frames))
-    n_fill = (w.sink_frames + w.window_frames) // w.chunk_frames + 1
-    t_append = 0.0
+    n_fill = (w.sink_frames + w.window_frames) // w.chunk_frames
     for i in range(n_fill):
+        o.append(0, i * w.chunk_frames, *synth.chunk_qkv(w, 0, i))
+    t_append = t_attn = 0.0
+    for i in range(n_fill, n_fill + chunks):
         q, k, v = synth.chunk_qkv(w, 0, i)
         t0 = time.perf_counter()
         o.append(0, i * w.chunk_frames, q, k, v)
-        t_append = time.perf_counter() - t0
-    sel = np.random.default_rng(0).choice(w.chunk_tokens, size=rows, replace=False)
-    t0 = time.perf_counter()
-    o.attn(0, rows=np.sort(sel))
-    t_attn = time.perf_counter() - t0
-    nk = len(o.live_frames(0)) * w.tokens_per_frame
-    fl = attn_flops(rows, nk, w.head_dim, w.heads)
-    # whole-layer estimate: the append of the chunk plus attention scaled to all query rows
-    per_layer_s = t_append + t_attn * (w.chunk_tokens / rows)
-    return {"value": fl / t_attn / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
-            "sample": f"1 layer, steady state, {w.heads} heads, {rows} of {w.chunk_tokens} query rows x {nk} keys, "
+        t1 = time.perf_counter()
+        o.attn(0)
+        t_attn += time.perf_counter() - t1
+        t_append += t1 - t0
+        nk = len(o.live_frames(0)) * w.tokens_per_frame
+        com = o.layer[0].committed                       # frames the key-set rule can never select again (memory only)
+        for f in [f for f in com if w.sink_frames <= f < (i + 1) * w.chunk_frames - w.window_frames]:
+            del com[f]
+    fl = attn_flops(w.chunk_tokens, nk, w.head_dim, w.heads) * chunks
+    per_layer_s = (t_append + t_attn) / chunks
+    return {"value": fl / (t_append + t_attn) / 1e12, "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "sample": f"1 layer, {chunks} steady-state chunks, {w.heads} heads, {w.chunk_tokens} query rows x {nk} keys, "
                       f"fp64 numpy: attention {t_attn:.2f} s, append {t_append:.2f} s; "
-                      f"extrapolated {per_layer_s * 30:.0f} s per 30-layer chunk step",
-            "seconds": t_attn, "affinity_cores": len(os.sched_getaffinity(0)), "os_cpu_count": os.cpu_count()}
+                      f"x30 layers = {per_layer_s * 30:.0f} s per 30-layer chunk step (extrapolated)",
+            "seconds": t_append + t_attn, "affinity_cores": len(os.sched_getaffinity(0)), "os_cpu_count": os.cpu_count()}
 
 
 def single_layer_stats(w, gen, warmup=10, iters=50):
