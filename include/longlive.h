@@ -12,8 +12,8 @@
  *     ll_last_error() gives a thread-local message for the last failure.
  *   - "device" pointers are HIP device memory of the current device, "host"
  *     pointers are ordinary process memory.  Tensors are bfloat16, token-major
- *     [tokens, H, D], densely packed; tokens of a chunk are frame-major and
- *     row-major (y * grid_w + x) inside a frame.
+ *     [tokens, H, D], densely packed, 16-byte aligned; tokens of a chunk are frame-major
+ *     and row-major (y * grid_w + x) inside a frame.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Device
  *     work is enqueued on it and the call returns without synchronising.  Tensors
  *     are borrowed until the stream has passed the call.

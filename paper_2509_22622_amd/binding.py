@@ -13,7 +13,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "liblonglive.so")
 _lib = None
 
-LL_OK = 0
+LL_OK, LL_ERR_INVALID_ARG, LL_ERR_STATE, LL_ERR_BUFFER_TOO_SMALL, LL_ERR_UNSUPPORTED, LL_ERR_HIP = range(6)
 STATUS_NAMES = {0: "LL_OK", 1: "LL_ERR_INVALID_ARG", 2: "LL_ERR_STATE", 3: "LL_ERR_BUFFER_TOO_SMALL",
                 4: "LL_ERR_UNSUPPORTED", 5: "LL_ERR_HIP"}
 

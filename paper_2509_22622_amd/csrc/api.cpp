@@ -152,6 +152,12 @@ ll_status ll_cache_destroy(ll_cache* cache) {
     return LL_OK;
 }
 
+// the kernels move 16 bytes per lane
+static bool aligned16(const void* a, const void* b = nullptr, const void* c = nullptr, const void* d = nullptr) {
+    return ((reinterpret_cast<uintptr_t>(a) | reinterpret_cast<uintptr_t>(b) | reinterpret_cast<uintptr_t>(c) |
+             reinterpret_cast<uintptr_t>(d)) & 15) == 0;
+}
+
 #define CHECK_CACHE_LAYER(cache, layer)                                             \
     if (!(cache)) return fail(LL_ERR_INVALID_ARG, "cache is null");                 \
     if ((layer) < 0 || (layer) >= (cache)->layers)                                  \
@@ -256,6 +262,7 @@ ll_status ll_chunk_append(ll_cache* cache, int layer, int64_t frame_start, int n
     const bool any_null = !q || !k || !v || !q_out;
     if (cache->dev && any_null) return fail(LL_ERR_INVALID_ARG, "null tensor");
     if (!cache->dev && !(!q && !k && !v && !q_out)) return fail(LL_ERR_INVALID_ARG, "index-only handle takes null tensors");
+    if (!aligned16(q, k, v, q_out)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
     LayerIndex& L = cache->layer[layer];
     if (classify_append(L, frame_start) == AppendKind::Invalid)
         return fail(LL_ERR_STATE, "layer %d: frame_start %lld neither repeats (%lld) nor follows (%lld) the staged chunk",
@@ -274,6 +281,7 @@ ll_status ll_sink_window_attn(ll_cache* cache, int layer, const void* q_roped, v
     CHECK_CACHE_LAYER(cache, layer);
     if (!cache->dev) return fail(LL_ERR_INVALID_ARG, "index-only handle has no device cache");
     if (!q_roped || !out) return fail(LL_ERR_INVALID_ARG, "null tensor");
+    if (!aligned16(q_roped, out)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
     const LayerIndex& L = cache->layer[layer];
     if (L.staged_n == 0) return fail(LL_ERR_STATE, "layer %d: no staged chunk", layer);
     std::vector<ChunkWork> work(1);
@@ -295,6 +303,7 @@ ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64
     if (cache->dev && any_null) return fail(LL_ERR_INVALID_ARG, "null tensor");
     if (!cache->dev && !(!q && !k && !v && !out)) return fail(LL_ERR_INVALID_ARG, "index-only handle takes null tensors");
     if (cache->dev && (out == q || out == k || out == v)) return fail(LL_ERR_INVALID_ARG, "out must not alias q, k or v");
+    if (!aligned16(q, k, v, out)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
     LayerIndex& L = cache->layer[layer];
     if (!include_sink && L.sink_have < g.S) return fail(LL_ERR_STATE, "layer %d: sink incomplete (%lld of %d frames)", layer, (long long)L.sink_have, g.S);
 

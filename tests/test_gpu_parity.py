@@ -234,3 +234,38 @@ def test_deterministic_and_in_place():
         res.append(H.to_bits(out))
         cache.close()
     assert np.array_equal(res[0], res[1])
+
+
+def test_device_argument_errors():
+    """Errors that need a device handle: null and misaligned tensors, attention without a staged chunk, aliasing in
+    the prefill.  Nothing is enqueued by a failing call; the handle stays usable."""
+    w = MID128
+    cache = H.make_cache(w)
+    n = w.chunk_tokens * w.heads * w.head_dim
+    shape = (w.chunk_tokens, w.heads, w.head_dim)
+    base = torch.zeros(n + 8, dtype=torch.bfloat16, device="cuda")
+    good, odd = base[:n].view(shape), base[1:n + 1].view(shape)        # odd starts 2 bytes into the allocation
+    assert odd.data_ptr() % 16 == 2
+    out = torch.empty_like(good)
+    with pytest.raises(B.LongLiveError) as e:
+        cache.sink_window_attn(0, good, out)                            # nothing staged yet
+    assert e.value.status == B.LL_ERR_STATE
+    with pytest.raises(B.LongLiveError) as e:
+        cache.chunk_append(0, 0, w.chunk_frames, odd, good, good, out)
+    assert e.value.status == B.LL_ERR_INVALID_ARG and "aligned" in str(e.value)
+    assert cache.live_frames(0) == []                                   # the failed append changed nothing
+    with pytest.raises(B.LongLiveError) as e:
+        cache.chunk_append(0, 0, w.chunk_frames, good, good, None, out)
+    assert e.value.status == B.LL_ERR_INVALID_ARG
+    cache.chunk_append(0, 0, w.chunk_frames, good, good, good, out)
+    with pytest.raises(B.LongLiveError) as e:
+        cache.sink_window_attn(0, out, odd)
+    assert e.value.status == B.LL_ERR_INVALID_ARG
+    nf = w.sink_frames + 3
+    big = torch.zeros((nf * w.tokens_per_frame, w.heads, w.head_dim), dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.LongLiveError) as e:
+        cache.recache_prefill(0, True, w.sink_frames, 3, big, big, big, big)     # out aliases the inputs
+    assert e.value.status == B.LL_ERR_INVALID_ARG
+    cache.sink_window_attn(0, out, torch.empty_like(out))               # still usable
+    torch.cuda.synchronize()
+    cache.close()
