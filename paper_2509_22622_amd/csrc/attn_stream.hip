@@ -1,4 +1,4 @@
-// Software-pipelined sink+window attention kernels (same mathematics and cache layout as
+// Software-pipelined sink+window attention kernel (same mathematics and cache layout as
 // attn_kernel.hip; see there and kernels.h).
 //
 // A workgroup of 8 waves (two per SIMD) owns 256 queries of one head, 32 per wave, and
@@ -23,7 +23,12 @@
 //     (exp2 | pack to bf16 and add to the row sum, one slot apart), the running maximum
 //     of the new scores in the last slots, LDS fragment reads for later slots, and the
 //     direct-to-LDS loads of a kblock six steps ahead.
-// One workgroup barrier per two steps hands the ring stages over.
+// One workgroup barrier per two steps hands the ring stages over (lds_plan.h holds both hand-made
+// synchronisation plans; host tests replay them).
+//
+// Under this load the chip is power-limited (its clock settles near 1.9 GHz with random bf16 operands): what
+// counts is not only the matrix pipe's duty cycle but the energy spent next to it, hence no MFMAs for rows that
+// do not exist, and the diagnostic kernel in probe_kernels.hip to measure the ceiling.
 //
 // Vector work is kept minimal: queries arrive pre-scaled by log2(e)/sqrt(D) (the append
 // kernel folds that factor into the rotary epilogue) and the score accumulator starts at
