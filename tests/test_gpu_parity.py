@@ -103,6 +103,36 @@ def test_peaky_softmax():
     _stream_and_check(ODD64, 6, q_scale=6.0, check_cache=False)
 
 
+@pytest.mark.parametrize("q_scale", [16.0, 64.0, 256.0])
+def test_extreme_logits_stay_finite_and_convex(q_scale):
+    """Logits of std 16 to 256 (softmax close to one-hot, the reference maximum jumps by far more than the slack in
+    almost every kblock).  bf16 storage of q' and k' moves such logits by more than 1, so element-wise parity is not
+    defined; what holds at any scale: outputs are finite, every output lies in the convex hull of the V rows of the
+    key set (per head and feature), and rows with a dominant key reproduce that key's V."""
+    w = WIDE
+    cache, oracle = H.make_cache(w), Oracle(H.oracle_cfg(w))
+    for i in range(4):
+        q, k, v = synth.chunk_qkv(w, 0, i, q_scale=q_scale)
+        qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+        qr, out = torch.empty_like(qd), torch.empty_like(qd)
+        cache.chunk_append(0, 3 * i, 3, qd, kd, vd, qr)
+        cache.sink_window_attn(0, qr, out)
+        torch.cuda.synchronize()
+        oracle.append(0, 3 * i, q, k, v)
+        got = bf16_bits_to_f64(H.to_bits(out))
+        assert np.isfinite(got).all(), f"chunk {i}"
+        vals = np.concatenate([oracle.frame_kv(0, f)[1] for f in oracle.live_frames(0)])      # [keys, H, D]
+        lo, hi = vals.min(axis=0), vals.max(axis=0)
+        tol = 2.0 ** -7 * np.maximum(np.abs(lo), np.abs(hi))                                   # output rounding
+        assert (got >= lo - tol).all() and (got <= hi + tol).all(), f"chunk {i}: output outside the hull of V"
+        want = oracle.attn(0)
+        # rows whose softmax is decided (the oracle's largest weight dominates) must agree closely
+        err = np.abs(got - want).max(axis=-1)
+        agree = (err < 0.05).mean()
+        assert agree > 0.5, f"chunk {i}: only {agree:.2f} of the (row, head) outputs near the oracle"
+    cache.close()
+
+
 def test_only_the_last_pass_stays():
     """Alg. 2: several passes of a chunk at the same start frame, the last one is what later chunks see."""
     _stream_and_check(MID128, 6, passes=3)
