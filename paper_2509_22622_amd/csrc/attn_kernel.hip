@@ -16,6 +16,7 @@
 #include "kernels.h"
 
 #include <algorithm>
+#include <vector>
 
 namespace ll {
 
@@ -290,7 +291,45 @@ hipError_t launch_attn(const AttnParams& p_in, int variant, hipStream_t s) {
         for (int r = 0; r < ch.n_ranges; ++r) ch.n_kblocks += (ch.re[r] + KBLOCK - 1) / KBLOCK - ch.rs[r] / KBLOCK;
         if (ch.n_kblocks < 1) return hipErrorInvalidValue;
     }
-    const int grid = ((total + 7) / 8) * 8;     // the kernels spread their workgroups over the 8 XCDs
+    int grid = ((total + 7) / 8) * 8;           // the kernels spread their workgroups over the 8 XCDs
+    p.n_groups = 0;
+    const int groups = p.H * p.n_chunks;
+    if (variant > kNumSimple && p.n_chunks > 1 && groups >= 16 && groups <= MAX_XCD_GROUPS) {
+        // Tiles of different chunks differ in length, and the hardware binds workgroup b to XCD b % 8: hand each
+        // XCD whole (head, chunk) groups so that all carry the same number of kblock steps (longest group to the
+        // least loaded XCD), and let each start with its longest tiles.
+        struct Group { int id, tiles, len; };
+        std::vector<Group> all;
+        for (int h = 0; h < p.H; ++h)
+            for (int c = 0; c < p.n_chunks; ++c) {
+                const int tiles = (c + 1 < p.n_chunks ? p.chunk[c + 1].tile_begin : p.n_tiles) - p.chunk[c].tile_begin;
+                all.push_back({h * p.n_chunks + c, tiles, p.chunk[c].n_kblocks});
+            }
+        std::stable_sort(all.begin(), all.end(), [](const Group& a, const Group& b) {
+            return int64_t(a.tiles) * a.len > int64_t(b.tiles) * b.len;
+        });
+        std::vector<Group> per_xcd[8];
+        int64_t load[8] = {};
+        for (const Group& g : all) {
+            const int x = int(std::min_element(load, load + 8) - load);
+            per_xcd[x].push_back(g);
+            load[x] += int64_t(g.tiles) * g.len;
+        }
+        int n = 0, most_tiles = 0;
+        for (int x = 0; x < 8; ++x) {
+            std::stable_sort(per_xcd[x].begin(), per_xcd[x].end(), [](const Group& a, const Group& b) { return a.len > b.len; });
+            p.xcd_first[x] = uint16_t(n);
+            int tiles = 0;
+            for (const Group& g : per_xcd[x]) {
+                p.xcd_group[n++] = uint16_t(g.id);
+                tiles += g.tiles;
+            }
+            most_tiles = std::max(most_tiles, tiles);
+        }
+        p.xcd_first[8] = uint16_t(n);
+        p.n_groups = n;
+        grid = 8 * most_tiles;
+    }
     static bool attr_set[32] = {};
     if (!attr_set[variant - 1]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.kernel),

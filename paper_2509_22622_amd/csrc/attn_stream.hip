@@ -473,12 +473,30 @@ template <int D>
 __global__ __launch_bounds__(SP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_attn_stream_kernel(const AttnParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int total = p.n_tiles * p.H;
-    const int per_xcd = (total + 7) >> 3;        // workgroups are dealt round-robin to the 8 XCDs: keep a head on one
-    const int item = (blockIdx.x & 7) * per_xcd + (blockIdx.x >> 3);
-    if (item >= total) return;                  // uniform over the workgroup
-    const int head = item / p.n_tiles;
-    const int tile = item % p.n_tiles;
+    // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: the workgroups that stream the same
+    // head's K/V should share one.
+    const int xcd = blockIdx.x & 7;
+    int idx = blockIdx.x >> 3, head = -1, tile = 0;
+    if (p.n_groups == 0) {                       // one contiguous run of (head, tile) items per XCD
+        const int total = p.n_tiles * p.H;
+        const int item = xcd * ((total + 7) >> 3) + idx;
+        if (item < total) {
+            head = item / p.n_tiles;
+            tile = item % p.n_tiles;
+        }
+    } else {                                     // this XCD's list of (head, chunk) groups, longest tiles first
+        for (int g = p.xcd_first[xcd]; g < p.xcd_first[xcd + 1]; ++g) {
+            const int grp = p.xcd_group[g], c = grp % p.n_chunks;
+            const int tiles = (c + 1 < p.n_chunks ? p.chunk[c + 1].tile_begin : p.n_tiles) - p.chunk[c].tile_begin;
+            if (idx < tiles) {
+                head = grp / p.n_chunks;
+                tile = p.chunk[c].tile_begin + idx;
+                break;
+            }
+            idx -= tiles;
+        }
+    }
+    if (head < 0) return;                        // uniform over the workgroup
     int ci = 0;
     while (ci + 1 < p.n_chunks && tile >= p.chunk[ci + 1].tile_begin) ++ci;
     const AttnChunk& ch = p.chunk[ci];

@@ -23,6 +23,7 @@ constexpr int PAD_KBLOCKS = 8;      // readable padding after the last kblock of
 constexpr int MAX_RANGES = 3;
 constexpr int MAX_ATTN_CHUNKS = 16; // query chunks per attention launch
 constexpr int MAX_APPEND_FRAMES = 32;
+constexpr int MAX_XCD_GROUPS = 256; // (head, chunk) groups an attention launch can place on the XCDs one by one
 __host__ __device__ inline int swap23(int i) {
     return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
 }
@@ -72,6 +73,13 @@ struct AttnParams {
     int H, D;
     float scale_log2e;           // factor still to apply to q.k in the log2 domain (1 when q is pre-scaled)
     int n_chunks, n_tiles;       // n_tiles = query tiles over all chunks
+    // Placement on the 8 XCDs (filled in by launch_attn; workgroup b runs on XCD b % 8).  n_groups == 0: the
+    // (head, tile) items are split into 8 contiguous runs.  Otherwise (launches of several chunks, whose tiles
+    // differ in length) XCD x runs the (head, chunk) groups xcd_group[xcd_first[x] .. xcd_first[x + 1]) in that
+    // order, all tiles of a group on one XCD; group = head * n_chunks + chunk.
+    int n_groups;
+    uint16_t xcd_first[9];
+    uint16_t xcd_group[MAX_XCD_GROUPS];
     AttnChunk chunk[MAX_ATTN_CHUNKS];
 };
 
