@@ -4,6 +4,8 @@ Integers must agree exactly: live frames, the slot map, and the merged slot rang
 """
 import random
 import re
+import shutil
+import subprocess
 
 import ctypes as C
 import os
@@ -172,3 +174,16 @@ def test_library_exports_every_declared_symbol():
     for name in sorted(names):
         assert hasattr(L, name), name
     assert names == set(B.SIGNATURES)
+
+
+@pytest.mark.skipif(shutil.which("gcc") is None, reason="no host C compiler")
+def test_header_and_library_from_plain_c(tmp_path):
+    """include/longlive.h compiles as pedantic C99, links against the built library with C linkage, and the
+    index-only handle works from C (tests/c_abi_check.c)."""
+    here = os.path.dirname(os.path.abspath(__file__))
+    libdir = os.path.dirname(B.LIB_PATH)
+    exe = tmp_path / "c_abi_check"
+    subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Werror", "-o", str(exe), os.path.join(here, "c_abi_check.c"),
+                    "-L", libdir, "-l:" + os.path.basename(B.LIB_PATH), "-Wl,-rpath," + libdir], check=True)
+    run = subprocess.run([str(exe)], capture_output=True, text=True)
+    assert run.returncode == 0 and "c abi ok" in run.stdout, f"exit {run.returncode}: {run.stdout}{run.stderr}"
