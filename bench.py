@@ -276,7 +276,10 @@ def main():
                             "total_ms": round(sum(per_chunk), 2)}
 
     # single-layer launches back to back (no appends in between): the Wan layer and the long window it replaces
-    res["single_layer"] = {"cfg2": single_layer_stats(synth.WAN_LAYER, gen), "cfg4": single_layer_stats(synth.LONG_WINDOW, gen)}
+    import dataclasses
+    wan14b = dataclasses.replace(synth.WAN_LAYER, name="wan14b-shaped-layer", heads=40)      # 40 heads: three rounds of tiles
+    res["single_layer"] = {"cfg2": single_layer_stats(synth.WAN_LAYER, gen), "cfg4": single_layer_stats(synth.LONG_WINDOW, gen),
+                           "heads40": single_layer_stats(wan14b, gen, warmup=5, iters=20)}
 
     # What a pure MFMA stream sustains on this GPU right now (diagnostic kernel of the library): the chip is
     # power-limited under a full matrix load, far below the boost clock when the operand bits toggle.
