@@ -54,6 +54,7 @@ ODD128 = synth.Workload("odd128", 102, 1, 2, 128, 7, 9, 3, 2, 5, 8)       # P = 
 NOSINK = synth.Workload("nosink", 103, 1, 2, 128, 6, 11, 2, 0, 7, 9)      # no sink, W % C != 0
 ODD64 = synth.Workload("odd64", 104, 1, 3, 64, 5, 7, 3, 3, 4, 7)
 WIDE = synth.Workload("wide", 105, 1, 2, 128, 16, 20, 3, 3, 3, 5)         # P = 320: several query tiles
+HEADS6 = synth.Workload("heads6", 106, 1, 6, 64, 9, 15, 2, 2, 6, 8)       # P = 135: ragged tiles, many (head, chunk) groups
 
 
 @pytest.mark.parametrize("w", [MID128, ODD128, NOSINK, ODD64, WIDE], ids=lambda w: w.name)
@@ -212,6 +213,8 @@ def test_recache_prefill_small():
     _prefill_case(ODD128, True, 8, 7, pre_chunks=5)                     # S % C != 0, short last chunk
     _prefill_case(ODD64, True, 12, 6, pre_chunks=6)
     _prefill_case(NOSINK, True, 10, 9, pre_chunks=10)                   # no sink at all
+    _prefill_case(HEADS6, True, 20, 8, pre_chunks=4)                    # 6 heads x 5 chunks: groups placed XCD by XCD
+    _prefill_case(HEADS6, False, 31, 7, pre_chunks=6)
 
 
 def test_prefill_equals_streaming_on_the_gpu():
