@@ -100,6 +100,8 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="attention kernel variant (0 = default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-recache", action="store_true")
+    ap.add_argument("--probe-issue", action="store_true",
+                    help="only run the library's MFMA probe with each kind of companion instruction and print a table")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the graph replay, the single-layer statistics and the MFMA probe (for profiler runs)")
     ap.add_argument("--full-loop", action="store_true",
@@ -118,6 +120,22 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     binding.set_attn_variant(args.variant)
+    if args.probe_issue:
+        for random_ops in (False, True):
+            print(f"operands: {'random bf16 mantissas and signs' if random_ops else 'constant 1.0'}")
+            binding.probe_mfma_mix(0, 1, random_operands=random_ops)          # let the clock settle
+            base, base_clk = binding.probe_mfma_mix(0, 1, random_operands=random_ops)
+            print(f"  {'companion':32s} per MFMA   TFLOP/s   clock GHz   vs none   matrix cycles lost per companion")
+            print(f"  {'none':32s}    -      {base:8.1f}   {base_clk:8.3f}")
+            for kind, name in binding.PROBE_COMPANIONS.items():
+                if kind == 0:
+                    continue
+                for per in ((1,) if kind == 7 else (1, 2)):
+                    t, c = binding.probe_mfma_mix(kind, per, random_operands=random_ops)
+                    # a 32x32x16 MFMA holds the pipe 32 cycles: time per MFMA grows by 32 * (base / t - 1) cycles
+                    lost = "" if kind == 7 else f"{32.0 * (base / t - 1.0) / per:8.2f}"
+                    print(f"  {name:32s}    {per}      {t:8.1f}   {c:8.3f}   {t / base:7.3f}   {lost}")
+        return
 
     w = synth.WAN_LOOP
     L, Hh, D, P, Cf = w.layers, w.heads, w.head_dim, w.tokens_per_frame, w.chunk_frames

@@ -146,6 +146,13 @@ const char* ll_attn_variant_name(int variant); /* NULL when `variant` does not e
  *   the call returns after the stream has finished.  tflops, clock_ghz: host. */
 ll_status ll_probe_mfma_rate(void* dev_scratch, size_t scratch_bytes, int workgroups, int iters,
                              int random_operands, double* tflops, double* clock_ghz, void* stream);
+/* The same loop with company: `per_mfma` (1 or 2) instructions of kind `companion` issued behind every MFMA, on
+ * registers no MFMA touches: 0 none, 1 v_add_f32, 2 v_exp_f32, 3 v_cvt_pk_bf16_f32, 4 v_dot2c_f32_bf16,
+ * 5 v_max3_f32, 6 ds_read_b128 (64 KB of LDS, conflict-free), 7 no companion but 16x16x32 MFMAs (twice as many,
+ * the same flops).  The drop against companion 0 is what that instruction costs the matrix pipe in issue slots and,
+ * with random operands, in power.  tflops counts the MFMA flops only.  Other arguments as above. */
+ll_status ll_probe_mfma_mix(void* dev_scratch, size_t scratch_bytes, int workgroups, int iters, int random_operands,
+                            int companion, int per_mfma, double* tflops, double* clock_ghz, void* stream);
 
 const char* ll_status_string(ll_status s);
 const char* ll_last_error(void); /* thread-local, never NULL */

@@ -34,6 +34,7 @@ SIGNATURES = {
     "ll_set_attn_variant": (_i, [_i]),
     "ll_attn_variant_name": (C.c_char_p, [_i]),
     "ll_probe_mfma_rate": (_i, [C.c_void_p, C.c_size_t, _i, _i, _i, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
+    "ll_probe_mfma_mix": (_i, [C.c_void_p, C.c_size_t, _i, _i, _i, _i, _i, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
     "ll_status_string": (C.c_char_p, [_i]),
     "ll_last_error": (C.c_char_p, []),
 }
@@ -88,6 +89,20 @@ def probe_mfma_rate(workgroups: int = 256, iters: int = 20000, random_operands: 
     tflops, ghz = C.c_double(), C.c_double()
     _check(lib().ll_probe_mfma_rate(C.c_void_p(scratch.data_ptr()), scratch.numel(), workgroups, iters,
                                     int(random_operands), C.byref(tflops), C.byref(ghz), _stream()))
+    return tflops.value, ghz.value
+
+
+PROBE_COMPANIONS = {0: "none", 1: "v_add_f32", 2: "v_exp_f32", 3: "v_cvt_pk_bf16_f32", 4: "v_dot2c_f32_bf16",
+                    5: "v_max3_f32", 6: "ds_read_b128", 7: "16x16x32 MFMAs, no companion"}
+
+
+def probe_mfma_mix(companion: int, per_mfma: int = 1, workgroups: int = 256, iters: int = 20000, random_operands: bool = True):
+    """(MFMA TFLOP/s, core clock in GHz) with `per_mfma` companion instructions behind every MFMA (see the header)."""
+    import torch
+    scratch = torch.empty(workgroups * 2048 + 16, dtype=torch.uint8, device="cuda")
+    tflops, ghz = C.c_double(), C.c_double()
+    _check(lib().ll_probe_mfma_mix(C.c_void_p(scratch.data_ptr()), scratch.numel(), workgroups, iters, int(random_operands),
+                                   companion, per_mfma, C.byref(tflops), C.byref(ghz), _stream()))
     return tflops.value, ghz.value
 
 

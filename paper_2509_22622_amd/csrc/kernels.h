@@ -109,8 +109,13 @@ bool attn_variant_supports(int v, int D);
 hipError_t launch_append(const AppendParams& p, hipStream_t s);
 hipError_t launch_attn(const AttnParams& p, int variant, hipStream_t s);
 hipError_t launch_read_frame(const ReadFrameParams& p, hipStream_t s);
-// diagnostic (probe_kernels.hip): sink holds workgroups * 512 floats, counters two 64-bit words
+// diagnostic (probe_kernels.hip): sink holds workgroups * 512 floats, counters two 64-bit words; `companion` is the
+// kind of instruction issued `per_mfma` (1 or 2) times behind every MFMA
+enum ProbeCompanion {
+    PROBE_NONE = 0, PROBE_ADD = 1, PROBE_EXP = 2, PROBE_CVT_BF16 = 3, PROBE_DOT2_BF16 = 4, PROBE_MAX3 = 5,
+    PROBE_LDS_READ = 6, PROBE_SHAPE_16X16X32 = 7   // 7: no companion, 16x16x32 MFMAs instead of 32x32x16
+};
 hipError_t launch_probe_mfma(float* sink, unsigned long long* counters, int workgroups, int iters, int random_operands,
-                             hipStream_t s);
+                             int companion, int per_mfma, hipStream_t s);
 
 }  // namespace ll
