@@ -18,8 +18,8 @@ if ROOT not in sys.path:
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/attn_wan_layer_pmc.txt):
-# fetch 170282 KiB x 2.0 (scale from a 1 GiB device copy) + write 14210 KiB x 1.0
-ATTN_HBM_TRAFFIC_BYTES = int(170282 * 1024 * 2.0 + 14210 * 1024 * 1.0)
+# fetch 100814 KiB x 2.0 (scale from a 1 GiB device copy) + write 14170 KiB x 1.0
+ATTN_HBM_TRAFFIC_BYTES = int(100814 * 1024 * 2.0 + 14170 * 1024 * 1.0)
 
 
 def attn_flops(nq, nk, d, h):

@@ -478,9 +478,12 @@ __global__ __launch_bounds__(SP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
     const int xcd = blockIdx.x & 7;
     int idx = blockIdx.x >> 3, head = -1, tile = 0;
     if (p.n_groups == 0) {                       // one contiguous run of (head, tile) items per XCD
+        // Runs of equal length (to within one item): XCD x takes items [ceil(x total / 8), ceil((x + 1) total / 8)).
+        // With 12 heads of 19 tiles the cuts fall on a head boundary every second XCD, and the 12 heads make 16
+        // (head, XCD) pairs, each streaming the head's K/V from memory once.
         const int total = p.n_tiles * p.H;
-        const int item = xcd * ((total + 7) >> 3) + idx;
-        if (item < total) {
+        const int item = ((xcd * total + 7) >> 3) + idx;
+        if (item < (((xcd + 1) * total + 7) >> 3)) {
             head = item / p.n_tiles;
             tile = item % p.n_tiles;
         }
@@ -500,7 +503,12 @@ __global__ __launch_bounds__(SP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
     int ci = 0;
     while (ci + 1 < p.n_chunks && tile >= p.chunk[ci + 1].tile_begin) ++ci;
     const AttnChunk& ch = p.chunk[ci];
-    const int q0 = ch.q_begin + (tile - ch.tile_begin) * 256 + wave * 32;
+    // Waves w and w + 4 share a SIMD and take neighbouring 32-row blocks: in a chunk's short last tile the blocks
+    // that do hold rows then pair up on SIMDs, and the workgroup advances at the pace of a full tile.  (One block
+    // per SIMD would let it run some hundred kblocks ahead of the head's other workgroups, past what L2 keeps, and
+    // the K/V it streamed would be fetched from memory a second time.)
+    const int row_block = ((wave & 3) << 1) | (wave >> 2);
+    const int q0 = ch.q_begin + (tile - ch.tile_begin) * 256 + row_block * 32;
     if (q0 >= ch.q_end) {                        // wave-uniform: this wave has no rows in the chunk's last tile
         sp_segment_loads_only<D>(p, ch, head, 0, ch.n_kblocks, lds);
         return;
