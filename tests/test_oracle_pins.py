@@ -375,3 +375,131 @@ def test_paper_effective_window():
     assert n_with_sink == n_short == eff                       # same cost, different frames
     w_long, s_long = (int(x) for x in g["long_window"].split("/"))
     assert len([f for f in _kf(f0, C, s_long, w_long) if f < f0]) == w_long > eff
+
+
+# ---- 8-bit cache variant (oracle/fp8_cache.py) ---------------------------------------------------------------
+from oracle import fp8_cache  # noqa: E402
+
+
+# ---- P13: the code table is the library's E4M3 type -----------------------------------------------------------
+def test_e4m3_table_matches_library_type():
+    lib = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    tab = fp8_cache.e4m3_table()
+    assert np.isnan(tab[[0x7F, 0xFF]]).all() and np.isnan(lib[[0x7F, 0xFF]]).all()
+    keep = ~np.isnan(tab)
+    assert keep.sum() == 254 and (tab[keep] == lib[keep]).all()
+    # facts of the format (OCP 8-bit floating point, E4M3): largest 448, smallest subnormal 2^-9, 1.0 = 0x38
+    golden = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "e4m3_format_facts.txt")) as fh:
+        for line in fh:
+            if line.strip() and not line.startswith("#"):
+                code, val = line.split()[:2]
+                golden[int(code, 16)] = float(val)
+    assert len(golden) >= 8
+    for code, val in golden.items():
+        assert tab[code] == val
+
+
+# ---- P14: rounding against the library's conversion -----------------------------------------------------------
+def test_e4m3_rounding_matches_library_conversion():
+    g = np.random.default_rng(5)
+    pos = fp8_cache.e4m3_table()[:0x7F]
+    mids = (pos[1:] + pos[:-1]) / 2                                   # every tie between neighbours
+    x = np.concatenate([g.standard_normal(20000) * 3.0, g.uniform(-448, 448, 20000), g.uniform(-0.03, 0.03, 20000),
+                        mids, -mids, pos, -pos, np.nextafter(mids, 0), np.nextafter(mids, 1e9),
+                        [0.0, -0.0, 448.0, -448.0]]).astype(np.float32)   # float32: what the library converts from
+    x = x[np.abs(x) <= 448.0]
+    lib = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = fp8_cache.e4m3_encode(x.astype(np.float64))
+    zero = (x == 0)
+    assert (got[~zero] == lib[~zero]).all()
+    assert ((got[zero] & 0x7F) == 0).all() and ((lib[zero] & 0x7F) == 0).all()
+    # beyond the largest value: clamp (the library's conversion does not; this is the stated reading)
+    assert (fp8_cache.e4m3_round(np.array([449.0, 500.0, 1e9, -1e9])) == np.array([448.0, 448.0, 448.0, -448.0])).all()
+
+
+# ---- P15: closed forms of the format ---------------------------------------------------------------------------
+def test_e4m3_rounding_closed_forms():
+    tab = fp8_cache.e4m3_table()
+    fin = tab[~np.isnan(tab)]
+    assert (fp8_cache.e4m3_round(fin) == fin).all()                    # representable values stay
+    g = np.random.default_rng(6)
+    x = np.concatenate([g.standard_normal(50000) * 5, g.uniform(-448, 448, 50000), g.uniform(-2 ** -6, 2 ** -6, 5000)])
+    r = fp8_cache.e4m3_round(x)
+    normal = np.abs(x) >= 2.0 ** -6
+    assert (np.abs(r - x)[normal] <= np.abs(x)[normal] * 2.0 ** -4).all()        # half a unit in the 3-bit mantissa
+    assert (np.abs(r - x)[~normal] <= 2.0 ** -10).all()                           # half the subnormal step 2^-9
+    order = np.argsort(x)
+    assert (np.diff(r[order]) >= 0).all()                                          # monotone
+    assert (fp8_cache.e4m3_round(-x) == -r).all()                                  # odd
+    assert (fp8_cache.e4m3_round(r) == r).all()                                    # idempotent
+    # brute force: nearest by exhaustive search, ties to the even code
+    small = np.concatenate([x[:300], (fin[:-1] + fin[1:])[:250] / 2])
+    codes = np.arange(256)[~np.isnan(tab)]
+    for v in small:
+        d = np.abs(tab[codes] - v)
+        best = codes[d == d.min()]
+        best = best[tab[best] == tab[best][0]] if len({abs(t) for t in tab[best]}) == 1 else best
+        want = {tab[b] for b in best if b % 2 == 0} or {tab[b] for b in best}
+        assert fp8_cache.e4m3_round(np.array([v]))[0] in want
+
+
+# ---- P16: on inputs the format holds exactly, the 8-bit oracle is the plain one ------------------------------
+def test_fp8_oracle_equals_plain_oracle_on_exact_inputs():
+    # one token per frame at row 0, column 0 and frame axis pairs fed zeros: the rotation leaves the other
+    # pairs alone at y = x = 0; k, v are small multiples of 1/8 (exact in E4M3); the query is quantised in
+    # both by hand
+    cfg = OracleConfig(1, 2, 12, 1, 1, 1, 1, 2)
+    n_t = rope_pair_split(cfg.head_dim)[0]
+    g = np.random.default_rng(9)
+    c = math.log2(math.e) / math.sqrt(cfg.head_dim)
+    plain, q8o = Oracle(cfg), fp8_cache.Fp8Oracle(cfg)
+    for f in range(6):
+        k = g.integers(-16, 17, (1, 2, 12)) / 8.0
+        v = g.integers(-16, 17, (1, 2, 12)) / 8.0
+        q = g.standard_normal((1, 2, 12))
+        k[..., :2 * n_t] = 0.0
+        q[..., :2 * n_t] = 0.0
+        bits = [synth.f32_to_bf16_bits(t.astype(np.float32)) for t in (q, k, v)]
+        plain.append(0, f, *bits)
+        q_rot = q8o.append(0, f, *bits)
+        qd = bf16_bits_to_f64(bits[0])
+        assert (q_rot == fp8_cache.e4m3_round(qd * c)).all()           # no rotation at the origin
+        K, V = plain.gather_keys(0)
+        K8, V8 = q8o.gather_keys(0)
+        assert (K == K8).all() and (V == V8).all()                     # exact inputs are stored as they are
+        # plain attention with the hand-quantised query (undo c and 1/sqrt(D): scores must agree)
+        want = attention(q_rot / c, K, V)
+        assert np.abs(q8o.attn(0) - want).max() < 1e-12
+
+
+# ---- P17: exponents are exact rescalings; quantised attention stays within the format's error of the exact one
+def test_fp8_oracle_exponents_and_error_bound():
+    cfg = OracleConfig(1, 2, 64, 2, 3, 2, 1, 3)
+    chunks = _stream(cfg, 5, 900)
+    exact, a, b = Oracle(cfg), fp8_cache.Fp8Oracle(cfg), fp8_cache.Fp8Oracle(cfg, k_exp=2, v_exp=-3)
+    for i, (q, k, v) in enumerate(chunks):
+        for o in (exact, a, b):
+            o.append(0, 2 * i, q, k, v)
+        want, got_a, got_b = exact.attn(0), a.attn(0), b.attn(0)
+        rel = np.linalg.norm(got_a - want) / np.linalg.norm(want)
+        assert 1e-4 < rel < 0.08                                       # rounding is there, and small
+        # power-of-two exponents move no mantissa while nothing leaves the normal range
+        K8a, V8a = a.gather_keys(0)
+        K8b, V8b = b.gather_keys(0)
+        big = np.abs(K8a) >= 2.0 ** -3
+        assert (K8a[big] == K8b[big] * 4.0).all()
+        bigv = (np.abs(V8a) > 2.0 ** -6) & (np.abs(V8a) <= 32.0)      # 2^-6 itself may have been rounded up to
+        assert (V8a[bigv] == V8b[bigv] / 8.0).all()
+        assert np.linalg.norm(got_b - want) / np.linalg.norm(want) < 0.08
+    # streaming == prefill holds for the 8-bit oracle too (same machinery, different storage)
+    P = cfg.tokens_per_frame
+    pre = fp8_cache.Fp8Oracle(cfg)
+    frames = [0] + list(range(5, 10))
+    q_all = np.concatenate([chunks[f // 2][0][(f % 2) * P:(f % 2 + 1) * P] for f in frames])
+    k_all = np.concatenate([chunks[f // 2][1][(f % 2) * P:(f % 2 + 1) * P] for f in frames])
+    v_all = np.concatenate([chunks[f // 2][2][(f % 2) * P:(f % 2 + 1) * P] for f in frames])
+    out = pre.recache_prefill(0, True, 5, 5, q_all, k_all, v_all)
+    assert out.shape == (6 * P, 2, 64) and np.isfinite(out).all()
+    K8, _ = pre.gather_keys(0)
+    assert (fp8_cache.e4m3_round(K8) == K8).all()
