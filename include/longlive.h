@@ -67,6 +67,32 @@ ll_status ll_cache_create(int layers, int heads, int head_dim, int tokens_per_fr
                           int grid_h, int grid_w, float rope_theta,
                           void* dev_buffer, size_t dev_bytes, ll_cache** out);
 
+/* The 8-bit variant of the cache: rotated keys, values and rotated queries are held as 8-bit floating point
+ * numbers (OCP E4M3: 4 exponent bits with bias 7, 3 mantissa bits, largest value 448) and both products of the
+ * attention run on the fp8 matrix instructions.  The paper quantises the model's weights to 8 bits and reports
+ * that quality holds (Appendix "Quantization" and its table); applying 8 bits to the attention operands is this
+ * library's extension, with its own, looser accuracy: the result differs from ll_cache_create's by a few per cent
+ * in relative L2 norm on random inputs.  Everything else is as for ll_cache_create, and every call below takes
+ * either kind of handle.  Definition (e4m3 = nearest E4M3 value, ties to even, |x| clamped to 448 first):
+ *     K8 = e4m3(K' * 2^-k_exp), V8 = e4m3(V * 2^-v_exp), Q8 = e4m3(q' * log2(e)/sqrt(D) * 2^k_exp),
+ *     out = 2^v_exp * sum_j w_j V8_j / sum_j w_j,   w_j = 2^(Q8 . K8_j - max);
+ *   the kernel also rounds the weights w_j to E4M3 (relative to a running reference) before the second product.
+ *   k_exp, v_exp in [-16, 16]: powers of two (exact to apply) that bring K' and V into E4M3's range; 0 suits
+ *   inputs of magnitude up to a few hundred, and a floating point format needs no finer (per-frame) scale.
+ *   Differences for the other calls with such a handle:
+ *     - q_out of ll_chunk_append and q_roped of ll_sink_window_attn are [n*P, H, D] bytes (E4M3 codes);
+ *       q_out must not alias q.  q, k, v and out stay bfloat16.
+ *     - ll_recache_prefill stages its queries in an area of the cache buffer shared by all layers: two prefill
+ *       calls on one handle must not overlap in time (enqueue them on one stream).  out is written only.
+ *     - ll_cache_read_frame returns codes: k_out, v_out are [P, H, D] bytes.
+ *   ll_cache_bytes_fp8 gives the buffer size (about half of ll_cache_bytes plus the staging area). */
+size_t ll_cache_bytes_fp8(int layers, int heads, int head_dim, int tokens_per_frame,
+                          int sink_frames, int window_frames, int chunk_frames);
+ll_status ll_cache_create_fp8(int layers, int heads, int head_dim, int tokens_per_frame,
+                              int sink_frames, int window_frames, int chunk_frames,
+                              int grid_h, int grid_w, float rope_theta, int k_exp, int v_exp,
+                              void* dev_buffer, size_t dev_bytes, ll_cache** out);
+
 /* Free the host bookkeeping.  The device buffer stays with the caller. */
 ll_status ll_cache_destroy(ll_cache* cache);
 

@@ -22,6 +22,8 @@ _vp, _i, _i64, _sz = C.c_void_p, C.c_int, C.c_int64, C.c_size_t
 SIGNATURES = {
     "ll_cache_bytes": (_sz, [_i] * 7),
     "ll_cache_create": (_i, [_i] * 9 + [C.c_float, _vp, _sz, C.POINTER(_vp)]),
+    "ll_cache_bytes_fp8": (_sz, [_i] * 7),
+    "ll_cache_create_fp8": (_i, [_i] * 9 + [C.c_float, _i, _i, _vp, _sz, C.POINTER(_vp)]),
     "ll_cache_destroy": (_i, [_vp]),
     "ll_cache_reset": (_i, [_vp, _i]),
     "ll_chunk_append": (_i, [_vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]),
@@ -74,8 +76,9 @@ def _stream():
     return C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def cache_bytes(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames) -> int:
-    return lib().ll_cache_bytes(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames)
+def cache_bytes(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames, kv_format="bf16") -> int:
+    fn = lib().ll_cache_bytes_fp8 if kv_format == "fp8_e4m3" else lib().ll_cache_bytes
+    return fn(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames)
 
 
 def set_attn_variant(variant: int) -> None:
@@ -117,17 +120,24 @@ def attn_variant_names() -> dict:
 
 
 class Cache:
-    """Handle on ``layers`` rolling KV caches.  ``device=None`` makes an index-only handle."""
+    """Handle on ``layers`` rolling KV caches.  ``device=None`` makes an index-only handle.
+
+    ``kv_format="fp8_e4m3"`` makes the 8-bit cache (``ll_cache_create_fp8``): q_out of ``chunk_append`` and the
+    tensors of ``read_frame`` are then uint8 (E4M3 codes) of the same shape; everything else stays bfloat16.
+    """
 
     def __init__(self, layers, heads, head_dim, grid_h, grid_w, chunk_frames, sink_frames, window_frames,
-                 rope_theta=10000.0, device="cuda"):
+                 rope_theta=10000.0, device="cuda", kv_format="bf16", k_exp=0, v_exp=0):
+        if kv_format not in ("bf16", "fp8_e4m3"):
+            raise ValueError(f"kv_format {kv_format!r}")
+        self.kv_format = kv_format
         self.layers, self.heads, self.head_dim = layers, heads, head_dim
         self.grid_h, self.grid_w = grid_h, grid_w
         self.P = grid_h * grid_w
         self.C, self.S, self.W = chunk_frames, sink_frames, window_frames
         self._h = C.c_void_p()
         self.buffer = None
-        nbytes = cache_bytes(layers, heads, head_dim, self.P, sink_frames, window_frames, chunk_frames)
+        nbytes = cache_bytes(layers, heads, head_dim, self.P, sink_frames, window_frames, chunk_frames, kv_format)
         if device is not None:
             import torch
             if nbytes == 0:
@@ -136,8 +146,12 @@ class Cache:
             ptr, size = C.c_void_p(self.buffer.data_ptr()), nbytes
         else:
             ptr, size = None, 0
-        _check(lib().ll_cache_create(layers, heads, head_dim, self.P, sink_frames, window_frames, chunk_frames,
-                                     grid_h, grid_w, rope_theta, ptr, size, C.byref(self._h)))
+        if kv_format == "fp8_e4m3":
+            _check(lib().ll_cache_create_fp8(layers, heads, head_dim, self.P, sink_frames, window_frames, chunk_frames,
+                                             grid_h, grid_w, rope_theta, k_exp, v_exp, ptr, size, C.byref(self._h)))
+        else:
+            _check(lib().ll_cache_create(layers, heads, head_dim, self.P, sink_frames, window_frames, chunk_frames,
+                                         grid_h, grid_w, rope_theta, ptr, size, C.byref(self._h)))
 
     def close(self):
         if self._h:

@@ -19,13 +19,17 @@
 using namespace ll;
 
 struct ll_cache {
+    int fmt;                // 0: bf16 cache, 1: 8-bit (E4M3) cache
+    int kb;                 // key slots per kblock: KBLOCK or KBLOCK8
+    int k_exp, v_exp;       // 8-bit cache: K8 = e4m3(K' 2^-k_exp), V8 = e4m3(V 2^-v_exp)
+    char* q8_stage;         // 8-bit cache: staging area for the E4M3 queries of a re-prefill
     int layers, H, D;
     Geometry g;
     int grid_h, grid_w;
     double theta;
     char* dev;              // null for an index-only handle
     int64_t kblocks;        // kblocks per head region (with padding)
-    int64_t head_stride;    // elements between heads (K region + V region)
+    int64_t head_stride;    // elements between heads (K region + V region); bytes for the 8-bit cache
     int64_t layer_stride;   // elements between layers
     RopeTables rope;
     std::vector<LayerIndex> layer;
@@ -51,22 +55,25 @@ namespace {
 struct Sizes {
     int64_t kblocks, head_stride, layer_stride, cache_elems;
     int n_t, n_h, n_w;
-    size_t table_off, row_off, col_off, total;
+    size_t stage_off, table_off, row_off, col_off, total;
 };
 bool shapes_ok(int layers, int H, int D, int P, int S, int W, int C) {
     return layers >= 1 && H >= 1 && (D == 64 || D == 128) && P >= 1 && S >= 0 && W >= 0 && C >= 1 &&
            int64_t(S + W + C) * P < (int64_t(1) << 30);
 }
-Sizes sizes(int layers, int H, int D, int P, int S, int W, int C, int grid_h, int grid_w) {
+Sizes sizes(int fmt, int layers, int H, int D, int P, int S, int W, int C, int grid_h, int grid_w) {
     Sizes z{};
+    const int kb = fmt ? KBLOCK8 : KBLOCK;
     const int64_t slots = int64_t(S + W + C) * P;
-    z.kblocks = (slots + KBLOCK - 1) / KBLOCK + PAD_KBLOCKS;
-    z.head_stride = 2 * z.kblocks * KBLOCK * D;
+    z.kblocks = (slots + kb - 1) / kb + PAD_KBLOCKS;
+    z.head_stride = 2 * z.kblocks * kb * D;
     z.layer_stride = z.head_stride * H;
     z.cache_elems = z.layer_stride * layers;
     const int d_hw = 2 * (D / 6), d_t = D - 2 * d_hw;
     z.n_t = d_t / 2; z.n_h = d_hw / 2; z.n_w = d_hw / 2;
-    size_t off = (size_t(z.cache_elems) * 2 + 255) & ~size_t(255);
+    size_t off = (size_t(z.cache_elems) * (fmt ? 1 : 2) + 255) & ~size_t(255);
+    z.stage_off = off;
+    if (fmt) off = (off + size_t(slots) * H * D + 255) & ~size_t(255);   // E4M3 queries of one re-prefill
     z.table_off = off; off += size_t(z.n_t) * sizeof(double);
     off = (off + 255) & ~size_t(255);
     z.row_off = off; off += size_t(grid_h) * z.n_h * sizeof(float2);
@@ -81,18 +88,29 @@ size_t table_bound(int D, int P) { return 3 * 256 + 64 * sizeof(double) + 2 * si
 
 extern "C" {
 
-size_t ll_cache_bytes(int layers, int heads, int head_dim, int tokens_per_frame, int sink_frames,
-                      int window_frames, int chunk_frames) {
+static size_t cache_bytes(int fmt, int layers, int heads, int head_dim, int tokens_per_frame, int sink_frames,
+                          int window_frames, int chunk_frames) {
     if (!shapes_ok(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames)) return 0;
-    Sizes z = sizes(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames, 0, 0);
+    Sizes z = sizes(fmt, layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames, 0, 0);
     return z.table_off + table_bound(head_dim, tokens_per_frame);
 }
 
-ll_status ll_cache_create(int layers, int heads, int head_dim, int tokens_per_frame, int sink_frames,
-                          int window_frames, int chunk_frames, int grid_h, int grid_w, float rope_theta,
-                          void* dev_buffer, size_t dev_bytes, ll_cache** out) {
+size_t ll_cache_bytes(int layers, int heads, int head_dim, int tokens_per_frame, int sink_frames,
+                      int window_frames, int chunk_frames) {
+    return cache_bytes(0, layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames);
+}
+size_t ll_cache_bytes_fp8(int layers, int heads, int head_dim, int tokens_per_frame, int sink_frames,
+                          int window_frames, int chunk_frames) {
+    return cache_bytes(1, layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames);
+}
+
+static ll_status cache_create(int fmt, int k_exp, int v_exp, int layers, int heads, int head_dim, int tokens_per_frame,
+                              int sink_frames, int window_frames, int chunk_frames, int grid_h, int grid_w,
+                              float rope_theta, void* dev_buffer, size_t dev_bytes, ll_cache** out) {
     if (!out) return fail(LL_ERR_INVALID_ARG, "out is null");
     *out = nullptr;
+    if (k_exp < -16 || k_exp > 16 || v_exp < -16 || v_exp > 16)
+        return fail(LL_ERR_INVALID_ARG, "k_exp %d or v_exp %d outside [-16, 16]", k_exp, v_exp);
     if (!shapes_ok(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames))
         return fail(head_dim != 64 && head_dim != 128 && head_dim > 0 ? LL_ERR_UNSUPPORTED : LL_ERR_INVALID_ARG,
                     "bad shape: layers %d heads %d head_dim %d (64 or 128) tokens_per_frame %d sink %d window %d chunk %d",
@@ -103,14 +121,16 @@ ll_status ll_cache_create(int layers, int heads, int head_dim, int tokens_per_fr
     if (chunk_frames > MAX_APPEND_FRAMES)
         return fail(LL_ERR_UNSUPPORTED, "chunk_frames above %d", MAX_APPEND_FRAMES);
     const bool index_only = dev_buffer == nullptr && dev_bytes == 0;
-    const size_t need = ll_cache_bytes(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames);
+    const size_t need = cache_bytes(fmt, layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames);
     if (!index_only) {
         if (!dev_buffer) return fail(LL_ERR_INVALID_ARG, "dev_buffer is null");
         if (reinterpret_cast<uintptr_t>(dev_buffer) & 255) return fail(LL_ERR_INVALID_ARG, "dev_buffer is not 256-byte aligned");
         if (dev_bytes < need) return fail(LL_ERR_BUFFER_TOO_SMALL, "dev_buffer has %zu bytes, %zu needed", dev_bytes, need);
     }
-    Sizes z = sizes(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames, grid_h, grid_w);
+    Sizes z = sizes(fmt, layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames, grid_h, grid_w);
     ll_cache* c = new ll_cache();
+    c->fmt = fmt; c->kb = fmt ? KBLOCK8 : KBLOCK; c->k_exp = k_exp; c->v_exp = v_exp;
+    c->q8_stage = (fmt && dev_buffer) ? static_cast<char*>(dev_buffer) + z.stage_off : nullptr;
     c->layers = layers; c->H = heads; c->D = head_dim;
     c->g.P = tokens_per_frame; c->g.S = sink_frames; c->g.W = window_frames; c->g.C = chunk_frames;
     c->grid_h = grid_h; c->grid_w = grid_w; c->theta = rope_theta;
@@ -147,6 +167,19 @@ ll_status ll_cache_create(int layers, int heads, int head_dim, int tokens_per_fr
     return LL_OK;
 }
 
+ll_status ll_cache_create(int layers, int heads, int head_dim, int tokens_per_frame, int sink_frames,
+                          int window_frames, int chunk_frames, int grid_h, int grid_w, float rope_theta,
+                          void* dev_buffer, size_t dev_bytes, ll_cache** out) {
+    return cache_create(0, 0, 0, layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames,
+                        grid_h, grid_w, rope_theta, dev_buffer, dev_bytes, out);
+}
+ll_status ll_cache_create_fp8(int layers, int heads, int head_dim, int tokens_per_frame, int sink_frames,
+                              int window_frames, int chunk_frames, int grid_h, int grid_w, float rope_theta,
+                              int k_exp, int v_exp, void* dev_buffer, size_t dev_bytes, ll_cache** out) {
+    return cache_create(1, k_exp, v_exp, layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames,
+                        chunk_frames, grid_h, grid_w, rope_theta, dev_buffer, dev_bytes, out);
+}
+
 ll_status ll_cache_destroy(ll_cache* cache) {
     delete cache;
     return LL_OK;
@@ -177,6 +210,12 @@ static uint16_t* layer_k(const ll_cache* c, int layer) {
 static uint16_t* layer_v(const ll_cache* c, int layer) {
     return layer_k(c, layer) + c->kblocks * KBLOCK * c->D;
 }
+static uint8_t* layer_k8(const ll_cache* c, int layer) {
+    return reinterpret_cast<uint8_t*>(c->dev) + int64_t(layer) * c->layer_stride;
+}
+static uint8_t* layer_v8(const ll_cache* c, int layer) {
+    return layer_k8(c, layer) + c->kblocks * KBLOCK8 * c->D;
+}
 
 // Enqueue the rotary + cache write of `n` frames whose absolute indices are frames[i];
 // rows of q/k/v are consecutive frames.
@@ -189,9 +228,16 @@ static ll_status enqueue_append(ll_cache* c, int layer, const int64_t* frames, i
         p.q = static_cast<const uint16_t*>(q) + base * frame_elems;
         p.k = static_cast<const uint16_t*>(k) + base * frame_elems;
         p.v = static_cast<const uint16_t*>(v) + base * frame_elems;
-        p.q_out = static_cast<uint16_t*>(q_out) + base * frame_elems;
         p.q_scale = float(1.4426950408889634 / std::sqrt(double(c->D)));
-        p.k_cache = layer_k(c, layer); p.v_cache = layer_v(c, layer);
+        if (c->fmt) {
+            p.q8_out = static_cast<uint8_t*>(q_out) + base * frame_elems;
+            p.k8_cache = layer_k8(c, layer); p.v8_cache = layer_v8(c, layer);
+            p.q_scale = std::ldexp(p.q_scale, c->k_exp);
+            p.k_mul = std::ldexp(1.0f, -c->k_exp); p.v_mul = std::ldexp(1.0f, -c->v_exp);
+        } else {
+            p.q_out = static_cast<uint16_t*>(q_out) + base * frame_elems;
+            p.k_cache = layer_k(c, layer); p.v_cache = layer_v(c, layer);
+        }
         p.head_stride = c->head_stride;
         p.rope = c->rope;
         p.H = c->H; p.D = c->D; p.P = c->g.P; p.grid_w = c->grid_w;
@@ -200,18 +246,18 @@ static ll_status enqueue_append(ll_cache* c, int layer, const int64_t* frames, i
         for (int i = 0; i < m; ++i) {
             p.frame[i] = frames[base + i];
             p.slot[i] = slot_of_frame(c->g, frames[base + i]);
-            const int nseg = int((p.slot[i] % KBLOCK + c->g.P + KBLOCK - 1) / KBLOCK);
+            const int nseg = int((p.slot[i] % c->kb + c->g.P + c->kb - 1) / c->kb);
             p.seg_begin[i + 1] = p.seg_begin[i] + nseg;
         }
-        hipError_t e = launch_append(p, s);
+        hipError_t e = c->fmt ? launch_append8(p, s) : launch_append(p, s);
         if (e != hipSuccess) return hip_fail(e, "append kernel launch");
     }
     return LL_OK;
 }
 
 static int pick_variant(const ll_cache* c) {
-    if (g_variant != 0 && attn_variant_supports(g_variant, c->D)) return g_variant;
-    return attn_variant_default(c->D);
+    if (g_variant != 0 && attn_variant_supports(g_variant, c->D, c->kb)) return g_variant;
+    return attn_variant_default(c->D, c->kb);
 }
 
 struct ChunkWork { int q_begin, q_end; std::vector<SlotRange> ranges; };
@@ -223,9 +269,16 @@ static ll_status enqueue_attn(ll_cache* c, int layer, const std::vector<ChunkWor
     const int qt = attn_variant_qtile(variant);
     for (size_t base = 0; base < work.size(); base += MAX_ATTN_CHUNKS) {
         AttnParams p{};
-        p.q = static_cast<const uint16_t*>(q);
         p.out = static_cast<uint16_t*>(out);
-        p.k_cache = layer_k(c, layer); p.v_cache = layer_v(c, layer);
+        p.kblock = c->kb;
+        if (c->fmt) {
+            p.q8 = static_cast<const uint8_t*>(q);
+            p.k8_cache = layer_k8(c, layer); p.v8_cache = layer_v8(c, layer);
+            p.out_scale = std::ldexp(1.0f, c->v_exp);
+        } else {
+            p.q = static_cast<const uint16_t*>(q);
+            p.k_cache = layer_k(c, layer); p.v_cache = layer_v(c, layer);
+        }
         p.head_stride = c->head_stride;
         p.H = c->H; p.D = c->D;
         p.scale_log2e = 1.0f;          // ll_chunk_append already folded log2(e)/sqrt(D) into q
@@ -263,6 +316,8 @@ ll_status ll_chunk_append(ll_cache* cache, int layer, int64_t frame_start, int n
     if (cache->dev && any_null) return fail(LL_ERR_INVALID_ARG, "null tensor");
     if (!cache->dev && !(!q && !k && !v && !q_out)) return fail(LL_ERR_INVALID_ARG, "index-only handle takes null tensors");
     if (!aligned16(q, k, v, q_out)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+    if (cache->fmt && cache->dev && (q_out == q || q_out == k || q_out == v))
+        return fail(LL_ERR_INVALID_ARG, "q_out (E4M3 bytes) must not alias q, k or v");
     LayerIndex& L = cache->layer[layer];
     if (classify_append(L, frame_start) == AppendKind::Invalid)
         return fail(LL_ERR_STATE, "layer %d: frame_start %lld neither repeats (%lld) nor follows (%lld) the staged chunk",
@@ -313,8 +368,11 @@ ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64
         std::vector<int64_t> frames;
         for (const ChunkSpan& c : chunks)
             for (int i = 0; i < c.n; ++i) frames.push_back(c.f0 + i);
-        // rotated queries are staged in `out`; the attention kernel reads and overwrites them in place
-        ll_status st = enqueue_append(cache, layer, frames.data(), int(frames.size()), q, k, v, out, s);
+        // rotated queries are staged in `out`; the attention kernel reads and overwrites them in place (bf16: a
+        // wave reads exactly the rows it writes).  E4M3 queries are half as wide as the output rows, so they are
+        // staged in the cache buffer's own area instead.
+        void* q_stage = cache->fmt ? static_cast<void*>(cache->q8_stage) : out;
+        ll_status st = enqueue_append(cache, layer, frames.data(), int(frames.size()), q, k, v, q_stage, s);
         if (st != LL_OK) return st;
     }
     begin_prefill(g, L, include_sink != 0, win_start);
@@ -328,7 +386,7 @@ ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64
         work.push_back(w);
         row = w.q_end;
     }
-    if (cache->dev) return enqueue_attn(cache, layer, work, out, out, s);
+    if (cache->dev) return enqueue_attn(cache, layer, work, cache->fmt ? static_cast<void*>(cache->q8_stage) : out, out, s);
     return LL_OK;
 }
 
@@ -365,10 +423,16 @@ ll_status ll_cache_read_frame(const ll_cache* cache, int layer, int64_t frame, v
     if (!cache->dev) return fail(LL_ERR_INVALID_ARG, "index-only handle has no device cache");
     if (!frame_held(cache->g, cache->layer[layer], frame)) return fail(LL_ERR_STATE, "layer %d does not hold frame %lld", layer, (long long)frame);
     ReadFrameParams p{};
-    p.k_cache = layer_k(cache, layer); p.v_cache = layer_v(cache, layer); p.head_stride = cache->head_stride;
-    p.k_out = static_cast<uint16_t*>(k_out); p.v_out = static_cast<uint16_t*>(v_out);
+    p.head_stride = cache->head_stride;
+    if (cache->fmt) {
+        p.k8_cache = layer_k8(cache, layer); p.v8_cache = layer_v8(cache, layer);
+        p.k8_out = static_cast<uint8_t*>(k_out); p.v8_out = static_cast<uint8_t*>(v_out);
+    } else {
+        p.k_cache = layer_k(cache, layer); p.v_cache = layer_v(cache, layer);
+        p.k_out = static_cast<uint16_t*>(k_out); p.v_out = static_cast<uint16_t*>(v_out);
+    }
     p.H = cache->H; p.D = cache->D; p.P = cache->g.P; p.slot = slot_of_frame(cache->g, frame);
-    hipError_t e = launch_read_frame(p, static_cast<hipStream_t>(stream));
+    hipError_t e = cache->fmt ? launch_read_frame8(p, static_cast<hipStream_t>(stream)) : launch_read_frame(p, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "read_frame kernel launch");
     return LL_OK;
 }

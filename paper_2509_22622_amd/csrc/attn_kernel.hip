@@ -254,7 +254,7 @@ __global__ __launch_bounds__(NW * 64) void ll_attn_kernel(const AttnParams p) {
 
 #define LL_VARIANT(D, QB, NW, KT)                                                              \
     { "d" #D "_q" #QB "x" #NW "_k" #KT, D, NW * QB * 32, 2 * 2 * KT * KBLOCK * D * 2,          \
-      ll_attn_kernel<D, QB, NW, KT>, NW * 64 }
+      ll_attn_kernel<D, QB, NW, KT>, NW * 64, KBLOCK }
 
 static const AttnVariant kSimpleVariants[] = {
     LL_VARIANT(128, 2, 4, 2),   // 1: 256 queries, 64-key tiles
@@ -266,29 +266,37 @@ static const AttnVariant kSimpleVariants[] = {
 };
 constexpr int kNumSimple = sizeof(kSimpleVariants) / sizeof(kSimpleVariants[0]);
 
-// variant ids: 1..kNumSimple are the kernels of this file, then the software-pipelined kernels
+// variant ids: 1..kNumSimple are the kernels of this file, then the software-pipelined kernels, then the
+// kernels of the 8-bit cache
 static const AttnVariant* variant(int v) {
     if (v >= 1 && v <= kNumSimple) return &kSimpleVariants[v - 1];
-    if (v > kNumSimple && v <= kNumSimple + kNumStreamVariants) return &kStreamVariants[v - kNumSimple - 1];
+    v -= kNumSimple;
+    if (v >= 1 && v <= kNumStreamVariants) return &kStreamVariants[v - 1];
+    v -= kNumStreamVariants;
+    if (v >= 1 && v <= kNumFp8Variants) return &kFp8Variants[v - 1];
     return nullptr;
 }
-int attn_variant_count() { return kNumSimple + kNumStreamVariants; }
+int attn_variant_count() { return kNumSimple + kNumStreamVariants + kNumFp8Variants; }
 const char* attn_variant_name(int v) { return variant(v) ? variant(v)->name : nullptr; }
 // the software-pipelined kernels are the default
-int attn_variant_default(int D) { return D == 128 ? kNumSimple + 1 : kNumSimple + 2; }
+int attn_variant_default(int D, int kblock) {
+    if (kblock == KBLOCK8) return kNumSimple + kNumStreamVariants + (D == 128 ? 1 : 2);
+    return D == 128 ? kNumSimple + 1 : kNumSimple + 2;
+}
 int attn_variant_qtile(int v) { return variant(v)->qtile; }
-bool attn_variant_supports(int v, int D) { return variant(v) && variant(v)->D == D; }
+bool attn_variant_supports(int v, int D, int kblock) { return variant(v) && variant(v)->D == D && variant(v)->kblock == kblock; }
 
 hipError_t launch_attn(const AttnParams& p_in, int variant, hipStream_t s) {
-    if (!attn_variant_supports(variant, p_in.D)) return hipErrorInvalidValue;
+    if (!attn_variant_supports(variant, p_in.D, p_in.kblock)) return hipErrorInvalidValue;
     AttnParams p = p_in;
+    const int KB = p.kblock;
     const AttnVariant& v = *ll::variant(variant);
     const int total = p.n_tiles * p.H;
     if (total <= 0) return hipSuccess;
     for (int c = 0; c < p.n_chunks; ++c) {
         AttnChunk& ch = p.chunk[c];
         ch.n_kblocks = 0;
-        for (int r = 0; r < ch.n_ranges; ++r) ch.n_kblocks += (ch.re[r] + KBLOCK - 1) / KBLOCK - ch.rs[r] / KBLOCK;
+        for (int r = 0; r < ch.n_ranges; ++r) ch.n_kblocks += (ch.re[r] + KB - 1) / KB - ch.rs[r] / KB;
         if (ch.n_kblocks < 1) return hipErrorInvalidValue;
     }
     int grid = ((total + 7) / 8) * 8;           // the kernels spread their workgroups over the 8 XCDs

@@ -519,8 +519,8 @@ __global__ __launch_bounds__(SP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
 }
 
 const AttnVariant kStreamVariants[] = {
-    {"d128_stream", 128, 256, 8 * 2 * KBLOCK * 128 * 2, ll_attn_stream_kernel<128>, SP_THREADS},
-    {"d64_stream", 64, 256, 8 * 2 * KBLOCK * 64 * 2, ll_attn_stream_kernel<64>, SP_THREADS},
+    {"d128_stream", 128, 256, 8 * 2 * KBLOCK * 128 * 2, ll_attn_stream_kernel<128>, SP_THREADS, KBLOCK},
+    {"d64_stream", 64, 256, 8 * 2 * KBLOCK * 64 * 2, ll_attn_stream_kernel<64>, SP_THREADS, KBLOCK},
 };
 const int kNumStreamVariants = sizeof(kStreamVariants) / sizeof(kStreamVariants[0]);
 

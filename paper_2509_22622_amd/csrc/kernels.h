@@ -37,6 +37,25 @@ __host__ __device__ inline int v_elem_offset(int k, int d) {
     return ((((((d >> 5) * 2 + t) * 2 + h) * 32) + (d & 31)) << 3) + e;
 }
 
+// ---- 8-bit (E4M3) cache.  One byte per element, kblocks of 64 slots, stored as the register image of the
+// 32x32x64 fp8 MFMA (lane = 32 * k-half + row holds 32 consecutive contraction elements of its k-half), in
+// 1 KB pieces [64 lanes][16 bytes] so that HBM -> LDS -> VGPR are straight 16-byte copies:
+//   K kblock  [2 row blocks R][D/64 feature halves dh][2 pieces c][lane (h, r)][16]
+//             lane (h, r) of piece (R, dh, c) holds key 32R + r, features 64dh + 32h + 16c + 0..15.
+//   V kblock  [D/32 d-blocks db][2 pieces R][lane (h, dd)][16]
+//             byte 4g + j of lane (h, dd) of piece (db, R) holds key 32R + 8g + 4h + j at feature 32db + dd:
+//             the keys whose scores the S^T accumulator registers 4g + j of a lane in half h hold, so the
+//             softmax weights go from accumulator to the second MFMA's operand without leaving the lane.
+constexpr int KBLOCK8 = 64;
+__host__ __device__ inline int k8_byte_offset(int k, int d, int D) {
+    const int R = k >> 5, r = k & 31, dh = d >> 6, h = (d >> 5) & 1, c = (d >> 4) & 1;
+    return ((((R * (D >> 6) + dh) * 2 + c) * 64 + h * 32 + r) << 4) + (d & 15);
+}
+__host__ __device__ inline int v8_byte_offset(int k, int d) {
+    const int R = k >> 5, r = k & 31, h = (r >> 2) & 1;
+    return ((((d >> 5) * 2 + R) * 64 + h * 32 + (d & 31)) << 4) + 4 * (r >> 3) + (r & 3);
+}
+
 struct RopeTables {            // device pointers into the cache buffer's tail
     const double* inv_freq_t;  // [n_t]      frame-axis frequencies theta^(-2i/d_t)
     const float2* row_cs;      // [grid_h][n_h]  (cos, sin) of y * freq
@@ -55,7 +74,10 @@ struct AppendParams {
     int n_frames;
     int64_t frame[MAX_APPEND_FRAMES];                           // absolute frame index
     int64_t slot[MAX_APPEND_FRAMES];                            // first token slot
-    int seg_begin[MAX_APPEND_FRAMES + 1];                       // prefix sum of 32-slot segments
+    int seg_begin[MAX_APPEND_FRAMES + 1];                       // prefix sum of kblock segments (32 or 64 slots)
+    // 8-bit cache (all null / unused for the bf16 cache): byte pointers, head_stride in bytes
+    uint8_t* q8_out; uint8_t* k8_cache; uint8_t* v8_cache;
+    float k_mul, v_mul;                                         // 2^-k_exp, 2^-v_exp (q_scale carries 2^k_exp)
 };
 
 struct AttnChunk {
@@ -78,6 +100,10 @@ struct AttnParams {
     // differ in length) XCD x runs the (head, chunk) groups xcd_group[xcd_first[x] .. xcd_first[x + 1]) in that
     // order, all tiles of a group on one XCD; group = head * n_chunks + chunk.
     int n_groups;
+    // 8-bit cache: E4M3 queries and cache (byte pointers, head_stride in bytes), factor 2^v_exp on the output
+    const uint8_t* q8; const uint8_t* k8_cache; const uint8_t* v8_cache;
+    float out_scale;
+    int kblock;                  // key slots per kblock: 32 (bf16 cache) or 64 (8-bit cache)
     uint16_t xcd_first[9];
     uint16_t xcd_group[MAX_XCD_GROUPS];
     AttnChunk chunk[MAX_ATTN_CHUNKS];
@@ -87,6 +113,8 @@ struct ReadFrameParams {
     const uint16_t* k_cache; const uint16_t* v_cache; int64_t head_stride;
     uint16_t* k_out; uint16_t* v_out;     // [P, H, D], either may be null
     int H, D, P; int64_t slot;
+    const uint8_t* k8_cache; const uint8_t* v8_cache;   // 8-bit cache: codes go to k8_out / v8_out
+    uint8_t* k8_out; uint8_t* v8_out;
 };
 
 // One attention kernel instantiation.
@@ -95,18 +123,23 @@ struct AttnVariant {
     int D, qtile, lds_bytes;
     void (*kernel)(const AttnParams);
     int threads;
+    int kblock;                  // 32: bf16 cache, 64: 8-bit cache
 };
 extern const AttnVariant kStreamVariants[];
 extern const int kNumStreamVariants;
+extern const AttnVariant kFp8Variants[];
+extern const int kNumFp8Variants;
 
 // Attention variants (query rows per workgroup differ).
 int attn_variant_count();
 const char* attn_variant_name(int v);
-int attn_variant_default(int D);
+int attn_variant_default(int D, int kblock);
 int attn_variant_qtile(int v);                 // query rows per workgroup
-bool attn_variant_supports(int v, int D);
+bool attn_variant_supports(int v, int D, int kblock);
 
 hipError_t launch_append(const AppendParams& p, hipStream_t s);
+hipError_t launch_append8(const AppendParams& p, hipStream_t s);
+hipError_t launch_read_frame8(const ReadFrameParams& p, hipStream_t s);
 hipError_t launch_attn(const AttnParams& p, int variant, hipStream_t s);
 hipError_t launch_read_frame(const ReadFrameParams& p, hipStream_t s);
 // diagnostic (probe_kernels.hip): sink holds workgroups * 512 floats, counters two 64-bit words; `companion` is the

@@ -1,0 +1,250 @@
+"""GPU parity of the 8-bit (E4M3) cache variant: the HIP library through its C-ABI against oracle/fp8_cache.py.
+
+What is compared, and how tightly:
+  * the bookkeeping (live frames) exactly;
+  * V codes in the cache bit for bit (bf16 -> E4M3 is one rounding of an exact value, both sides decide it on the
+    same number);
+  * K and q' codes: the kernel rotates in fp32, the oracle in fp64, so a value that lies within fp32 noise of a
+    rounding boundary may land on the neighbouring code: at most one code step apart, and rarely (bound below);
+  * the attention output within the tolerance of this accuracy tier.  The oracle keeps the softmax weights exact;
+    the kernel rounds them to E4M3 (relative error at most 2^-4, about 2.6 % rms, independent from key to key).
+    For one output element the error is sum_j w_j e_j V_j / sum_j w_j: at most 2^-4 * max|V| in magnitude (the
+    max-abs tolerance, plus the bf16 rounding of the output), and for values that are independent from key to
+    key about 2.6 % of the output's own rms, so that the relative L2 error of a tensor is gated at 6 %.  A wrong
+    key order, a wrong slot or a transposed operand gives a relative L2 error above 1.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle.fp8_cache import Fp8Oracle, e4m3_encode, e4m3_table
+from oracle.longlive_oracle import bf16_bits_to_f64, error_metrics
+from paper_2509_22622_amd import binding as B
+from paper_2509_22622_amd import synth
+
+import gpu_harness as H
+from test_gpu_parity import HEADS6, MID128, NOSINK, ODD128, ODD64, WIDE, _random_workload
+
+pytestmark = pytest.mark.gpu
+
+REL_L2_TOL_FP8 = 6e-2
+CODE_FLIP_FRACTION = 2e-3     # fp32 rotation noise ~1e-7 relative against code boundaries 2^-4 apart: ~1e-5 expected
+TABLE = e4m3_table()
+
+
+def make_cache8(w, k_exp=0, v_exp=0):
+    return B.Cache(w.layers, w.heads, w.head_dim, w.grid_h, w.grid_w, w.chunk_frames, w.sink_frames, w.window_frames,
+                   kv_format="fp8_e4m3", k_exp=k_exp, v_exp=v_exp)
+
+
+def assert_codes_close(got: np.ndarray, want_values: np.ndarray, what: str):
+    """`got` (uint8 codes from the GPU) against the oracle's E4M3 values: equal, or one code step apart, rarely."""
+    want = e4m3_encode(want_values)
+    gv, wv = TABLE[got], TABLE[want]
+    assert not np.isnan(gv).any(), f"{what}: NaN code"
+    differ = gv != wv                                             # +0 and -0 count as equal
+    if differ.any():
+        mag_g, mag_w = (got & 0x7F).astype(np.int32), (want & 0x7F).astype(np.int32)
+        same_sign = (got & 0x80) == (want & 0x80)
+        one_step = (np.abs(mag_g - mag_w) == 1) & same_sign
+        tiny = (mag_g + mag_w) <= 1                               # across zero: +-2^-9 against 0
+        assert (one_step | tiny)[differ].all(), f"{what}: codes more than one step apart"
+    assert differ.mean() <= CODE_FLIP_FRACTION, f"{what}: {differ.mean():.2e} of the codes differ"
+
+
+def assert_parity8(out_bits, want, v_absmax, what):
+    got = bf16_bits_to_f64(out_bits)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    max_abs, rel = error_metrics(got, want)
+    bound = 2.0 ** -4 * v_absmax * 1.02 + 2.0 ** -8 * np.abs(want).max()
+    assert max_abs <= bound and rel <= REL_L2_TOL_FP8, f"{what}: max_abs {max_abs:.3e} (bound {bound:.3e}) rel_l2 {rel:.3e}"
+    return max_abs, rel
+
+
+def check_frame8(cache, oracle, w, layer, frame, k_exp=0):
+    shape = (w.tokens_per_frame, w.heads, w.head_dim)
+    kd = torch.empty(shape, dtype=torch.uint8, device="cuda")
+    vd = torch.empty(shape, dtype=torch.uint8, device="cuda")
+    cache.read_frame(layer, frame, kd, vd)
+    torch.cuda.synchronize()
+    k_want, v_want = oracle.frame_kv(layer, frame)
+    gv = TABLE[vd.cpu().numpy()]
+    assert np.array_equal(gv, v_want), f"V codes of frame {frame} not bit-exact"
+    assert_codes_close(kd.cpu().numpy(), k_want, f"K codes of frame {frame}")
+
+
+def _v_absmax(oracle, layer):
+    return max(np.abs(oracle.frame_kv(layer, f)[1]).max() for f in oracle.live_frames(layer)) * 2.0 ** oracle.v_exp
+
+
+def _stream_and_check8(w, n_chunks, k_exp=0, v_exp=0, q_scale=1.0, passes=1, check_cache=True, short_last=False):
+    cache, oracle = make_cache8(w, k_exp, v_exp), Fp8Oracle(H.oracle_cfg(w), k_exp, v_exp)
+    worst = (0.0, 0.0)
+    f0 = 0
+    for i in range(n_chunks):
+        n = 1 if (short_last and i == n_chunks - 1) else w.chunk_frames
+        for rep in range(passes):
+            q, k, v = synth.chunk_qkv(w, 0, i + 1000 * (passes - 1 - rep), n, q_scale=q_scale)
+            qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+            qr = torch.empty(qd.shape, dtype=torch.uint8, device="cuda")
+            out = torch.empty_like(qd)
+            cache.chunk_append(0, f0, n, qd, kd, vd, qr)
+            cache.sink_window_attn(0, qr, out)
+            torch.cuda.synchronize()
+            q_want = oracle.append(0, f0, q, k, v)
+        assert cache.live_frames(0) == oracle.live_frames(0)
+        assert_codes_close(qr.cpu().numpy(), q_want, f"q' codes chunk {i}")
+        m = assert_parity8(H.to_bits(out), oracle.attn(0), _v_absmax(oracle, 0), f"{w.name} fp8 chunk {i}")
+        worst = (max(worst[0], m[0]), max(worst[1], m[1]))
+        if check_cache:
+            for f in oracle.live_frames(0):
+                check_frame8(cache, oracle, w, 0, f)
+        f0 += n
+    cache.close()
+    return worst
+
+
+def test_tiny_config_every_element_fp8():
+    worst = _stream_and_check8(synth.TINY, synth.TINY.n_chunks)
+    print("tiny fp8 worst (max_abs, rel_l2):", worst)
+
+
+@pytest.mark.parametrize("w", [MID128, ODD128, NOSINK, ODD64, WIDE], ids=lambda w: w.name)
+def test_small_shapes_every_element_fp8(w):
+    _stream_and_check8(w, w.n_chunks)
+
+
+def test_exponents_fp8():
+    """Power-of-two scales: k_exp moves K' down and q' up by the same factor, v_exp comes back on the output."""
+    _stream_and_check8(MID128, 5, k_exp=2, v_exp=-3)
+    _stream_and_check8(ODD64, 5, k_exp=-1, v_exp=2)
+
+
+def test_peaky_softmax_fp8():
+    """Logits of standard deviation 4: the reference moves often; the weights of a row span many binades."""
+    _stream_and_check8(MID128, 6, q_scale=4.0, check_cache=False)
+    _stream_and_check8(ODD64, 6, q_scale=4.0, check_cache=False)
+
+
+def test_only_the_last_pass_stays_fp8():
+    _stream_and_check8(MID128, 6, passes=3)
+
+
+def _prefill_case8(w, include_sink, ws, n_win, pre_chunks, follow=2):
+    P = w.tokens_per_frame
+    cache, oracle = make_cache8(w), Fp8Oracle(H.oracle_cfg(w))
+    for i in range(pre_chunks):
+        q, k, v = synth.chunk_qkv(w, 0, i)
+        qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+        cache.chunk_append(0, i * w.chunk_frames, w.chunk_frames, qd, kd, vd, torch.empty(qd.shape, dtype=torch.uint8, device="cuda"))
+        oracle.append(0, i * w.chunk_frames, q, k, v)
+    nf = (w.sink_frames if include_sink else 0) + n_win
+    shape = (nf * P, w.heads, w.head_dim)
+    q, k, v = (synth.normal_bf16(shape, w.cfg_id, 0, 500, t) for t in "qkv")
+    qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+    out = torch.empty_like(qd)
+    cache.recache_prefill(0, include_sink, ws, n_win, qd, kd, vd, out)
+    torch.cuda.synchronize()
+    want = oracle.recache_prefill(0, include_sink, ws, n_win, q, k, v)
+    assert cache.live_frames(0) == oracle.live_frames(0)
+    assert_parity8(H.to_bits(out), want, _v_absmax(oracle, 0), f"{w.name} fp8 prefill")
+    for f in oracle.live_frames(0):
+        check_frame8(cache, oracle, w, 0, f)
+    f0 = ws + n_win
+    for i in range(follow):
+        q, k, v = synth.chunk_qkv(w, 0, 600 + i)
+        qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+        qr, out = torch.empty(qd.shape, dtype=torch.uint8, device="cuda"), torch.empty_like(qd)
+        cache.chunk_append(0, f0, w.chunk_frames, qd, kd, vd, qr)
+        cache.sink_window_attn(0, qr, out)
+        torch.cuda.synchronize()
+        oracle.append(0, f0, q, k, v)
+        assert cache.live_frames(0) == oracle.live_frames(0)
+        assert_parity8(H.to_bits(out), oracle.attn(0), _v_absmax(oracle, 0), f"{w.name} fp8 after prefill {i}")
+        f0 += w.chunk_frames
+    cache.close()
+
+
+def test_recache_prefill_fp8():
+    _prefill_case8(MID128, True, 3, 9, pre_chunks=4)
+    _prefill_case8(MID128, True, 177, 9, pre_chunks=60)
+    _prefill_case8(MID128, False, 15, 9, pre_chunks=8)
+    _prefill_case8(ODD128, True, 8, 7, pre_chunks=5)
+    _prefill_case8(ODD64, True, 12, 6, pre_chunks=6)
+    _prefill_case8(NOSINK, True, 10, 9, pre_chunks=10)
+    _prefill_case8(HEADS6, True, 20, 8, pre_chunks=4)
+
+
+@pytest.mark.parametrize("idx", range(8))
+def test_random_geometries_fp8(idx):
+    rng = np.random.default_rng(4200 + idx)
+    w = _random_workload(rng, idx)
+    _stream_and_check8(w, w.n_chunks, short_last=bool(idx % 2))
+    if w.window_frames + w.chunk_frames >= 2:
+        n_win = int(rng.integers(1, w.window_frames + w.chunk_frames + 1))
+        ws = w.sink_frames + int(rng.integers(0, 40))
+        pre = (w.sink_frames + w.chunk_frames - 1) // w.chunk_frames + 1
+        _prefill_case8(w, bool(idx % 3), ws, n_win, pre_chunks=pre)
+
+
+def test_dead_slots_may_hold_nan_fp8():
+    """NaN inputs leave extreme codes in the cache; once their frames have left the key set they have no influence."""
+    w = ODD128
+    cache, oracle = make_cache8(w), Fp8Oracle(H.oracle_cfg(w))
+    f0, n_chunks = 0, 7
+    for i in range(n_chunks):
+        n = 1 if i == n_chunks - 1 else w.chunk_frames
+        q, k, v = synth.chunk_qkv(w, 0, i, n)
+        kg, vg = k, v
+        if i == 3:
+            kg, vg = np.full_like(k, 0x7FC0), np.full_like(v, 0x7FC0)
+        qd, kd, vd = H.to_dev(q), H.to_dev(kg), H.to_dev(vg)
+        qr, out = torch.empty(qd.shape, dtype=torch.uint8, device="cuda"), torch.empty_like(qd)
+        cache.chunk_append(0, f0, n, qd, kd, vd, qr)
+        cache.sink_window_attn(0, qr, out)
+        torch.cuda.synchronize()
+        oracle.append(0, f0, q, k, v)                                  # the oracle never sees the NaNs ...
+        live = oracle.live_frames(0)
+        if not any(9 <= f < 12 for f in live):                         # ... and is compared only without them
+            assert_parity8(H.to_bits(out), oracle.attn(0), _v_absmax(oracle, 0), f"chunk {i}")
+        f0 += n
+    assert not any(9 <= f < 12 for f in live)
+    cache.close()
+
+
+def test_wan_layer_sampled_rows_fp8():
+    """The benchmark's layer shape (12 heads x 128, 1560 tokens per frame): warm-up and steady state, sampled rows."""
+    w = synth.WAN_LAYER
+    cache, oracle = make_cache8(w), Fp8Oracle(H.oracle_cfg(w))
+    for i in range(6):
+        q, k, v = synth.chunk_qkv(w, 0, i)
+        qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+        qr, out = torch.empty(qd.shape, dtype=torch.uint8, device="cuda"), torch.empty_like(qd)
+        cache.chunk_append(0, 3 * i, 3, qd, kd, vd, qr)
+        cache.sink_window_attn(0, qr, out)
+        torch.cuda.synchronize()
+        oracle.append(0, 3 * i, q, k, v)
+        assert cache.live_frames(0) == oracle.live_frames(0)
+        rnd = np.random.default_rng(100 + i).choice(w.chunk_tokens, size=60, replace=False)
+        rows = np.unique(np.concatenate([rnd, [0, 1, w.chunk_tokens - 2, w.chunk_tokens - 1]]))
+        got = H.to_bits(out[torch.from_numpy(rows).cuda()])
+        m = assert_parity8(got, oracle.attn(0, rows=rows), _v_absmax(oracle, 0), f"wan layer fp8 chunk {i}")
+        print(f"chunk {i}: max_abs {m[0]:.3e} rel_l2 {m[1]:.3e}")
+    check_frame8(cache, oracle, w, 0, 0)
+    check_frame8(cache, oracle, w, 0, 17)
+    cache.close()
+
+
+def test_fp8_argument_errors():
+    w = MID128
+    with pytest.raises(B.LongLiveError) as e:
+        make_cache8(w, k_exp=40)
+    assert e.value.status == B.LL_ERR_INVALID_ARG
+    cache = make_cache8(w)
+    shape = (w.chunk_tokens, w.heads, w.head_dim)
+    q = torch.zeros(shape, dtype=torch.bfloat16, device="cuda")
+    with pytest.raises(B.LongLiveError) as e:
+        cache.chunk_append(0, 0, w.chunk_frames, q, q, q, q)          # E4M3 q_out over the bf16 q
+    assert e.value.status == B.LL_ERR_INVALID_ARG
+    assert cache.live_frames(0) == []
+    cache.close()
