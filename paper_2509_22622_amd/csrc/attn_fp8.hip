@@ -291,6 +291,287 @@ __device__ __forceinline__ void f8_segment(const AttnParams& p, const AttnChunk&
     st.l = lsum0 + lsum1;
 }
 
+// LDS reads the compiler does not see, with hand-counted waits (see f8_segment_sp).
+__device__ __forceinline__ void f8_lds_read(u32x4& dst, unsigned addr, int offset) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(offset));
+}
+template <int N>
+__device__ __forceinline__ void f8_lds_wait(u32x4& x, u32x4& y) {
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(x), "+v"(y) : "n"(N));
+}
+
+// The same computation as f8_segment as an explicit pipeline.  A step (one kblock of 64 keys) is NSLOT = D/16
+// slots, each opened by one MFMA:
+//     first  2*D/64 slots: S^T of kblock I + 1 (row block R, feature half dh), with the softmax weights of
+//                          kblock I behind them (per slot: exp2 of 32/NK scores, their sum, their conversion
+//                          to E4M3 into the P8^T operand);
+//     then   D/32   slots: O^T += V8^T P8^T of kblock I, with the running maximum of the new scores behind them.
+// Operand fragments (two 16-byte LDS reads each) are read two slots before their MFMA into four rotating
+// register buffers (buffer = slot mod 4), so a read never lands in registers an MFMA issued less than two slots
+// ago may still be reading.  The reads are inline asm; the LDS returns in order, and exactly one fragment (two
+// reads) is issued between a fragment's own reads and its use, so every MFMA is preceded by s_waitcnt lgkmcnt(2).
+// Ring, direct-to-LDS loads, waits and barriers are those of attn_stream.hip (lds_plan.h: a pair of steps reads
+// kblocks i .. i+2 here, inside the i .. i+3 that plan covers).  Kblocks that a range boundary may cut run
+// through the general form of the step one at a time, all others in aligned pairs through a form with no
+// masking logic.
+template <int D>
+__device__ __forceinline__ void f8_segment_sp(const AttnParams& p, const AttnChunk& ch, int head, int q0, char* lds, F8State<D>& st) {
+    constexpr int DH = D / 64;
+    constexpr int DB = D / 32;
+    constexpr int NK = 2 * DH;                  // S^T slots
+    constexpr int NSLOT = NK + DB;
+    constexpr int KB_BYTES = KBLOCK8 * D;
+    constexpr int STAGE_BYTES = 2 * KB_BYTES;
+    constexpr int NS = RingPlan::STAGES;
+    constexpr int NF = STAGE_BYTES / 1024;
+    constexpr int NW = 8;
+    constexpr int LPW = NF / NW;
+    constexpr int PF = RingPlan::AHEAD;
+    constexpr int LAND = RingPlan::LANDED;
+    constexpr int QPS = 8 / NK;                 // score quads converted per S^T slot
+    constexpr int MPS = 32 / DB;                // scores entering the running maximum per O^T slot
+    constexpr int DMA_STEP = NSLOT / LPW, DMA_FIRST = DMA_STEP - 1;
+    static_assert(NF % NW == 0 && 8 % NK == 0 && NSLOT % 4 == 0, "step shape");
+    static_assert(PF >= LAND && PF + 2 <= NS, "ring too short for the prefetch distance");
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int col = lane & 31, half = lane >> 5;
+
+    const int n_ranges = ch.n_ranges;
+    const int rs0 = ch.rs[0], re0 = ch.re[0];
+    int rs1 = ch.rs[1], re1 = ch.re[1], rs2 = ch.rs[2], re2 = ch.re[2];
+    if (n_ranges < 2) rs1 = re1 = 0;
+    if (n_ranges < 3) rs2 = re2 = 0;
+    const int kb0 = rs0 / KBLOCK8, ke0 = (re0 + KBLOCK8 - 1) / KBLOCK8;
+    const int kb1 = rs1 / KBLOCK8, ke1 = (re1 + KBLOCK8 - 1) / KBLOCK8;
+    const int kb2 = rs2 / KBLOCK8, ke2 = (re2 + KBLOCK8 - 1) / KBLOCK8;
+    const int q_end = ch.q_end;
+    const int T = (ke0 - kb0) + (ke1 - kb1) + (ke2 - kb2);
+    const int n0 = ke0 - kb0, n01 = n0 + (ke1 - kb1);
+    const int vb = 0, ve = T;
+#define F8_PHYS_KB(v) ((v) + f8_pick((v), n0, n01, kb0, kb1 - n0, kb2 - n01))
+#define F8_LIVE(v) f8_live_mask(F8_PHYS_KB(v) * KBLOCK8, f8_pick((v), n0, n01, rs0, rs1, rs2), f8_pick((v), n0, n01, re0, re1, re2), half)
+
+    i32x8 qf[DH];
+    {
+        const int row = min(q0 + col, q_end - 1);
+        const uint8_t* src = p.q8 + (int64_t(row) * p.H + head) * D + half * 32;
+#pragma unroll
+        for (int dh = 0; dh < DH; ++dh)
+            qf[dh] = f8_join(*reinterpret_cast<const u32x4*>(src + dh * 64), *reinterpret_cast<const u32x4*>(src + dh * 64 + 16));
+    }
+
+    const char* kbase = reinterpret_cast<const char*>(p.k8_cache + head * p.head_stride);
+    const char* vbase = reinterpret_cast<const char*>(p.v8_cache + head * p.head_stride);
+    const unsigned lane_off = lane * 16;
+    const unsigned lds_a = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds + lane_off;
+    auto issue_load = [&](int kb, int stage, int l) {
+        const int64_t kb_off = int64_t(kb) * KB_BYTES;
+        const int f = wave + NW * l;
+        const char* sbase = (f < NF / 2 ? kbase + f * 1024 : vbase + (f - NF / 2) * 1024) + kb_off;
+        const char* src = sbase + lane_off;
+        char* dst = lds + stage * STAGE_BYTES + f * 1024;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),
+                                         (__attribute__((address_space(3))) void*)(dst), 16, 0, 0);
+    };
+
+#pragma unroll
+    for (int j = 0; j < PF; ++j) {
+        const int v = min(vb + j, ve - 1);
+#pragma unroll
+        for (int l = 0; l < LPW; ++l) issue_load(F8_PHYS_KB(v), (vb + j) & (NS - 1), l);
+    }
+    f8_wait_vmcnt<(PF - LAND) * LPW>();
+    __builtin_amdgcn_s_barrier();
+
+    auto mask_s = [&](f32x16 (&s)[2], unsigned live) {
+#pragma unroll
+        for (int b = 0; b < 32; ++b)
+            if (!((live >> b) & 1)) s[b >> 4][b & 15] = -INFINITY;
+    };
+    auto max_s = [&](const f32x16 (&s)[2]) {
+        float m = fmaxf(s[0][0], s[1][0]);
+#pragma unroll
+        for (int r = 1; r < 16; ++r) m = fmaxf(fmaxf(m, s[0][r]), s[1][r]);
+        return m;
+    };
+
+    float lsum0 = 0.f, lsum1 = 0.f;
+    float mref;
+    f32x16 negm;
+    float mx;
+    f32x16 sA[2], sB[2];
+    u32x4 fr[4][2];                              // rotating operand buffers: slot j uses fr[j % 4]
+    unsigned vmask[8];                           // byte masks of the V8^T operand of a kblock cut by a range boundary
+
+    // ---- prologue: scores of kblock vb and the first reference (plain reads: consumed here, nothing is pending
+    // at the loop head), then the reads of the first two slots
+    {
+        float zero = 0.f;
+        asm volatile("" : "+v"(zero));
+#pragma unroll
+        for (int db = 0; db < DB; ++db)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) st.o[db][r] = 0.f;
+        const char* kt = lds + (vb & (NS - 1)) * STAGE_BYTES + lane_off;
+#pragma unroll
+        for (int R = 0; R < 2; ++R) {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sA[R][r] = zero;
+#pragma unroll
+            for (int dh = 0; dh < DH; ++dh) {
+                const char* kp = kt + ((R * DH + dh) * 2) * 1024;
+                sA[R] = f8_mfma(f8_join(*reinterpret_cast<const u32x4*>(kp), *reinterpret_cast<const u32x4*>(kp + 1024)), qf[dh], sA[R]);
+            }
+        }
+        mask_s(sA, F8_LIVE(vb));
+        const float m = max_s(sA);
+        mref = fmaxf(m, __shfl_xor(m, 32));
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            negm[r] = F8_SHIFT - mref;
+            sA[0][r] += F8_SHIFT - mref;
+            sA[1][r] += F8_SHIFT - mref;
+        }
+        mx = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) vmask[j] = 0xFFFFFFFFu;
+    }
+    // fragment of slot j of the step whose S^T kblock is stage `ks` and whose O^T kblock is stage `vs`
+#define F8_READ_FRAG(J, KT_A, VT_A)                                                                                 \
+    {                                                                                                               \
+        if ((J) < NK) {                                                                                             \
+            f8_lds_read(fr[(J) % 4][0], (KT_A), ((J) * 2) * 1024);                                                  \
+            f8_lds_read(fr[(J) % 4][1], (KT_A), ((J) * 2 + 1) * 1024);                                              \
+        } else {                                                                                                    \
+            f8_lds_read(fr[(J) % 4][0], (VT_A), (((J) - NK) * 2) * 1024);                                           \
+            f8_lds_read(fr[(J) % 4][1], (VT_A), (((J) - NK) * 2 + 1) * 1024);                                       \
+        }                                                                                                           \
+    }
+    {
+        const unsigned kt_a = lds_a + ((vb + 1) & (NS - 1)) * STAGE_BYTES;
+        const unsigned vt_a = lds_a + (vb & (NS - 1)) * STAGE_BYTES + KB_BYTES;
+        F8_READ_FRAG(0, kt_a, vt_a)
+        F8_READ_FRAG(1, kt_a, vt_a)
+    }
+
+#define F8_PIN(x) asm volatile("" ::"v"(x))
+#define F8_STEP(I, S_CUR, S_NEXT, EDGE, BAR)                                                                        \
+    {                                                                                                               \
+        const bool edge = EDGE && (I) == next_edge;                                                                 \
+        if (__builtin_expect(edge || vote, 0)) {                                                                    \
+            if (edge) {                                                                                             \
+                const unsigned live = F8_LIVE(I);                                                                   \
+                next_edge = f8_next_edge((I), n0, n01, T);                                                          \
+                mask_s(S_CUR, live);                                                                                \
+                mx = max_s(S_CUR);                                                                                  \
+                _Pragma("unroll") for (int j = 0; j < 8; ++j) {                                                     \
+                    const unsigned b4 = (live >> (4 * j)) & 0xF;                                                    \
+                    vmask[j] = ((b4 & 1) ? 0xFFu : 0u) | ((b4 & 2) ? 0xFF00u : 0u) | ((b4 & 4) ? 0xFF0000u : 0u) |  \
+                               ((b4 & 8) ? 0xFF000000u : 0u);                                                       \
+                }                                                                                                   \
+            }                                                                                                       \
+            const float delta = fmaxf(fmaxf(mx, __shfl_xor(mx, 32)) - F8_SHIFT, 0.f);                               \
+            const float alpha = __builtin_amdgcn_exp2f(-delta);                                                     \
+            mref += delta;                                                                                          \
+            lsum0 *= alpha;                                                                                         \
+            lsum1 *= alpha;                                                                                         \
+            _Pragma("unroll") for (int db = 0; db < DB; ++db)                                                       \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;                                \
+            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                        \
+                negm[r] -= delta;                                                                                   \
+                S_CUR[0][r] -= delta;                                                                               \
+                S_CUR[1][r] -= delta;                                                                               \
+            }                                                                                                       \
+        }                                                                                                           \
+        const unsigned kt_a = lds_a + (((I) + 1) & (NS - 1)) * STAGE_BYTES;            /* K8 of kblock I + 1 */      \
+        const unsigned vt_a = lds_a + ((I) & (NS - 1)) * STAGE_BYTES + KB_BYTES;       /* V8 of kblock I     */      \
+        const unsigned kn_a = lds_a + (((I) + 2) & (NS - 1)) * STAGE_BYTES;            /* K8 of kblock I + 2 */      \
+        i32x8 pb;                                                                                                   \
+        float m_run = -INFINITY;                                                                                    \
+        _Pragma("unroll") for (int k = 0; k < NSLOT; ++k) {                                                         \
+            if (k == 0) __builtin_amdgcn_s_setprio(1);                                                              \
+            if (k == NK) __builtin_amdgcn_s_setprio(0);                                                             \
+            f8_lds_wait<2>(fr[k % 4][0], fr[k % 4][1]);                                                             \
+            if (k < NK) {                                                                                           \
+                const int R = k / DH, dh = k % DH;                                                                  \
+                S_NEXT[R] = f8_mfma(f8_join(fr[k % 4][0], fr[k % 4][1]), qf[dh], dh == 0 ? negm : S_NEXT[R]);       \
+            } else {                                                                                                \
+                const int db = k - NK;                                                                              \
+                if (EDGE && edge) {                                                                                 \
+                    _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                 \
+                        fr[k % 4][0][j] &= vmask[j];                                                                \
+                        fr[k % 4][1][j] &= vmask[4 + j];                                                            \
+                    }                                                                                               \
+                }                                                                                                   \
+                st.o[db] = f8_mfma(f8_join(fr[k % 4][0], fr[k % 4][1]), pb, st.o[db]);                              \
+            }                                                                                                       \
+            if (k >= DMA_FIRST && (k - DMA_FIRST) % DMA_STEP == 0 && (k - DMA_FIRST) / DMA_STEP < LPW) {            \
+                const int v = min((I) + PF, ve - 1);                                                                \
+                issue_load(F8_PHYS_KB(v), ((I) + PF) & (NS - 1), (k - DMA_FIRST) / DMA_STEP);                       \
+            }                                                                                                       \
+            /* the fragment of the slot after next (the first two slots of the next step read kblock I + 2) */      \
+            if (k + 2 < NSLOT) F8_READ_FRAG(k + 2, kt_a, vt_a)                                                      \
+            else F8_READ_FRAG(k + 2 - NSLOT, kn_a, vt_a)                                                            \
+            if (k < NK) {                                                                                           \
+                _Pragma("unroll") for (int g = k * QPS; g < (k + 1) * QPS; ++g) {                                   \
+                    const int R = g / 4, r = 4 * (g % 4);                                                           \
+                    const float e0 = __builtin_amdgcn_exp2f(S_CUR[R][r]), e1 = __builtin_amdgcn_exp2f(S_CUR[R][r + 1]);     \
+                    const float e2 = __builtin_amdgcn_exp2f(S_CUR[R][r + 2]), e3 = __builtin_amdgcn_exp2f(S_CUR[R][r + 3]); \
+                    lsum0 += e0;                                                                                    \
+                    lsum1 += e1;                                                                                    \
+                    lsum0 += e2;                                                                                    \
+                    lsum1 += e3;                                                                                    \
+                    int w = __builtin_amdgcn_cvt_pk_fp8_f32(e0, e1, 0, false);                                      \
+                    w = __builtin_amdgcn_cvt_pk_fp8_f32(e2, e3, w, true);                                           \
+                    pb[g] = w;                                                                                      \
+                    F8_PIN(w);                                                                                      \
+                    F8_PIN(lsum0);                                                                                  \
+                    F8_PIN(lsum1);                                                                                  \
+                }                                                                                                   \
+            } else {                                                                                                \
+                _Pragma("unroll") for (int b = (k - NK) * MPS; b < (k - NK + 1) * MPS; b += 2)                      \
+                    m_run = fmaxf(fmaxf(m_run, S_NEXT[b >> 4][b & 15]), S_NEXT[b >> 4][(b & 15) + 1]);              \
+            }                                                                                                       \
+            __builtin_amdgcn_sched_barrier(0);                                                                      \
+        }                                                                                                           \
+        mx = m_run;                                                                                                 \
+        vote = __any(mx > F8_SHIFT + F8_SLACK);                                                                     \
+        if (EDGE && edge) {                                                                                         \
+            _Pragma("unroll") for (int j = 0; j < 8; ++j) vmask[j] = 0xFFFFFFFFu;                                   \
+        }                                                                                                           \
+        if (BAR == 1 || (BAR == 2 && RingPlan::barrier_after((I) - vb))) {                                          \
+            f8_wait_vmcnt<(PF - LAND) * LPW>();                                                                     \
+            __builtin_amdgcn_s_barrier();                                                                           \
+        }                                                                                                           \
+    }
+
+    int next_edge = f8_next_edge(vb - 1, n0, n01, T);
+    bool vote = false;
+    int i = vb;
+    while (i < ve) {
+        while (i < ve && (((i - vb) & 1) || i + 1 >= ve || i == next_edge || i + 1 == next_edge)) {
+            F8_STEP(i, sA, sB, 1, 2)
+#pragma unroll
+            for (int R = 0; R < 2; ++R) sA[R] = sB[R];
+            ++i;
+        }
+        for (int n = (min(ve, next_edge) - i) >> 1; n > 0; --n) {
+            F8_STEP(i, sA, sB, 0, 0)
+            F8_STEP(i + 1, sB, sA, 0, 1)
+            i += 2;
+        }
+    }
+#undef F8_STEP
+#undef F8_PIN
+#undef F8_READ_FRAG
+#undef F8_PHYS_KB
+#undef F8_LIVE
+    __builtin_amdgcn_s_waitcnt(0);
+    st.l = lsum0 + lsum1;
+}
+
 // A wave without queries in a chunk's short last tile: its share of the loads, waits and barriers only.
 template <int D>
 __device__ __forceinline__ void f8_segment_loads_only(const AttnParams& p, const AttnChunk& ch, int head, char* lds) {
@@ -360,7 +641,7 @@ __device__ __forceinline__ void f8_store_out(const AttnParams& p, int head, int 
 }
 
 // ---- one workgroup per (head, query tile); placement on the XCDs as in attn_stream.hip
-template <int D>
+template <int D, bool PIPE>
 __global__ __launch_bounds__(F8_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_attn_fp8_kernel(const AttnParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -396,13 +677,16 @@ __global__ __launch_bounds__(F8_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
         return;
     }
     F8State<D> st;
-    f8_segment<D>(p, ch, head, q0, lds, st);
+    if (PIPE) f8_segment_sp<D>(p, ch, head, q0, lds, st);
+    else f8_segment<D>(p, ch, head, q0, lds, st);
     f8_store_out<D>(p, head, q0, ch.q_end, st);
 }
 
 const AttnVariant kFp8Variants[] = {
-    {"d128_fp8", 128, 256, 8 * 2 * KBLOCK8 * 128, ll_attn_fp8_kernel<128>, F8_THREADS, KBLOCK8},
-    {"d64_fp8", 64, 256, 8 * 2 * KBLOCK8 * 64, ll_attn_fp8_kernel<64>, F8_THREADS, KBLOCK8},
+    {"d128_fp8", 128, 256, 8 * 2 * KBLOCK8 * 128, ll_attn_fp8_kernel<128, true>, F8_THREADS, KBLOCK8},
+    {"d64_fp8", 64, 256, 8 * 2 * KBLOCK8 * 64, ll_attn_fp8_kernel<64, true>, F8_THREADS, KBLOCK8},
+    {"d128_fp8_simple", 128, 256, 8 * 2 * KBLOCK8 * 128, ll_attn_fp8_kernel<128, false>, F8_THREADS, KBLOCK8},
+    {"d64_fp8_simple", 64, 256, 8 * 2 * KBLOCK8 * 64, ll_attn_fp8_kernel<64, false>, F8_THREADS, KBLOCK8},
 };
 const int kNumFp8Variants = sizeof(kFp8Variants) / sizeof(kFp8Variants[0]);
 

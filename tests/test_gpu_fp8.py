@@ -114,6 +114,18 @@ def test_small_shapes_every_element_fp8(w):
     _stream_and_check8(w, w.n_chunks)
 
 
+@pytest.mark.parametrize("name,w", [("d128_fp8_simple", WIDE), ("d128_fp8_simple", ODD128), ("d64_fp8_simple", ODD64)],
+                         ids=lambda x: getattr(x, "name", x))
+def test_simple_fp8_variants(name, w):
+    """The compiler-scheduled form of the kernel, kept as a cross-check of the hand-pipelined default."""
+    ids = {n: v for v, n in B.attn_variant_names().items()}
+    B.set_attn_variant(ids[name])
+    try:
+        _stream_and_check8(w, 6, check_cache=False)
+    finally:
+        B.set_attn_variant(0)
+
+
 def test_exponents_fp8():
     """Power-of-two scales: k_exp moves K' down and q' up by the same factor, v_exp comes back on the output."""
     _stream_and_check8(MID128, 5, k_exp=2, v_exp=-3)
