@@ -20,8 +20,10 @@
 //
 // The scaled form of the MFMA is used with both scales 1 (E8M0 code 127).  The compiler may place its result on
 // top of an operand that dies at the instruction, which this multi-pass instruction does not tolerate (wrong
-// numbers, seen on the GPU): f8_mfma keeps both operands alive past it, and tests/test_fp8_mfma_operands.py
-// checks the generated code for such overlaps.
+// numbers, seen on the GPU): f8_mfma keeps both operands alive, together with the result, past the instruction, and
+// tests/test_fp8_mfma_operands.py checks the generated code for such overlaps.  The same test checks that nothing
+// is spilled: the hand-issued LDS reads below leave their destination registers pending, and a spill or copy of
+// such a register before the counted wait would store stale data.
 #include "kernels.h"
 #include "lds_plan.h"
 
@@ -47,8 +49,9 @@ __device__ __forceinline__ void f8_wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
 }
 __device__ __forceinline__ f32x16 f8_mfma(const i32x8& a, const i32x8& b, const f32x16& c) {
-    const f32x16 d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
-    asm volatile("" ::"v"(a), "v"(b));           // both operands outlive the instruction: the result cannot land on them
+    f32x16 d = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0x7F7F7F7F, 0, 0x7F7F7F7F);
+    // result and both operands are alive together here, after the instruction: the result cannot be placed on them
+    asm volatile("" : "+v"(d) : "v"(a), "v"(b));
     return d;
 }
 __device__ __forceinline__ i32x8 f8_join(const u32x4& lo, const u32x4& hi) {

@@ -30,3 +30,22 @@ def test_no_result_over_operand():
         assert d[1] < a[0] or a[1] < d[0], f"result v[{d0}:{d1}] overlaps operand A v[{a0}:{a1}]"
         assert d[1] < b[0] or b[1] < d[0], f"result v[{d0}:{d1}] overlaps operand B v[{b0}:{b1}]"
         assert c.startswith("v["), f"accumulator input is not a register tuple: {c}"
+    # the pipelined kernels issue LDS reads whose destination registers stay pending until a counted wait: a spill
+    # of such a register in between would store stale data, so these kernels must not spill at all
+    spills = dict(re.findall(r"\.name:\s+(\S+)[\s\S]*?\.vgpr_spill_count:\s+(\d+)", text))
+    piped = {k: int(v) for k, v in spills.items() if "ll_attn_fp8_kernel" in k and "ELb1E" in k}
+    assert len(piped) == 2 and all(v == 0 for v in piped.values()), f"spills in the pipelined kernels: {piped}"
+
+
+def test_bf16_stream_kernels_do_not_spill():
+    """The bf16 software-pipelined kernels use the same pending LDS reads: they must not spill either."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    src = os.path.join(ROOT, "paper_2509_22622_amd", "csrc", "attn_stream.hip")
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "attn_stream.s")
+        subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                        "-packed-fp32-ops", "-S", "--cuda-device-only", src, "-o", out], check=True, capture_output=True)
+        text = open(out).read()
+    spills = dict(re.findall(r"\.name:\s+(\S+)[\s\S]*?\.vgpr_spill_count:\s+(\d+)", text))
+    stream = {k: int(v) for k, v in spills.items() if "ll_attn_stream_kernel" in k}
+    assert len(stream) == 2 and all(v == 0 for v in stream.values()), f"spills: {stream}"
