@@ -62,16 +62,19 @@ def cpu_baseline(w, chunks=3):
             "seconds": t_append + t_attn, "affinity_cores": len(os.sched_getaffinity(0)), "os_cpu_count": os.cpu_count()}
 
 
-def single_layer_stats(w, gen, warmup=10, iters=50):
+PEAK_FP8_TFLOPS = 2 * PEAK_BF16_TFLOPS      # dense fp8 MFMA peak (published: 5.0 PFLOP/s)
+
+
+def single_layer_stats(w, gen, warmup=10, iters=50, kv_format="bf16"):
     """Attention launch times of one layer in steady state: median, p10, p90 over `iters` launches (HIP events)."""
     import torch
     from paper_2509_22622_amd import binding
     Hh, D, Cf = w.heads, w.head_dim, w.chunk_frames
     nq = w.chunk_tokens
     nk = (w.sink_frames + w.window_frames + Cf) * w.tokens_per_frame
-    cache = binding.Cache(1, Hh, D, w.grid_h, w.grid_w, Cf, w.sink_frames, w.window_frames)
+    cache = binding.Cache(1, Hh, D, w.grid_h, w.grid_w, Cf, w.sink_frames, w.window_frames, kv_format=kv_format)
     q, k, v = (torch.randn((nq, Hh, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16) for _ in range(3))
-    qr, out = torch.empty_like(q), torch.empty_like(q)
+    qr, out = torch.empty(q.shape, dtype=torch.bfloat16 if kv_format == "bf16" else torch.uint8, device="cuda"), torch.empty_like(q)
     for c in range((w.sink_frames + w.window_frames) // Cf + 2):
         cache.chunk_append(0, c * Cf, Cf, q, k, v, qr)
     assert sum(b - a for a, b in cache.live_ranges(0)) == nk
@@ -87,9 +90,99 @@ def single_layer_stats(w, gen, warmup=10, iters=50):
     med = ms[len(ms) // 2]
     fl = attn_flops(nq, nk, D, Hh)
     cache.close()
-    return {"workload": f"{w.name}: {nq} queries x {nk} keys x {Hh} heads x {D}", "launches": iters,
-            "ms_median": round(med, 4), "ms_p10": round(ms[len(ms) // 10], 4), "ms_p90": round(ms[(len(ms) * 9) // 10], 4),
-            "TFLOP/s": round(fl / (med * 1e-3) / 1e12, 1), "pct_of_bf16_mfma_peak": round(100 * fl / (med * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2)}
+    res = {"workload": f"{w.name}: {nq} queries x {nk} keys x {Hh} heads x {D}", "launches": iters,
+           "ms_median": round(med, 4), "ms_p10": round(ms[len(ms) // 10], 4), "ms_p90": round(ms[(len(ms) * 9) // 10], 4),
+           "TFLOP/s": round(fl / (med * 1e-3) / 1e12, 1)}
+    if kv_format == "bf16":
+        res["pct_of_bf16_mfma_peak"] = round(100 * fl / (med * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2)
+    else:
+        res["pct_of_fp8_mfma_peak"] = round(100 * fl / (med * 1e-3) / 1e12 / PEAK_FP8_TFLOPS, 2)
+    return res
+
+
+def fp8_cache_stats(w_loop, gen, q, k, v, steps, only_step=False):
+    """The 8-bit (E4M3) cache variant: a different accuracy tier, reported next to the bf16 figures and never as
+    `value`.  Single-layer launch statistics, the 30-layer chunk step (append + attention, wall clock), and the
+    distance between the two paths' outputs on the same inputs."""
+    import torch
+    from paper_2509_22622_amd import binding, synth
+    w = w_loop
+    L, Hh, D, Cf = w.layers, w.heads, w.head_dim, w.chunk_frames
+    nq = w.chunk_tokens
+    nk = (w.sink_frames + w.window_frames + Cf) * w.tokens_per_frame
+    res = {"what": "K', V and q' held as 8-bit floating point (OCP E4M3), both products on the fp8 MFMA: reduced "
+                   "precision, not the benchmark's metric"}
+    if not only_step:
+        res["single_layer"] = {"cfg2": single_layer_stats(synth.WAN_LAYER, gen, kv_format="fp8_e4m3"),
+                               "cfg4": single_layer_stats(synth.LONG_WINDOW, gen, kv_format="fp8_e4m3")}
+        res.update(_fp8_vs_bf16(q, k, v, L, Hh, D, Cf))
+    return _fp8_step(res, w, q, k, v, steps)
+
+
+def _fp8_vs_bf16(q, k, v, L, Hh, D, Cf):
+    """Distance between the two paths' outputs: one layer, six chunks streamed into both kinds of cache."""
+    import torch
+    from paper_2509_22622_amd import binding, synth
+    res = {}
+    wl = synth.WAN_LAYER
+    ca = binding.Cache(1, Hh, D, wl.grid_h, wl.grid_w, Cf, wl.sink_frames, wl.window_frames)
+    cb = binding.Cache(1, Hh, D, wl.grid_h, wl.grid_w, Cf, wl.sink_frames, wl.window_frames, kv_format="fp8_e4m3")
+    qa, oa = torch.empty_like(q[0, 0]), torch.empty_like(q[0, 0])
+    qb, ob = torch.empty(q[0, 0].shape, dtype=torch.uint8, device="cuda"), torch.empty_like(q[0, 0])
+    for c in range(6):
+        i, l = c % q.shape[0], c % L
+        ca.chunk_append(0, c * Cf, Cf, q[i, l], k[i, l], v[i, l], qa)
+        cb.chunk_append(0, c * Cf, Cf, q[i, l], k[i, l], v[i, l], qb)
+    ca.sink_window_attn(0, qa, oa)
+    cb.sink_window_attn(0, qb, ob)
+    torch.cuda.synchronize()
+    d = (ob.float() - oa.float())
+    res["rel_l2_vs_bf16_path"] = round(float(d.norm() / oa.float().norm()), 5)
+    res["max_abs_vs_bf16_path"] = round(float(d.abs().max()), 5)
+    ca.close()
+    cb.close()
+    return res
+
+
+def _fp8_step(res, w, q, k, v, steps):
+    """The 30-layer chunk step (append + attention per layer) over the 8-bit cache, wall clock."""
+    import torch
+    from paper_2509_22622_amd import binding
+    L, Hh, D, Cf = w.layers, w.heads, w.head_dim, w.chunk_frames
+    nq = w.chunk_tokens
+    nk = (w.sink_frames + w.window_frames + Cf) * w.tokens_per_frame
+    cache = binding.Cache(L, Hh, D, w.grid_h, w.grid_w, Cf, w.sink_frames, w.window_frames, kv_format="fp8_e4m3")
+    res["cache_bytes"] = int(cache.buffer.numel())
+    qr = torch.empty((L, nq, Hh, D), dtype=torch.uint8, device="cuda")
+    out = torch.empty((L, nq, Hh, D), dtype=torch.bfloat16, device="cuda")
+    chunk = 0
+    pool = q.shape[0]
+
+    def step(attn=True):
+        nonlocal chunk
+        f0, i = chunk * Cf, chunk % pool
+        for l in range(L):
+            cache.chunk_append(l, f0, Cf, q[i, l], k[i, l], v[i, l], qr[l])
+            if attn:
+                cache.sink_window_attn(l, qr[l], out[l])
+        chunk += 1
+
+    for _ in range((w.sink_frames + w.window_frames) // Cf + 1):
+        step(attn=False)
+    for _ in range(2):
+        step()
+    assert sum(b - a for a, b in cache.live_ranges(0)) == nk
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) / steps * 1e3
+    fl = attn_flops(nq, nk, D, Hh) * L
+    res["step_30_layers"] = {"ms_per_step": round(ms, 4), "TFLOP/s": round(fl / (ms * 1e-3) / 1e12, 1),
+                             "pct_of_fp8_mfma_peak": round(100 * fl / (ms * 1e-3) / 1e12 / PEAK_FP8_TFLOPS, 2), "steps": steps}
+    cache.close()
+    return res
 
 
 def main():
@@ -100,6 +193,9 @@ def main():
     ap.add_argument("--variant", type=int, default=0, help="attention kernel variant (0 = default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-recache", action="store_true")
+    ap.add_argument("--no-fp8", action="store_true", help="leave out the figures of the 8-bit cache variant")
+    ap.add_argument("--fp8-only", action="store_true",
+                    help="only the 30-layer step over the 8-bit cache (for profiler runs: one launch shape)")
     ap.add_argument("--probe-issue", action="store_true",
                     help="only run the library's MFMA probe with each kind of companion instruction and print a table")
     ap.add_argument("--no-extras", action="store_true",
@@ -154,6 +250,9 @@ def main():
                 t[i, l] = torch.randn((nq, Hh, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
         return t
     q, k, v = gen_bf16(), gen_bf16(), gen_bf16()
+    if args.fp8_only:
+        print(json.dumps({"fp8_cache": fp8_cache_stats(w, gen, q, k, v, args.steps, only_step=True)}))
+        return
     qr = torch.empty((L, nq, Hh, D), dtype=torch.bfloat16, device="cuda")
     out = torch.empty((L, nq, Hh, D), dtype=torch.bfloat16, device="cuda")
 
@@ -307,6 +406,9 @@ def main():
                          "constant_operands": {"TFLOP/s": round(pc_t, 1), "clock_GHz": round(pc_c, 3)},
                          "workload": "256 workgroups x 8 waves, 32x32x16 bf16 MFMAs back to back",
                          "attn_kernel_vs_random_operand_probe": round(attn_tflops / pr_t, 4)}
+
+    if not args.no_fp8:
+        res["fp8_cache"] = fp8_cache_stats(w, gen, q, k, v, args.steps)
 
     if args.probe_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(3)
