@@ -287,3 +287,86 @@ def test_fp8_argument_errors():
     assert e.value.status == B.LL_ERR_INVALID_ARG
     assert cache.live_frames(0) == []
     cache.close()
+
+
+def _sample_rows(n_rows, seed, n=60):
+    rnd = np.random.default_rng(seed).choice(n_rows, size=n, replace=False)
+    return np.unique(np.concatenate([rnd, [0, 1, n_rows - 2, n_rows - 1]]))
+
+
+def _trim(oracle, layer, keep_from, sink):
+    """Drop frames the key-set rule can never select again (memory only)."""
+    com = oracle.layer[layer].committed
+    for f in [f for f in com if sink <= f < keep_from]:
+        del com[f]
+
+
+def test_recache_prefill_full_size_fp8():
+    """The recache workload (sink 3 + 12 window frames at a late position, 23400 queries, chunk-causal) over the
+    8-bit cache: sampled rows of every chunk, cache contents, and streaming on from the rebuilt cache."""
+    w = synth.RECACHE
+    P = w.tokens_per_frame
+    cache, oracle = make_cache8(w), Fp8Oracle(H.oracle_cfg(w))
+    layer, ws, n_win = 7, 165, 12
+    shape = ((3 + n_win) * P, w.heads, w.head_dim)
+    q, k, v = (synth.normal_bf16(shape, w.cfg_id, layer, 0, t) for t in "qkv")
+    qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+    out = torch.empty_like(qd)
+    cache.recache_prefill(layer, True, ws, n_win, qd, kd, vd, out)
+    torch.cuda.synchronize()
+    rows = _sample_rows(3 * P, 300)
+    want = oracle.recache_prefill(layer, True, ws, n_win, q, k, v, rows_per_chunk=rows)
+    idx = np.concatenate([c * 3 * P + rows for c in range(5)])
+    got = H.to_bits(out[torch.from_numpy(idx).cuda()])
+    assert_parity8(got, want, _v_absmax(oracle, layer), "recache prefill fp8")
+    assert cache.live_frames(layer) == oracle.live_frames(layer) == [0, 1, 2] + list(range(ws, ws + 12))
+    for f in (0, 2, ws + 3, ws + 11):
+        check_frame8(cache, oracle, w, layer, f)
+    q, k, v = synth.chunk_qkv(w, layer, 1)
+    qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+    qr, o2 = torch.empty(qd.shape, dtype=torch.uint8, device="cuda"), torch.empty_like(qd)
+    cache.chunk_append(layer, ws + n_win, 3, qd, kd, vd, qr)
+    cache.sink_window_attn(layer, qr, o2)
+    torch.cuda.synchronize()
+    oracle.append(layer, ws + n_win, q, k, v)
+    rows = _sample_rows(w.chunk_tokens, 301)
+    assert_parity8(H.to_bits(o2[torch.from_numpy(rows).cuda()]), oracle.attn(layer, rows=rows), _v_absmax(oracle, layer),
+                   "recache fp8 next chunk")
+    cache.close()
+
+
+def test_thirty_layer_loop_fp8():
+    """30 independent 8-bit layer caches, 12 consecutive chunks (the ring wraps twice), in the launch configuration
+    bench.py times: layers 0 and 29 are replayed by the oracle from the same bits and checked on sampled rows at
+    every chunk; live sets at every chunk; the footprint never changes."""
+    w = synth.WAN_LOOP
+    L, n_chunks = w.layers, 12
+    cache = make_cache8(w)
+    nbytes = cache.buffer.numel()
+    oracles = {l: Fp8Oracle(H.oracle_cfg(synth.WAN_LAYER)) for l in (0, 29)}
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(synth.MASTER_SEED + 8)
+    shape = (w.chunk_tokens, w.heads, w.head_dim)
+    qr = torch.empty(shape, dtype=torch.uint8, device="cuda")
+    out = torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    for i in range(n_chunks):
+        f0 = 3 * i
+        for l in range(L):
+            q, k, v = (torch.randn(shape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+                       for _ in range(3))
+            cache.chunk_append(l, f0, 3, q, k, v, qr)
+            cache.sink_window_attn(l, qr, out)
+            if l in oracles:
+                torch.cuda.synchronize()
+                o = oracles[l]
+                o.append(0, f0, H.to_bits(q), H.to_bits(k), H.to_bits(v))
+                assert cache.live_frames(l) == o.live_frames(0)
+                rows = _sample_rows(w.chunk_tokens, 1000 * l + i, n=28)
+                assert_parity8(H.to_bits(out[torch.from_numpy(rows).cuda()]), o.attn(0, rows=rows), _v_absmax(o, 0),
+                               f"fp8 loop layer {l} chunk {i}")
+                _trim(o, 0, f0 - w.window_frames, w.sink_frames)
+        if i >= 4:
+            assert sum(b - a for a, b in cache.live_ranges(L - 1)) == 15 * w.tokens_per_frame
+    torch.cuda.synchronize()
+    assert cache.buffer.numel() == nbytes
+    cache.close()
