@@ -7,19 +7,26 @@ import torch
 
 from paper_2509_22622_amd import binding as B
 from paper_2509_22622_amd import synth
+from oracle.fp8_cache import Fp8Oracle
 from oracle.longlive_oracle import Oracle
 
 import gpu_harness as H
+from test_gpu_fp8 import assert_parity8
 
 pytestmark = pytest.mark.gpu
 
 W = synth.Workload("graph-mid", 91, 3, 4, 128, 6, 10, 3, 3, 6, 8)
 
 
-def test_graph_replay_equals_eager_passes():
+@pytest.mark.parametrize("kv_format", ["bf16", "fp8_e4m3"])
+def test_graph_replay_equals_eager_passes(kv_format):
     P, C = W.tokens_per_frame, W.chunk_frames
-    eager, graphed = H.make_cache(W), H.make_cache(W)
-    oracle = Oracle(H.oracle_cfg(W))
+    fp8 = kv_format != "bf16"
+    make = (lambda: B.Cache(W.layers, W.heads, W.head_dim, W.grid_h, W.grid_w, C, W.sink_frames, W.window_frames,
+                            kv_format=kv_format))
+    eager, graphed = make(), make()
+    oracle = Fp8Oracle(H.oracle_cfg(W)) if fp8 else Oracle(H.oracle_cfg(W))
+    qdt = torch.uint8 if fp8 else torch.bfloat16            # rotated queries: E4M3 bytes in the 8-bit variant
     shape = (C * P, W.heads, W.head_dim)
     hist = 5
     for i in range(hist):                                   # same history in both caches (and the oracle, layer 0)
@@ -27,12 +34,12 @@ def test_graph_replay_equals_eager_passes():
             q, k, v = synth.chunk_qkv(W, l, i)
             qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
             for c in (eager, graphed):
-                c.chunk_append(l, i * C, C, qd, kd, vd, torch.empty_like(qd))
+                c.chunk_append(l, i * C, C, qd, kd, vd, torch.empty(qd.shape, dtype=qdt, device="cuda"))
             if l == 0:
                 oracle.append(0, i * C, q, k, v)
     f0 = hist * C
     sq, sk, sv = (torch.zeros((W.layers,) + shape, dtype=torch.bfloat16, device="cuda") for _ in range(3))
-    sqr, sout = torch.empty_like(sq), torch.empty_like(sq)
+    sqr, sout = torch.empty(sq.shape, dtype=qdt, device="cuda"), torch.empty_like(sq)
 
     def one_pass(cache, q, k, v, qr, out):
         for l in range(W.layers):
@@ -47,23 +54,27 @@ def test_graph_replay_equals_eager_passes():
     for rep in range(4):                                    # four denoising passes with fresh contents
         host = [synth.chunk_qkv(W, l, 100 + rep) for l in range(W.layers)]
         q, k, v = (torch.stack([H.to_dev(h[t]) for h in host]) for t in range(3))
-        qr, out = torch.empty_like(q), torch.empty_like(q)
+        qr, out = torch.empty(q.shape, dtype=qdt, device="cuda"), torch.empty_like(q)
         one_pass(eager, q, k, v, qr, out)                   # the program's own eager work between replays
         torch.cuda.synchronize()
         sq.copy_(q), sk.copy_(k), sv.copy_(v)
         g.replay()
         torch.cuda.synchronize()
         assert torch.equal(sout.view(torch.int16), out.view(torch.int16)), f"replay {rep}"
-        assert torch.equal(sqr.view(torch.int16), qr.view(torch.int16)), f"replay {rep}"
+        assert torch.equal(sqr, qr), f"replay {rep}"
         assert graphed.live_frames(0) == eager.live_frames(0)
         oracle.append(0, f0, *host[0])                      # same f0: overwrites the staged chunk
-        H.assert_parity(H.to_bits(sout[0]), oracle.attn(0), f"replay {rep} vs oracle")
+        if fp8:
+            vmax = max(np.abs(oracle.frame_kv(0, f)[1]).max() for f in oracle.live_frames(0))
+            assert_parity8(H.to_bits(sout[0]), oracle.attn(0), vmax, f"replay {rep} vs oracle")
+        else:
+            H.assert_parity(H.to_bits(sout[0]), oracle.attn(0), f"replay {rep} vs oracle")
     # the next chunk commits the staged one in both caches alike
     q, k, v = synth.chunk_qkv(W, 0, 200)
     qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
     outs = []
     for c in (eager, graphed):
-        qr, o = torch.empty_like(qd), torch.empty_like(qd)
+        qr, o = torch.empty(qd.shape, dtype=qdt, device="cuda"), torch.empty_like(qd)
         c.chunk_append(0, f0 + C, C, qd, kd, vd, qr)
         c.sink_window_attn(0, qr, o)
         outs.append(o)
