@@ -231,6 +231,13 @@ def main():
                     # a 32x32x16 MFMA holds the pipe 32 cycles: time per MFMA grows by 32 * (base / t - 1) cycles
                     lost = "" if kind == 7 else f"{32.0 * (base / t - 1.0) / per:8.2f}"
                     print(f"  {name:32s}    {per}      {t:8.1f}   {c:8.3f}   {t / base:7.3f}   {lost}")
+            print(f"  fp8 MFMAs (32x32x64, 64 cycles each), {'random E4M3 mantissas and signs' if random_ops else 'constant 1.0'}")
+            binding.probe_mfma_mix(8, 1, random_operands=random_ops)
+            base8 = None
+            for kind, name in binding.PROBE_FP8_KINDS.items():
+                t, c = binding.probe_mfma_mix(kind, 1, random_operands=random_ops)
+                base8 = base8 or t
+                print(f"  {name:58s} {t:8.1f}   {c:8.3f}   {t / base8:7.3f}")
         return
 
     w = synth.WAN_LOOP

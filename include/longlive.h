@@ -176,7 +176,10 @@ ll_status ll_probe_mfma_rate(void* dev_scratch, size_t scratch_bytes, int workgr
  * registers no MFMA touches: 0 none, 1 v_add_f32, 2 v_exp_f32, 3 v_cvt_pk_bf16_f32, 4 v_dot2c_f32_bf16,
  * 5 v_max3_f32, 6 ds_read_b128 (64 KB of LDS, conflict-free), 7 no companion but 16x16x32 MFMAs (twice as many,
  * the same flops).  The drop against companion 0 is what that instruction costs the matrix pipe in issue slots and,
- * with random operands, in power.  tflops counts the MFMA flops only.  Other arguments as above. */
+ * with random operands, in power.  tflops counts the MFMA flops only.  Other arguments as above.
+ * Companions 8 to 11 run fp8 MFMAs instead (32x32x64, E4M3 operands, four times the flops per instruction; per_mfma
+ * is ignored): 8 alone, 9 with what the 8-bit attention kernel issues per MFMA (4 v_exp_f32, 4 v_add_f32,
+ * 2 v_cvt_pk_fp8_f32, 2 v_max3_f32, 2 ds_read_b128), 10 with the vector part of that only, 11 with the LDS part only. */
 ll_status ll_probe_mfma_mix(void* dev_scratch, size_t scratch_bytes, int workgroups, int iters, int random_operands,
                             int companion, int per_mfma, double* tflops, double* clock_ghz, void* stream);
 

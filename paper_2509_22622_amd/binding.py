@@ -97,6 +97,8 @@ def probe_mfma_rate(workgroups: int = 256, iters: int = 20000, random_operands: 
 
 PROBE_COMPANIONS = {0: "none", 1: "v_add_f32", 2: "v_exp_f32", 3: "v_cvt_pk_bf16_f32", 4: "v_dot2c_f32_bf16",
                     5: "v_max3_f32", 6: "ds_read_b128", 7: "16x16x32 MFMAs, no companion"}
+PROBE_FP8_KINDS = {8: "fp8 32x32x64 MFMAs alone", 9: "+ the 8-bit kernel's vector and LDS work per MFMA",
+                   10: "+ its vector work only (4 exp2, 4 add, 2 cvt, 2 max3)", 11: "+ its LDS reads only (2 x 16 B)"}
 
 
 def probe_mfma_mix(companion: int, per_mfma: int = 1, workgroups: int = 256, iters: int = 20000, random_operands: bool = True):

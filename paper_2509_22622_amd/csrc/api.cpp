@@ -454,8 +454,8 @@ ll_status ll_probe_mfma_mix(void* dev_scratch, size_t scratch_bytes, int workgro
     if (!dev_scratch || !tflops || !clock_ghz) return fail(LL_ERR_INVALID_ARG, "null pointer");
     if (workgroups < 1 || workgroups > 4096 || iters < 1 || iters > (1 << 22))
         return fail(LL_ERR_INVALID_ARG, "workgroups %d or iters %d out of range", workgroups, iters);
-    if (companion < PROBE_NONE || companion > PROBE_SHAPE_16X16X32 || per_mfma < 1 || per_mfma > 2)
-        return fail(LL_ERR_INVALID_ARG, "companion %d (0..7) or per_mfma %d (1, 2) out of range", companion, per_mfma);
+    if (companion < PROBE_NONE || companion > PROBE_FP8_LDS || per_mfma < 1 || per_mfma > 2)
+        return fail(LL_ERR_INVALID_ARG, "companion %d (0..11) or per_mfma %d (1, 2) out of range", companion, per_mfma);
     const size_t sink_bytes = size_t(workgroups) * 512 * sizeof(float);
     if (scratch_bytes < sink_bytes + 16) return fail(LL_ERR_BUFFER_TOO_SMALL, "scratch has %zu bytes, %zu needed", scratch_bytes, sink_bytes + 16);
     hipStream_t s = static_cast<hipStream_t>(stream);
@@ -476,8 +476,8 @@ ll_status ll_probe_mfma_mix(void* dev_scratch, size_t scratch_bytes, int workgro
     if (e0) (void)hipEventDestroy(e0);
     if (e1) (void)hipEventDestroy(e1);
     if (e != hipSuccess) return hip_fail(e, "ll_probe_mfma_mix");
-    // 8 waves per workgroup, 16 MFMAs of 32x32x16 (2 * 32 * 32 * 16 flops) per iteration and wave
-    *tflops = double(workgroups) * 8 * iters * 16 * 32768.0 / (double(ms) * 1e9);
+    // 8 waves per workgroup, 16 MFMAs of 32x32x16 (2 * 32 * 32 * 16 flops; 32x32x64 for the fp8 kinds) per iteration and wave
+    *tflops = double(workgroups) * 8 * iters * 16 * (companion >= PROBE_FP8_NONE ? 131072.0 : 32768.0) / (double(ms) * 1e9);
     *clock_ghz = host[1] ? double(host[0]) / (double(host[1]) * 10.0) : 0.0;
     return LL_OK;
 }

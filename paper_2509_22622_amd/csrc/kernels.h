@@ -146,7 +146,10 @@ hipError_t launch_read_frame(const ReadFrameParams& p, hipStream_t s);
 // kind of instruction issued `per_mfma` (1 or 2) times behind every MFMA
 enum ProbeCompanion {
     PROBE_NONE = 0, PROBE_ADD = 1, PROBE_EXP = 2, PROBE_CVT_BF16 = 3, PROBE_DOT2_BF16 = 4, PROBE_MAX3 = 5,
-    PROBE_LDS_READ = 6, PROBE_SHAPE_16X16X32 = 7   // 7: no companion, 16x16x32 MFMAs instead of 32x32x16
+    PROBE_LDS_READ = 6, PROBE_SHAPE_16X16X32 = 7,  // 7: no companion, 16x16x32 MFMAs instead of 32x32x16
+    // fp8 32x32x64 MFMAs (E4M3 operands): alone, with what the 8-bit attention kernel issues per MFMA (4 exp2, 4 adds,
+    // 2 conversions, 2 max3, two 16-byte LDS reads), with its vector part only, with its LDS part only
+    PROBE_FP8_NONE = 8, PROBE_FP8_MIX = 9, PROBE_FP8_VALU = 10, PROBE_FP8_LDS = 11
 };
 hipError_t launch_probe_mfma(float* sink, unsigned long long* counters, int workgroups, int iters, int random_operands,
                              int companion, int per_mfma, hipStream_t s);

@@ -16,6 +16,7 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned u32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
 
 // companion instruction kinds (PROBE_* in kernels.h).  Each works on registers no MFMA touches.
 template <int KIND>
@@ -27,14 +28,38 @@ __device__ __forceinline__ void probe_companion(float& x, float c, u32x4& frag, 
     if (KIND == PROBE_MAX3) asm volatile("v_max3_f32 %0, %0, %1, %1" : "+v"(x) : "v"(c));
     if (KIND == PROBE_LDS_READ) asm volatile("ds_read_b128 %0, %1" : "=v"(frag) : "v"(lds_addr));
 }
+// What the 8-bit attention kernel issues per fp8 MFMA, on registers no MFMA touches: the vector part (4 exp2, 4 adds,
+// 2 conversions to E4M3, 2 max3) and the LDS part (two 16-byte reads).
+template <int KIND>
+__device__ __forceinline__ void probe_fp8_company(float (&x)[4], float c, u32x4& frag, unsigned lds_addr) {
+    if (KIND == PROBE_FP8_MIX || KIND == PROBE_FP8_VALU) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            asm volatile("v_exp_f32 %0, %0" : "+v"(x[i]));
+            asm volatile("v_add_f32 %0, %0, %1" : "+v"(x[i]) : "v"(c));
+        }
+        unsigned w = 0;
+        asm volatile("v_cvt_pk_fp8_f32 %0, %1, %2" : "+v"(w) : "v"(x[0]), "v"(x[1]));
+        asm volatile("v_cvt_pk_fp8_f32 %0, %1, %2 op_sel:[0,0,1]" : "+v"(w) : "v"(x[2]), "v"(x[3]));
+        asm volatile("v_max3_f32 %0, %0, %1, %2" : "+v"(x[0]) : "v"(c), "v"(w));
+        asm volatile("v_max3_f32 %0, %0, %1, %1" : "+v"(x[1]) : "v"(c));
+    }
+    if (KIND == PROBE_FP8_MIX || KIND == PROBE_FP8_LDS) {
+        asm volatile("ds_read_b128 %0, %1" : "=v"(frag) : "v"(lds_addr));
+        asm volatile("ds_read_b128 %0, %1 offset:1024" : "=v"(frag) : "v"(lds_addr));
+    }
+}
 
-// Each wave issues iters * 16 MFMAs 32x32x16 (or iters * 32 MFMAs 16x16x32: the same flops) back to back, four
-// (eight) independent accumulators, two waves per SIMD, PER companion instructions behind each MFMA.
+// Each wave issues iters * 16 MFMAs 32x32x16 (or iters * 32 MFMAs 16x16x32: the same flops; or iters * 16 fp8 MFMAs
+// 32x32x64: four times the flops) back to back, four (eight) independent accumulators, two waves per SIMD, PER
+// companion instructions behind each MFMA.
 // counters[0] = core clocks, counters[1] = 100 MHz reference ticks spent in the loop by wave 0 of workgroup 0.
 template <int KIND, int PER>
 __global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
 void ll_probe_mfma_kernel(float* sink, unsigned long long* counters, int iters, int random_operands) {
-    __shared__ __attribute__((aligned(16))) unsigned lds[KIND == PROBE_LDS_READ ? 16384 : 4];
+    constexpr bool FP8 = KIND >= PROBE_FP8_NONE;
+    constexpr bool USES_LDS = KIND == PROBE_LDS_READ || KIND == PROBE_FP8_MIX || KIND == PROBE_FP8_LDS;
+    __shared__ __attribute__((aligned(16))) unsigned lds[USES_LDS ? 16384 : 4];
     u32x4 a[8], b[8];
     unsigned x = (blockIdx.x * 512u + threadIdx.x) * 2654435761u + 12345u;
 #pragma unroll
@@ -45,11 +70,16 @@ void ll_probe_mfma_kernel(float* sink, unsigned long long* counters, int iters, 
             const unsigned ra = x ^ (x >> 13);
             x = x * 1664525u + 1013904223u;
             const unsigned rb = x ^ (x >> 13);
-            // bf16 pairs in [0.5, 1) with random mantissas and signs, or all 1.0
-            a[i][j] = random_operands ? ((ra & 0x807F807Fu) | 0x3F003F00u) : 0x3F803F80u;
-            b[i][j] = random_operands ? ((rb & 0x807F807Fu) | 0x3F003F00u) : 0x3F803F80u;
+            // bf16 pairs (E4M3 bytes for the fp8 kinds) in [0.5, 1) with random mantissas and signs, or all 1.0
+            if (FP8) {
+                a[i][j] = random_operands ? ((ra & 0x87878787u) | 0x30303030u) : 0x38383838u;
+                b[i][j] = random_operands ? ((rb & 0x87878787u) | 0x30303030u) : 0x38383838u;
+            } else {
+                a[i][j] = random_operands ? ((ra & 0x807F807Fu) | 0x3F003F00u) : 0x3F803F80u;
+                b[i][j] = random_operands ? ((rb & 0x807F807Fu) | 0x3F003F00u) : 0x3F803F80u;
+            }
         }
-    if (KIND == PROBE_LDS_READ) {
+    if (USES_LDS) {
         for (int i = threadIdx.x; i < 16384; i += 512) {
             x = x * 1664525u + 1013904223u;
             lds[i] = random_operands ? x : 0x3F803F80u;
@@ -65,15 +95,29 @@ void ll_probe_mfma_kernel(float* sink, unsigned long long* counters, int iters, 
         for (int r = 0; r < 16; ++r) o[j][r] = 0.f;
 #pragma unroll
     for (int j = 0; j < 8; ++j) o4[j] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float v[16 * PER];
+    constexpr int NV = FP8 ? 64 : 16 * PER;
+    float v[NV];
 #pragma unroll
-    for (int i = 0; i < 16 * PER; ++i) v[i] = -0.5f - 0.001f * i - 1e-5f * threadIdx.x;
+    for (int i = 0; i < NV; ++i) v[i] = -0.5f - 0.001f * i - 1e-5f * threadIdx.x;
+    i32x8 a8[4], b8[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            a8[i][j] = int(a[2 * i][j]); a8[i][4 + j] = int(a[2 * i + 1][j]);
+            b8[i][j] = int(b[2 * i][j]); b8[i][4 + j] = int(b[2 * i + 1][j]);
+        }
     u32x4 frag = {0, 0, 0, 0};
     const unsigned long long c0 = __builtin_amdgcn_s_memtime(), r0 = __builtin_amdgcn_s_memrealtime();
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
-            if (KIND == PROBE_SHAPE_16X16X32) {
+            if (FP8) {
+                o[k % 4] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a8[k % 4], b8[(k * 3 + 1) % 4], o[k % 4], 0, 0, 0,
+                                                                           0x7F7F7F7F, 0, 0x7F7F7F7F);
+                float(&x4)[4] = *reinterpret_cast<float(*)[4]>(&v[4 * k]);
+                probe_fp8_company<KIND>(x4, 0.999f, frag, lds_addr + (k & 7) * 2048);
+            } else if (KIND == PROBE_SHAPE_16X16X32) {
                 o4[(2 * k) % 8] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[k % 8]),
                                       __builtin_bit_cast(bf16x8, b[(k * 3 + 1) % 8]), o4[(2 * k) % 8], 0, 0, 0);
                 o4[(2 * k + 1) % 8] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[k % 8]),
@@ -82,11 +126,13 @@ void ll_probe_mfma_kernel(float* sink, unsigned long long* counters, int iters, 
                 o[k % 4] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a[k % 8]),
                                __builtin_bit_cast(bf16x8, b[(k * 3 + 1) % 8]), o[k % 4], 0, 0, 0);
             }
+            if (!FP8) {
 #pragma unroll
-            for (int r = 0; r < PER; ++r) probe_companion<KIND>(v[k * PER + r], 0.999f, frag, lds_addr + ((k * PER + r) & 15) * 1024);
+                for (int r = 0; r < PER; ++r) probe_companion<KIND>(v[k * PER + r], 0.999f, frag, lds_addr + ((k * PER + r) & 15) * 1024);
+            }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (KIND == PROBE_LDS_READ) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(frag));
+        if (USES_LDS) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(frag));
         if ((it & 63) == 63) {
 #pragma unroll
             for (int j = 0; j < 4; ++j) o[j] *= 1e-3f;      // keep the accumulators finite
@@ -105,7 +151,7 @@ void ll_probe_mfma_kernel(float* sink, unsigned long long* counters, int iters, 
 #pragma unroll
     for (int j = 0; j < 16; ++j) s += cs[j];
 #pragma unroll
-    for (int i = 0; i < 16 * PER; ++i) s += v[i];
+    for (int i = 0; i < NV; ++i) s += v[i];
     sink[blockIdx.x * 512 + threadIdx.x] = s;
 }
 
@@ -131,6 +177,10 @@ hipError_t launch_probe_mfma(float* sink, unsigned long long* counters, int work
         LL_PROBE_CASE(PROBE_DOT2_BF16)
         LL_PROBE_CASE(PROBE_MAX3)
         LL_PROBE_CASE(PROBE_LDS_READ)
+        case PROBE_FP8_NONE: return launch_probe<PROBE_FP8_NONE, 1>(sink, counters, workgroups, iters, random_operands, s);
+        case PROBE_FP8_MIX: return launch_probe<PROBE_FP8_MIX, 1>(sink, counters, workgroups, iters, random_operands, s);
+        case PROBE_FP8_VALU: return launch_probe<PROBE_FP8_VALU, 1>(sink, counters, workgroups, iters, random_operands, s);
+        case PROBE_FP8_LDS: return launch_probe<PROBE_FP8_LDS, 1>(sink, counters, workgroups, iters, random_operands, s);
     }
 #undef LL_PROBE_CASE
     return hipErrorInvalidValue;
