@@ -181,6 +181,33 @@ def _fp8_step(res, w, q, k, v, steps):
     fl = attn_flops(nq, nk, D, Hh) * L
     res["step_30_layers"] = {"ms_per_step": round(ms, 4), "TFLOP/s": round(fl / (ms * 1e-3) / 1e12, 1),
                              "pct_of_fp8_mfma_peak": round(100 * fl / (ms * 1e-3) / 1e12 / PEAK_FP8_TFLOPS, 2), "steps": steps}
+    if "single_layer" in res:
+        # the recache workload (sink 3 + 12 window frames at a late position, chunk-causal), 30 layers
+        from paper_2509_22622_amd import synth
+        wr = synth.RECACHE
+        nf = wr.sink_frames + wr.window_frames + wr.chunk_frames
+        rshape = (nf * w.tokens_per_frame, Hh, D)
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(synth.MASTER_SEED + 5)
+        rq, rk, rv = (torch.randn(rshape, generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16) for _ in range(3))
+        ro = torch.empty(rshape, dtype=torch.bfloat16, device="cuda")
+        ws = chunk * Cf - (wr.window_frames + wr.chunk_frames)
+
+        def recache():
+            for l in range(L):
+                cache.recache_prefill(l, True, ws, wr.window_frames + wr.chunk_frames, rq, rk, rv, ro)
+
+        recache()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            recache()
+        torch.cuda.synchronize()
+        r_ms = (time.perf_counter() - t0) / 3 * 1e3
+        n_ch = nf // Cf
+        pairs = sum(min(i + 1, (wr.sink_frames + wr.window_frames) // Cf + 1) for i in range(n_ch))
+        r_fl = attn_flops(nq, nq, D, Hh) * pairs * L
+        res["recache_prefill"] = {"ms_30_layers": round(r_ms, 3), "TFLOP/s": round(r_fl / (r_ms * 1e-3) / 1e12, 1)}
     cache.close()
     return res
 
