@@ -38,10 +38,13 @@ def rotate_vec(vec, head_dim, f, y, x, theta):
     return out
 
 
-def stream_attention(chunks, heads, head_dim, grid_h, grid_w, C, S, W, theta=10000.0):
+def stream_attention(chunks, heads, head_dim, grid_h, grid_w, C, S, W, theta=10000.0, sink_relative=False):
     """chunks: list of (q_bits, k_bits, v_bits), each an [n*P, H, D] nested array
     of bf16 bit patterns, appended in order from frame 0.  Returns, per chunk, the
     attention output [n*P][H][D] as nested lists of floats.
+
+    sink_relative: for keys of sink frames the query is rotated as if its frame index were smaller by
+    max(0, f0 - W - S), f0 being the first frame of its chunk (the sink keeps a fixed rotary distance to the window).
     """
     P = grid_h * grid_w
     all_k, all_v, all_frame = [], [], []   # one entry per token ever produced
@@ -50,11 +53,13 @@ def stream_attention(chunks, heads, head_dim, grid_h, grid_w, C, S, W, theta=100
     for (qb, kb, vb) in chunks:
         n_tok = len(qb)
         n = n_tok // P
-        q_rot = []
+        q_rot, q_sink = [], []
+        shift = max(0, f0 - W - S) if sink_relative else 0
         for t in range(n_tok):
             f = f0 + t // P
             y, x = divmod(t % P, grid_w)
             q_rot.append([rotate_vec([_bf16(b) for b in qb[t][h]], head_dim, f, y, x, theta) for h in range(heads)])
+            q_sink.append([rotate_vec([_bf16(b) for b in qb[t][h]], head_dim, f - shift, y, x, theta) for h in range(heads)])
             all_k.append([rotate_vec([_bf16(b) for b in kb[t][h]], head_dim, f, y, x, theta) for h in range(heads)])
             all_v.append([[_bf16(b) for b in vb[t][h]] for h in range(heads)])
             all_frame.append(f)
@@ -68,9 +73,10 @@ def stream_attention(chunks, heads, head_dim, grid_h, grid_w, C, S, W, theta=100
                     if not visible:
                         logits.append(None)
                         continue
+                    qv = q_sink[t][h] if g < S else q_rot[t][h]
                     dot = 0.0
                     for d in range(head_dim):
-                        dot += q_rot[t][h][d] * all_k[j][h][d]
+                        dot += qv[d] * all_k[j][h][d]
                     logits.append(dot / math.sqrt(head_dim))
                 m = max(l for l in logits if l is not None)
                 den = sum(math.exp(l - m) for l in logits if l is not None)

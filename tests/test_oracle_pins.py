@@ -503,3 +503,53 @@ def test_fp8_oracle_exponents_and_error_bound():
     assert out.shape == (6 * P, 2, 64) and np.isfinite(out).all()
     K8, _ = pre.gather_keys(0)
     assert (fp8_cache.e4m3_round(K8) == K8).all()
+
+
+# ---- sink at a fixed rotary distance (oracle/sink_relative.py) ---------------------------------------------------
+from oracle.sink_relative import SinkRelativeOracle  # noqa: E402
+
+
+# ---- P18: equal to the plain rule while the window touches the sink; brute force afterwards --------------------
+@pytest.mark.parametrize("S,W,C", [(2, 2, 2), (1, 3, 2), (3, 1, 3)])
+def test_sink_relative_brute_force_and_warmup(S, W, C):
+    cfg = OracleConfig(1, 2, 12, 2, 2, C, S, W)
+    chunks = _stream(cfg, 6, 300 + S * 7 + W)
+    want = brute.stream_attention([(q.tolist(), k.tolist(), v.tolist()) for q, k, v in chunks],
+                                  cfg.heads, cfg.head_dim, cfg.grid_h, cfg.grid_w, C, S, W, sink_relative=True)
+    plain, rel = Oracle(cfg), SinkRelativeOracle(cfg)
+    differs = False
+    for i, (q, k, v) in enumerate(chunks):
+        plain.append(0, i * C, q, k, v)
+        rel.append(0, i * C, q, k, v)
+        got = rel.attn(0)
+        assert np.abs(got - np.array(want[i])).max() < 1e-12
+        if i * C <= W + S:
+            assert np.abs(got - plain.attn(0)).max() < 1e-12        # Delta = 0: the plain rule
+        else:
+            differs = differs or np.abs(got - plain.attn(0)).max() > 1e-6
+    assert differs                                                  # and a different one afterwards
+
+
+# ---- P19: the outputs do not depend on where in the video the window lies --------------------------------------
+def test_sink_relative_is_invariant_under_window_position():
+    cfg = OracleConfig(1, 2, 24, 2, 3, 2, 2, 4)
+    P, S, W, C = cfg.tokens_per_frame, 2, 4, 2
+    shape = ((S + W + C) * P, cfg.heads, cfg.head_dim)
+    q, k, v = _bits(shape, 41), _bits(shape, 42), _bits(shape, 43)
+    outs = {}
+    for ws in (W + S, W + S + 5, 400):
+        for name, cls in (("plain", Oracle), ("rel", SinkRelativeOracle)):
+            outs[name, ws] = cls(cfg).recache_prefill(0, True, ws, W + C, q, k, v)
+    first = S * P                                                   # the sink chunk itself never depends on ws
+    for ws in (W + S + 5, 400):
+        assert np.abs(outs["rel", ws] - outs["rel", W + S]).max() < 1e-9
+        assert np.abs(outs["plain", ws][first:] - outs["plain", W + S][first:]).max() > 1e-4
+    # the rotary distance of rows and columns is untouched: with one token row and column per frame and the frame
+    # axis pairs zeroed in q, the variant cannot differ from the plain rule
+    n_t = rope_pair_split(cfg.head_dim)[0]
+    qz = bf16_bits_to_f64(q).copy()
+    qz[..., :2 * n_t] = 0.0
+    qz_bits = synth.f32_to_bf16_bits(qz.astype(np.float32))
+    a = Oracle(cfg).recache_prefill(0, True, 400, W + C, qz_bits, k, v)
+    b = SinkRelativeOracle(cfg).recache_prefill(0, True, 400, W + C, qz_bits, k, v)
+    assert np.abs(a - b).max() < 1e-12
