@@ -65,7 +65,7 @@ def cpu_baseline(w, chunks=3):
 PEAK_FP8_TFLOPS = 2 * PEAK_BF16_TFLOPS      # dense fp8 MFMA peak (published: 5.0 PFLOP/s)
 
 
-def single_layer_stats(w, gen, warmup=10, iters=50, kv_format="bf16"):
+def single_layer_stats(w, gen, warmup=10, iters=50, kv_format="bf16", sink_relative=False):
     """Attention launch times of one layer in steady state: median, p10, p90 over `iters` launches (HIP events)."""
     import torch
     from paper_2509_22622_amd import binding
@@ -73,6 +73,8 @@ def single_layer_stats(w, gen, warmup=10, iters=50, kv_format="bf16"):
     nq = w.chunk_tokens
     nk = (w.sink_frames + w.window_frames + Cf) * w.tokens_per_frame
     cache = binding.Cache(1, Hh, D, w.grid_h, w.grid_w, Cf, w.sink_frames, w.window_frames, kv_format=kv_format)
+    if sink_relative:
+        cache.set_sink_relative(True)
     q, k, v = (torch.randn((nq, Hh, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16) for _ in range(3))
     qr, out = torch.empty(q.shape, dtype=torch.bfloat16 if kv_format == "bf16" else torch.uint8, device="cuda"), torch.empty_like(q)
     for c in range((w.sink_frames + w.window_frames) // Cf + 2):
@@ -430,7 +432,9 @@ def main():
     import dataclasses
     wan14b = dataclasses.replace(synth.WAN_LAYER, name="wan14b-shaped-layer", heads=40)      # 40 heads: three rounds of tiles
     res["single_layer"] = {"cfg2": single_layer_stats(synth.WAN_LAYER, gen), "cfg4": single_layer_stats(synth.LONG_WINDOW, gen),
-                           "heads40": single_layer_stats(wan14b, gen, warmup=5, iters=20)}
+                           "heads40": single_layer_stats(wan14b, gen, warmup=5, iters=20),
+                           # the sink at a fixed rotary distance from the window (its own range, queries turned for it)
+                           "cfg2_sink_relative": single_layer_stats(synth.WAN_LAYER, gen, sink_relative=True)}
 
     # What a pure MFMA stream sustains on this GPU right now (diagnostic kernel of the library): the chip is
     # power-limited under a full matrix load, far below the boost clock when the operand bits toggle.

@@ -156,6 +156,19 @@ ll_status ll_cache_live_ranges(const ll_cache* cache, int layer, int64_t* ranges
 ll_status ll_cache_read_frame(const ll_cache* cache, int layer, int64_t frame, void* k_out,
                               void* v_out, void* stream);
 
+/* Variant of the rule for very long videos (this library's reading; the paper keeps the first frames as a sink for
+ * videos of any length, Sec. 3.3 "Frame Sink", and does not say which rotary positions they get): with absolute
+ * frame positions the rotary distance between a query and the sink grows with the video without bound.  With
+ * on != 0, every later ll_sink_window_attn and ll_recache_prefill of this handle takes the scores of the sink
+ * keys as if the query's frame index were smaller by max(0, f0 - W - S), f0 = first frame of the query's chunk:
+ * seen from the queries the sink sits at frames 0 .. S-1 and the oldest window frame at S, wherever in the video
+ * the window lies.  Only the frame axis of the rotary embedding is concerned, the other scores are unchanged, and
+ * nothing differs while f0 <= W + S.  The cache contents do not depend on the setting (keys stay rotated at their
+ * absolute frames; the kernel turns the queries instead, with one more rounding to bfloat16 for the sink's
+ * scores).  LL_ERR_UNSUPPORTED for handles of the 8-bit cache; a later attention call returns LL_ERR_UNSUPPORTED
+ * if a kernel variant without this mode was selected with ll_set_attn_variant. */
+ll_status ll_cache_set_sink_relative(ll_cache* cache, int on);
+
 /* Attention kernel variant: 0 = default for the shape, otherwise a variant id listed by
  * ll_attn_variant_name.  Process-wide tuning knob for benchmarking. */
 ll_status ll_set_attn_variant(int variant);

@@ -33,6 +33,7 @@ SIGNATURES = {
     "ll_cache_slot_of_frame": (_i, [_vp, _i, _i64, C.POINTER(_i64)]),
     "ll_cache_live_ranges": (_i, [_vp, _i, C.POINTER(_i64), _i, C.POINTER(_i)]),
     "ll_cache_read_frame": (_i, [_vp, _i, _i64, _vp, _vp, _vp]),
+    "ll_cache_set_sink_relative": (_i, [_vp, _i]),
     "ll_set_attn_variant": (_i, [_i]),
     "ll_attn_variant_name": (C.c_char_p, [_i]),
     "ll_probe_mfma_rate": (_i, [C.c_void_p, C.c_size_t, _i, _i, _i, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
@@ -165,6 +166,10 @@ class Cache:
             self.close()
         except Exception:
             pass
+
+    def set_sink_relative(self, on: bool) -> None:
+        """Sink at a fixed rotary distance from the window (see ``ll_cache_set_sink_relative``)."""
+        _check(lib().ll_cache_set_sink_relative(self._h, int(bool(on))))
 
     def reset(self, layer=-1):
         _check(lib().ll_cache_reset(self._h, layer))

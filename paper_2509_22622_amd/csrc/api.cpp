@@ -23,6 +23,7 @@ struct ll_cache {
     int kb;                 // key slots per kblock: KBLOCK or KBLOCK8
     int k_exp, v_exp;       // 8-bit cache: K8 = e4m3(K' 2^-k_exp), V8 = e4m3(V 2^-v_exp)
     char* q8_stage;         // 8-bit cache: staging area for the E4M3 queries of a re-prefill
+    bool sink_relative;     // the sink keeps a fixed rotary distance to the window (ll_cache_set_sink_relative)
     int layers, H, D;
     Geometry g;
     int grid_h, grid_w;
@@ -130,6 +131,7 @@ static ll_status cache_create(int fmt, int k_exp, int v_exp, int layers, int hea
     Sizes z = sizes(fmt, layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames, grid_h, grid_w);
     ll_cache* c = new ll_cache();
     c->fmt = fmt; c->kb = fmt ? KBLOCK8 : KBLOCK; c->k_exp = k_exp; c->v_exp = v_exp;
+    c->sink_relative = false;
     c->q8_stage = (fmt && dev_buffer) ? static_cast<char*>(dev_buffer) + z.stage_off : nullptr;
     c->layers = layers; c->H = heads; c->D = head_dim;
     c->g.P = tokens_per_frame; c->g.S = sink_frames; c->g.W = window_frames; c->g.C = chunk_frames;
@@ -260,7 +262,13 @@ static int pick_variant(const ll_cache* c) {
     return attn_variant_default(c->D, c->kb);
 }
 
-struct ChunkWork { int q_begin, q_end; std::vector<SlotRange> ranges; };
+struct ChunkWork { int q_begin, q_end; std::vector<SlotRange> ranges; int64_t f0; };
+
+// Frames by which the queries of a chunk starting at f0 are turned back for the sink's scores (0: plain rule).
+static int64_t sink_shift_of(const ll_cache* c, int64_t f0) {
+    if (!c->sink_relative || c->g.S == 0) return 0;
+    return std::max<int64_t>(0, f0 - c->g.W - c->g.S);
+}
 
 // Enqueue attention for a list of query chunks (each with its key ranges).
 static ll_status enqueue_attn(ll_cache* c, int layer, const std::vector<ChunkWork>& work, const void* q, void* out,
@@ -288,13 +296,28 @@ static ll_status enqueue_attn(ll_cache* c, int layer, const std::vector<ChunkWor
         for (int i = 0; i < m; ++i) order[i] = int(base) + i;
         auto keys = [&](int i) { int64_t t = 0; for (auto& r : work[i].ranges) t += r.end - r.begin; return t; };
         std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return keys(a) > keys(b); });
+        p.inv_freq_t = c->rope.inv_freq_t; p.n_t = c->rope.n_t;
         int tiles = 0;
         for (int i = 0; i < m; ++i) {
-            const ChunkWork& w = work[order[i]];
+            ChunkWork w = work[order[i]];
+            const int64_t shift = sink_shift_of(c, w.f0);
+            if (shift != 0) {
+                // the sink's scores use other queries than the rest: the sink must be a range of its own
+                if (!attn_variant_sink_shift(variant)) return fail(LL_ERR_UNSUPPORTED, "attention variant %d has no sink-relative mode", variant);
+                if (shift > 0x7FFFFFFF) return fail(LL_ERR_UNSUPPORTED, "sink shift %lld too large", (long long)shift);
+                const int64_t sink_end = int64_t(c->g.S) * c->g.P;
+                if (w.ranges.empty() || w.ranges[0].begin != 0 || w.ranges[0].end < sink_end)
+                    return fail(LL_ERR_STATE, "sink frames are not the first key range");
+                if (w.ranges[0].end > sink_end) {
+                    w.ranges.insert(w.ranges.begin() + 1, SlotRange{sink_end, w.ranges[0].end});
+                    w.ranges[0].end = sink_end;
+                }
+            }
             if (w.ranges.empty() || w.ranges.size() > size_t(MAX_RANGES))
                 return fail(LL_ERR_STATE, "key set has %zu ranges", w.ranges.size());
             AttnChunk& ch = p.chunk[i];
             ch.q_begin = w.q_begin; ch.q_end = w.q_end; ch.tile_begin = tiles;
+            ch.sink_shift = int(shift);
             ch.n_ranges = int(w.ranges.size());
             for (int r = 0; r < ch.n_ranges; ++r) { ch.rs[r] = int(w.ranges[r].begin); ch.re[r] = int(w.ranges[r].end); }
             tiles += (w.q_end - w.q_begin + qt - 1) / qt;
@@ -343,6 +366,7 @@ ll_status ll_sink_window_attn(ll_cache* cache, int layer, const void* q_roped, v
     work[0].q_begin = 0;
     work[0].q_end = L.staged_n * cache->g.P;
     work[0].ranges = live_ranges(cache->g, L);
+    work[0].f0 = L.staged_f0;
     return enqueue_attn(cache, layer, work, q_roped, out, static_cast<hipStream_t>(stream));
 }
 
@@ -383,6 +407,7 @@ ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64
         ChunkWork w;
         w.q_begin = row; w.q_end = row + c.n * g.P;
         w.ranges = live_ranges(g, L);
+        w.f0 = c.f0;
         work.push_back(w);
         row = w.q_end;
     }
@@ -434,6 +459,13 @@ ll_status ll_cache_read_frame(const ll_cache* cache, int layer, int64_t frame, v
     p.H = cache->H; p.D = cache->D; p.P = cache->g.P; p.slot = slot_of_frame(cache->g, frame);
     hipError_t e = cache->fmt ? launch_read_frame8(p, static_cast<hipStream_t>(stream)) : launch_read_frame(p, static_cast<hipStream_t>(stream));
     if (e != hipSuccess) return hip_fail(e, "read_frame kernel launch");
+    return LL_OK;
+}
+
+ll_status ll_cache_set_sink_relative(ll_cache* cache, int on) {
+    if (!cache) return fail(LL_ERR_INVALID_ARG, "cache is null");
+    if (on && cache->fmt) return fail(LL_ERR_UNSUPPORTED, "the 8-bit cache has no sink-relative mode");
+    cache->sink_relative = on != 0;
     return LL_OK;
 }
 

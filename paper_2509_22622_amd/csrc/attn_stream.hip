@@ -131,7 +131,7 @@ struct SpState {
 // Virtual kblocks [vb, ve) of chunk `ch` for the 32 queries starting at row q0 of head `head`.
 template <int D>
 __device__ __forceinline__ void sp_segment(const AttnParams& p, const AttnChunk& ch, int head, int q0, int vb, int ve,
-                                           char* lds, SpState<D>& st) {
+                                           char* lds, SpState<D>& st, const float2* shift_cs) {
     constexpr int KS = D / 16;                  // k-steps of S^T = K Q^T, also fragments per K kblock
     constexpr int DB = D / 32;                  // 32-row blocks of O^T
     constexpr int NV = 2 * DB;                  // V^T fragments per kblock
@@ -170,11 +170,27 @@ __device__ __forceinline__ void sp_segment(const AttnParams& p, const AttnChunk&
 
     // Q^T fragments (pre-scaled by log2(e)/sqrt(D)): fragment ks holds features 16*ks + 8*half + 0..7 of query q0 + col
     bf16x8 qf[KS];
-    {
-        const int row = min(q0 + col, q_end - 1);
-        const uint16_t* src = p.q + (int64_t(row) * p.H + head) * D + half * 8;
+    const uint16_t* q_src = p.q + (int64_t(min(q0 + col, q_end - 1)) * p.H + head) * D + half * 8;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(src + ks * 16);
+    for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(q_src + ks * 16);
+    // Sink at a fixed rotary distance: range 0 is the sink, and its scores are taken with the queries turned back
+    // by sink_shift frames on the frame axis: pair i (features 2i, 2i+1) times exp(-i * shift * freq_i), from the
+    // table the workgroup prepared.  The scores of kblock v are computed one step ahead, so the unturned queries
+    // are loaded again at the start of step n0 - 1 (the last kblock of range 0, always taken by the general step).
+    const int sink_shift = ch.sink_shift;
+    if (sink_shift != 0) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const int pi = 8 * ks + 4 * half + j;
+                if (pi < p.n_t) {
+                    const float2 cs = shift_cs[pi];
+                    const float re = float(qf[ks][2 * j]), im = float(qf[ks][2 * j + 1]);
+                    qf[ks][2 * j] = __bf16(re * cs.x + im * cs.y);
+                    qf[ks][2 * j + 1] = __bf16(im * cs.x - re * cs.y);
+                }
+            }
     }
 
     const char* kbase = reinterpret_cast<const char*>(p.k_cache + head * p.head_stride);
@@ -295,6 +311,10 @@ __device__ __forceinline__ void sp_segment(const AttnParams& p, const AttnChunk&
                 next_edge = sp_next_edge((I), n0, n01, T);                                                          \
                 mask_s(S_CUR, SP_LIVE(I));                                                                          \
                 mx = max_s(S_CUR);                                                                                  \
+                if (sink_shift != 0 && (I) == n0 - 1) {     /* the sink ends here: back to the unturned queries */  \
+                    _Pragma("unroll") for (int ks = 0; ks < KS; ++ks)                                               \
+                        qf[ks] = *reinterpret_cast<const bf16x8*>(q_src + ks * 16);                                 \
+                }                                                                                                   \
             }                                                                                                       \
             const float delta = fmaxf(fmaxf(mx, __shfl_xor(mx, 32)), 0.f);                                          \
             const float alpha = __builtin_amdgcn_exp2f(-delta);                                                     \
@@ -472,6 +492,7 @@ __device__ __forceinline__ void sp_store_out(const AttnParams& p, int head, int 
 template <int D>
 __global__ __launch_bounds__(SP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_attn_stream_kernel(const AttnParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
+    __shared__ float2 shift_cs[64];              // (cos, sin) of sink_shift * frame-axis frequency, per rotary pair
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     // Workgroups are dealt round-robin to the 8 XCDs, each with its own L2: the workgroups that stream the same
     // head's K/V should share one.
@@ -503,6 +524,14 @@ __global__ __launch_bounds__(SP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
     int ci = 0;
     while (ci + 1 < p.n_chunks && tile >= p.chunk[ci + 1].tile_begin) ++ci;
     const AttnChunk& ch = p.chunk[ci];
+    if (ch.sink_shift != 0) {                    // uniform over the workgroup
+        if ((int)threadIdx.x < p.n_t) {
+            double sn, cs;
+            sincos(double(ch.sink_shift) * p.inv_freq_t[threadIdx.x], &sn, &cs);
+            shift_cs[threadIdx.x] = make_float2(float(cs), float(sn));
+        }
+        __syncthreads();
+    }
     // Waves w and w + 4 share a SIMD and take neighbouring 32-row blocks: in a chunk's short last tile the blocks
     // that do hold rows then pair up on SIMDs, and the workgroup advances at the pace of a full tile.  (One block
     // per SIMD would let it run some hundred kblocks ahead of the head's other workgroups, past what L2 keeps, and
@@ -514,7 +543,7 @@ __global__ __launch_bounds__(SP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
         return;
     }
     SpState<D> st;
-    sp_segment<D>(p, ch, head, q0, 0, ch.n_kblocks, lds, st);
+    sp_segment<D>(p, ch, head, q0, 0, ch.n_kblocks, lds, st, shift_cs);
     sp_store_out<D>(p, head, q0, ch.q_end, st);
 }
 

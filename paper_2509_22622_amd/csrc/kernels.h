@@ -86,6 +86,9 @@ struct AttnChunk {
     int n_ranges;
     int rs[MAX_RANGES], re[MAX_RANGES];   // key token-slot ranges
     int n_kblocks;               // kblocks the ranges touch        (filled in by launch_attn)
+    // Sink at a fixed rotary distance (0 = off): range 0 is exactly the sink, and its scores are taken with the
+    // queries turned back by sink_shift frames on the frame axis of the rotary embedding.
+    int sink_shift;
 };
 
 struct AttnParams {
@@ -104,6 +107,8 @@ struct AttnParams {
     const uint8_t* q8; const uint8_t* k8_cache; const uint8_t* v8_cache;
     float out_scale;
     int kblock;                  // key slots per kblock: 32 (bf16 cache) or 64 (8-bit cache)
+    const double* inv_freq_t;    // frame-axis rotary frequencies [n_t] (used when a chunk has a sink_shift)
+    int n_t;
     uint16_t xcd_first[9];
     uint16_t xcd_group[MAX_XCD_GROUPS];
     AttnChunk chunk[MAX_ATTN_CHUNKS];
@@ -136,6 +141,7 @@ const char* attn_variant_name(int v);
 int attn_variant_default(int D, int kblock);
 int attn_variant_qtile(int v);                 // query rows per workgroup
 bool attn_variant_supports(int v, int D, int kblock);
+bool attn_variant_sink_shift(int v);          // the variant honours AttnChunk::sink_shift
 
 hipError_t launch_append(const AppendParams& p, hipStream_t s);
 hipError_t launch_append8(const AppendParams& p, hipStream_t s);
