@@ -302,3 +302,13 @@ def test_device_argument_errors():
     cache.sink_window_attn(0, out, torch.empty_like(out))               # still usable
     torch.cuda.synchronize()
     cache.close()
+
+
+MANY = synth.Workload("many-chunks", 107, 1, 2, 64, 3, 5, 1, 2, 40, 6)     # chunk = 1 frame, ring of 41 frames
+
+
+def test_prefill_beyond_one_launch():
+    """A re-prefill of 43 frames in chunks of one frame: more frames than one append launch takes (32) and more
+    chunks than one attention launch takes (16), so the library cuts both; streaming goes on afterwards."""
+    _prefill_case(MANY, True, 50, 41, pre_chunks=4, follow=3)
+    _prefill_case(MANY, False, 7, 20, pre_chunks=3, follow=2)           # 20 chunks: two attention launches
