@@ -187,3 +187,37 @@ def test_header_and_library_from_plain_c(tmp_path):
                     "-L", libdir, "-l:" + os.path.basename(B.LIB_PATH), "-Wl,-rpath," + libdir], check=True)
     run = subprocess.run([str(exe)], capture_output=True, text=True)
     assert run.returncode == 0 and "c abi ok" in run.stdout, f"exit {run.returncode}: {run.stdout}{run.stderr}"
+
+
+def test_fp8_and_sink_relative_handles_share_the_bookkeeping():
+    """Index-only handles of the 8-bit cache and of the sink-relative mode keep exactly the plain handle's books
+    (the variants change what is stored or how scores are taken, never which frames are live or where they sit)."""
+    rng = random.Random(77)
+    for _ in range(10):
+        S, W, Cc = rng.randint(0, 4), rng.randint(0, 7), rng.randint(1, 4)
+        gh, gw = rng.randint(2, 6), rng.randint(2, 9)
+        make = lambda **kw: B.Cache(1, 2, 64, gh, gw, Cc, S, W, device=None, **kw)
+        a, b, c = make(), make(kv_format="fp8_e4m3", k_exp=1, v_exp=-2), make()
+        c.set_sink_relative(True)
+        f0 = 0
+        for i in range(12):
+            n = rng.randint(1, Cc)
+            for h in (a, b, c):
+                h.chunk_append(0, f0, n)
+            assert a.live_frames(0) == b.live_frames(0) == c.live_frames(0)
+            assert a.live_ranges(0) == b.live_ranges(0) == c.live_ranges(0)
+            if rng.random() < 0.3:                                  # a re-pass of the same chunk
+                for h in (a, b, c):
+                    h.chunk_append(0, f0, n)
+            f0 += n
+        assert B.cache_bytes(1, 2, 64, gh * gw, S, W, Cc, "fp8_e4m3") < B.cache_bytes(1, 2, 64, gh * gw, S, W, Cc) + (S + W + Cc) * gh * gw * 2 * 64 + 1
+        for h in (a, b, c):
+            h.close()
+    with pytest.raises(B.LongLiveError) as e:
+        B.Cache(1, 2, 64, 2, 2, 1, 1, 1, device=None, kv_format="fp8_e4m3", k_exp=17)
+    assert e.value.status == B.LL_ERR_INVALID_ARG
+    h8 = B.Cache(1, 2, 64, 2, 2, 1, 1, 1, device=None, kv_format="fp8_e4m3")
+    with pytest.raises(B.LongLiveError) as e:
+        h8.set_sink_relative(True)
+    assert e.value.status == B.LL_ERR_UNSUPPORTED
+    h8.close()
