@@ -334,7 +334,10 @@ __device__ __forceinline__ void f8_segment_sp(const AttnParams& p, const AttnChu
     constexpr int QPS = 8 / NK;                 // score quads converted per S^T slot
     constexpr int MPS = 32 / DB;                // scores entering the running maximum per O^T slot
     constexpr int DMA_STEP = NSLOT / LPW, DMA_FIRST = DMA_STEP - 1;
-    static_assert(NF % NW == 0 && 8 % NK == 0 && NSLOT % 4 == 0, "step shape");
+    using Plan = Fp8LdsPlan<D>;                 // which buffer a slot's fragment lives in, when it is read, the wait
+    constexpr int AH = Plan::AHEAD_SLOTS;
+    static_assert(Plan::NK == NK && Plan::NSLOT == NSLOT && Plan::BUFFERS == 4, "plan and kernel disagree on the step's shape");
+    static_assert(NF % NW == 0 && 8 % NK == 0, "step shape");
     static_assert(PF >= LAND && PF + 2 <= NS, "ring too short for the prefetch distance");
 
     const int tid = threadIdx.x, lane = tid & 63;
@@ -445,18 +448,18 @@ __device__ __forceinline__ void f8_segment_sp(const AttnParams& p, const AttnChu
 #define F8_READ_FRAG(J, KT_A, VT_A)                                                                                 \
     {                                                                                                               \
         if ((J) < NK) {                                                                                             \
-            f8_lds_read(fr[(J) % 4][0], (KT_A), ((J) * 2) * 1024);                                                  \
-            f8_lds_read(fr[(J) % 4][1], (KT_A), ((J) * 2 + 1) * 1024);                                              \
+            f8_lds_read(fr[Plan::buffer(J)][0], (KT_A), ((J) * 2) * 1024);                                                  \
+            f8_lds_read(fr[Plan::buffer(J)][1], (KT_A), ((J) * 2 + 1) * 1024);                                              \
         } else {                                                                                                    \
-            f8_lds_read(fr[(J) % 4][0], (VT_A), (((J) - NK) * 2) * 1024);                                           \
-            f8_lds_read(fr[(J) % 4][1], (VT_A), (((J) - NK) * 2 + 1) * 1024);                                       \
+            f8_lds_read(fr[Plan::buffer(J)][0], (VT_A), (((J) - NK) * 2) * 1024);                                           \
+            f8_lds_read(fr[Plan::buffer(J)][1], (VT_A), (((J) - NK) * 2 + 1) * 1024);                                       \
         }                                                                                                           \
     }
     {
         const unsigned kt_a = lds_a + ((vb + 1) & (NS - 1)) * STAGE_BYTES;
         const unsigned vt_a = lds_a + (vb & (NS - 1)) * STAGE_BYTES + KB_BYTES;
-        F8_READ_FRAG(0, kt_a, vt_a)
-        F8_READ_FRAG(1, kt_a, vt_a)
+#pragma unroll
+        for (int j = 0; j < AH; ++j) F8_READ_FRAG(j, kt_a, vt_a)
     }
 
 #define F8_PIN(x) asm volatile("" ::"v"(x))
@@ -496,27 +499,27 @@ __device__ __forceinline__ void f8_segment_sp(const AttnParams& p, const AttnChu
         _Pragma("unroll") for (int k = 0; k < NSLOT; ++k) {                                                         \
             if (k == 0) __builtin_amdgcn_s_setprio(1);                                                              \
             if (k == NK) __builtin_amdgcn_s_setprio(0);                                                             \
-            f8_lds_wait<2>(fr[k % 4][0], fr[k % 4][1]);                                                             \
+            f8_lds_wait<Plan::wait()>(fr[Plan::buffer(k)][0], fr[Plan::buffer(k)][1]);                                                             \
             if (k < NK) {                                                                                           \
                 const int R = k / DH, dh = k % DH;                                                                  \
-                S_NEXT[R] = f8_mfma(f8_join(fr[k % 4][0], fr[k % 4][1]), qf[dh], dh == 0 ? negm : S_NEXT[R]);       \
+                S_NEXT[R] = f8_mfma(f8_join(fr[Plan::buffer(k)][0], fr[Plan::buffer(k)][1]), qf[dh], dh == 0 ? negm : S_NEXT[R]);       \
             } else {                                                                                                \
                 const int db = k - NK;                                                                              \
                 if (EDGE && edge) {                                                                                 \
                     _Pragma("unroll") for (int j = 0; j < 4; ++j) {                                                 \
-                        fr[k % 4][0][j] &= vmask[j];                                                                \
-                        fr[k % 4][1][j] &= vmask[4 + j];                                                            \
+                        fr[Plan::buffer(k)][0][j] &= vmask[j];                                                                \
+                        fr[Plan::buffer(k)][1][j] &= vmask[4 + j];                                                            \
                     }                                                                                               \
                 }                                                                                                   \
-                st.o[db] = f8_mfma(f8_join(fr[k % 4][0], fr[k % 4][1]), pb, st.o[db]);                              \
+                st.o[db] = f8_mfma(f8_join(fr[Plan::buffer(k)][0], fr[Plan::buffer(k)][1]), pb, st.o[db]);                              \
             }                                                                                                       \
             if (k >= DMA_FIRST && (k - DMA_FIRST) % DMA_STEP == 0 && (k - DMA_FIRST) / DMA_STEP < LPW) {            \
                 const int v = min((I) + PF, ve - 1);                                                                \
                 issue_load(F8_PHYS_KB(v), ((I) + PF) & (NS - 1), (k - DMA_FIRST) / DMA_STEP);                       \
             }                                                                                                       \
             /* the fragment of the slot after next (the first two slots of the next step read kblock I + 2) */      \
-            if (k + 2 < NSLOT) F8_READ_FRAG(k + 2, kt_a, vt_a)                                                      \
-            else F8_READ_FRAG(k + 2 - NSLOT, kn_a, vt_a)                                                            \
+            if (k + AH < NSLOT) F8_READ_FRAG(k + AH, kt_a, vt_a)                                                    \
+            else F8_READ_FRAG(k + AH - NSLOT, kn_a, vt_a)                                                           \
             if (k < NK) {                                                                                           \
                 _Pragma("unroll") for (int g = k * QPS; g < (k + 1) * QPS; ++g) {                                   \
                     const int R = g / 4, r = 4 * (g % 4);                                                           \

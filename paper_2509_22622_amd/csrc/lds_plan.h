@@ -36,6 +36,28 @@ struct LdsPlan {
     }
 };
 
+// The same for the kernel of the 8-bit cache.  A step has NK = 2 * D/64 slots of S^T MFMAs (for the next kblock)
+// and DB = D/32 slots of O^T MFMAs (for this one); every MFMA consumes one operand fragment, read with two 16-byte
+// LDS reads.  Slot k issues its MFMA first and then the two reads of the fragment that slot k + AHEAD_SLOTS needs
+// (slots past the end of the step are the first slots of the next step), into register buffer
+// (k + AHEAD_SLOTS) % BUFFERS.  So exactly (AHEAD_SLOTS - 1) fragments are issued between a fragment's reads and
+// its use, and one wait count serves every slot.  A buffer is rewritten BUFFERS - AHEAD_SLOTS slots after the MFMA
+// that used it was issued: two slots, i.e. after one more MFMA of the same wave has entered the matrix pipe behind it.
+template <int D>
+struct Fp8LdsPlan {
+    static constexpr int NK = 2 * (D / 64);
+    static constexpr int DB = D / 32;
+    static constexpr int NSLOT = NK + DB;
+    static constexpr int AHEAD_SLOTS = 2;
+    static constexpr int BUFFERS = 4;
+    static constexpr int READS_PER_FRAGMENT = 2;
+    static constexpr int buffer(int slot) { return slot % BUFFERS; }
+    // reads issued after a fragment's own when its slot starts
+    static constexpr int wait() { return (AHEAD_SLOTS - 1) * READS_PER_FRAGMENT; }
+    static_assert(NSLOT % BUFFERS == 0, "the buffer of a slot must not depend on the step");
+    static_assert(AHEAD_SLOTS < BUFFERS, "a fragment would be read into a buffer still in use");
+};
+
 // The ring of K/V stages in LDS and its hand-over between the waves of a workgroup.
 //   Kblock v lives in stage v % STAGES.  The prologue issues the loads of the first AHEAD kblocks; step i issues
 //   those of kblock i + AHEAD, and reads kblock i (V^T) and kblock i + 2 (K for the scores of the step after next;

@@ -52,3 +52,30 @@ def test_ring_simulation_catches_a_wrong_plan(tmp_path, old, new):
     shutil.copy(os.path.join(HERE, "check_ring_plan.cpp"), tmp_path / "tests" / "check_ring_plan.cpp")
     run = _build_and_run(tmp_path, tmp_path / "tests" / "check_ring_plan.cpp", "check_wrong")
     assert run.returncode == 1 and re.search(r"reads kblock \d+", run.stdout), run.stdout + run.stderr
+
+
+def test_fp8_lds_plan_replay(tmp_path):
+    """The 8-bit kernel's fragment reads (two slots ahead, four rotating buffers, one wait count for every slot)."""
+    run = _build_and_run(tmp_path, os.path.join(HERE, "check_fp8_lds_plan.cpp"), "check_fp8_lds_plan")
+    assert run.returncode == 0, run.stdout + run.stderr
+    assert "fp8 lds plan ok" in run.stdout
+
+
+@pytest.mark.parametrize("old, new, message", [
+    ("return (AHEAD_SLOTS - 1) * READS_PER_FRAGMENT; }", "return (AHEAD_SLOTS - 1) * READS_PER_FRAGMENT + 1; }", "too weak"),
+    ("static constexpr int AHEAD_SLOTS = 2;", "static constexpr int AHEAD_SLOTS = 3;", "rewritten"),
+    ("static constexpr int buffer(int slot) { return slot % BUFFERS; }",
+     "static constexpr int buffer(int slot) { return (slot + 1) % BUFFERS; }", None),
+])
+def test_fp8_plan_check_catches_a_wrong_plan(tmp_path, old, new, message):
+    text = open(PLAN).read()
+    assert old in text
+    (tmp_path / "paper_2509_22622_amd" / "csrc").mkdir(parents=True)
+    (tmp_path / "tests").mkdir()
+    (tmp_path / "paper_2509_22622_amd" / "csrc" / "lds_plan.h").write_text(text.replace(old, new))
+    shutil.copy(os.path.join(HERE, "check_fp8_lds_plan.cpp"), tmp_path / "tests" / "check_fp8_lds_plan.cpp")
+    run = _build_and_run(tmp_path, tmp_path / "tests" / "check_fp8_lds_plan.cpp", "check_wrong")
+    if message is None:                       # a consistent renaming of the buffers is still a correct plan
+        assert run.returncode == 0, run.stdout + run.stderr
+    else:
+        assert run.returncode == 1 and message in run.stdout, run.stdout + run.stderr
