@@ -235,7 +235,7 @@ def main():
                     help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
-        sys.exit("bench.py: this build runs on one GPU only (--gpus 1); the path shards by head, see DESIGN.md")
+        sys.exit("bench.py: this build runs on one GPU only (--gpus 1); heads are independent, so the path would shard by head")
 
     import torch
     from paper_2509_22622_amd import binding, synth
