@@ -317,7 +317,16 @@ __device__ __forceinline__ void f8_lds_wait(u32x4& x, u32x4& y) {
 // kblocks i .. i+2 here, inside the i .. i+3 that plan covers).  Kblocks that a range boundary may cut run
 // through the general form of the step one at a time, all others in aligned pairs through a form with no
 // masking logic.
-template <int D>
+//
+// LOGLIN = true is a cheaper way to the weights (the exponentials bound the exact form: 16 cycles each on the vector
+// pipe).  An E4M3 code read as an integer is nearly linear in the logarithm of its value (8 codes per octave), so the
+// code of 2^x is taken as round(8 x + 56) (56 = the code of 1.0) with one multiply-add and one v_cvt_pk_u8_f32 per
+// score (which also clamps at 0 and inserts the byte into the operand word): the weight is 2^x times a factor between
+// 0.96 and 1.02 (after the common factor has cancelled in the normalisation), on top of a rounding to an eighth of
+// an octave.  The row sum is then taken from the same 8-bit weights by one more MFMA per kblock whose A operand is all
+// ones, so numerator and denominator agree exactly and the output is a convex combination of the V8 rows; the
+// accumulators hold the raw scores (started from zero), the reference enters through the multiply-add's constant.
+template <int D, bool LOGLIN>
 __device__ __forceinline__ void f8_segment_sp(const AttnParams& p, const AttnChunk& ch, int head, int q0, char* lds, F8State<D>& st) {
     constexpr int DH = D / 64;
     constexpr int DB = D / 32;
@@ -408,6 +417,10 @@ __device__ __forceinline__ void f8_segment_sp(const AttnParams& p, const AttnChu
     f32x16 negm;
     float mx;
     f32x16 sA[2], sB[2];
+    f32x16 lacc;                                 // LOGLIN: row sums (every register of a lane holds its query's sum)
+    i32x8 ones;                                  // LOGLIN: A operand of all 1.0
+    float bias = 0.f;                            // LOGLIN: code of 2^(t - mref + SHIFT) = round(8 t + bias)
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     u32x4 fr[4][2];                              // rotating operand buffers: slot j uses fr[j % 4]
     unsigned vmask[8];                           // byte masks of the V8^T operand of a kblock cut by a range boundary
 
@@ -434,11 +447,19 @@ __device__ __forceinline__ void f8_segment_sp(const AttnParams& p, const AttnChu
         mask_s(sA, F8_LIVE(vb));
         const float m = max_s(sA);
         mref = fmaxf(m, __shfl_xor(m, 32));
+        if (LOGLIN) {
+            bias = 56.0f + 8.0f * (F8_SHIFT - mref);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            negm[r] = F8_SHIFT - mref;
-            sA[0][r] += F8_SHIFT - mref;
-            sA[1][r] += F8_SHIFT - mref;
+            for (int r = 0; r < 16; ++r) lacc[r] = zero;
+#pragma unroll
+            for (int j = 0; j < 8; ++j) ones[j] = 0x38383838;
+        } else {
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                negm[r] = F8_SHIFT - mref;
+                sA[0][r] += F8_SHIFT - mref;
+                sA[1][r] += F8_SHIFT - mref;
+            }
         }
         mx = -INFINITY;
 #pragma unroll
@@ -478,17 +499,23 @@ __device__ __forceinline__ void f8_segment_sp(const AttnParams& p, const AttnChu
                                ((b4 & 8) ? 0xFF000000u : 0u);                                                       \
                 }                                                                                                   \
             }                                                                                                       \
-            const float delta = fmaxf(fmaxf(mx, __shfl_xor(mx, 32)) - F8_SHIFT, 0.f);                               \
+            /* mx: largest accumulator value, the raw score (LOGLIN) or the score - mref + SHIFT */                  \
+            const float delta = fmaxf(fmaxf(mx, __shfl_xor(mx, 32)) - (LOGLIN ? mref : F8_SHIFT), 0.f);             \
             const float alpha = __builtin_amdgcn_exp2f(-delta);                                                     \
             mref += delta;                                                                                          \
             lsum0 *= alpha;                                                                                         \
             lsum1 *= alpha;                                                                                         \
             _Pragma("unroll") for (int db = 0; db < DB; ++db)                                                       \
                 _Pragma("unroll") for (int r = 0; r < 16; ++r) st.o[db][r] *= alpha;                                \
-            _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                        \
-                negm[r] -= delta;                                                                                   \
-                S_CUR[0][r] -= delta;                                                                               \
-                S_CUR[1][r] -= delta;                                                                               \
+            if (LOGLIN) {                                                                                           \
+                bias -= 8.0f * delta;                                                                               \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) lacc[r] *= alpha;                                    \
+            } else {                                                                                                \
+                _Pragma("unroll") for (int r = 0; r < 16; ++r) {                                                    \
+                    negm[r] -= delta;                                                                               \
+                    S_CUR[0][r] -= delta;                                                                           \
+                    S_CUR[1][r] -= delta;                                                                           \
+                }                                                                                                   \
             }                                                                                                       \
         }                                                                                                           \
         const unsigned kt_a = lds_a + (((I) + 1) & (NS - 1)) * STAGE_BYTES;            /* K8 of kblock I + 1 */      \
@@ -502,7 +529,8 @@ __device__ __forceinline__ void f8_segment_sp(const AttnParams& p, const AttnChu
             f8_lds_wait<Plan::wait()>(fr[Plan::buffer(k)][0], fr[Plan::buffer(k)][1]);                                                             \
             if (k < NK) {                                                                                           \
                 const int R = k / DH, dh = k % DH;                                                                  \
-                S_NEXT[R] = f8_mfma(f8_join(fr[Plan::buffer(k)][0], fr[Plan::buffer(k)][1]), qf[dh], dh == 0 ? negm : S_NEXT[R]);       \
+                S_NEXT[R] = f8_mfma(f8_join(fr[Plan::buffer(k)][0], fr[Plan::buffer(k)][1]), qf[dh],                \
+                                    dh == 0 ? (LOGLIN ? zero16 : negm) : S_NEXT[R]);                                \
             } else {                                                                                                \
                 const int db = k - NK;                                                                              \
                 if (EDGE && edge) {                                                                                 \
@@ -511,7 +539,8 @@ __device__ __forceinline__ void f8_segment_sp(const AttnParams& p, const AttnChu
                         fr[Plan::buffer(k)][1][j] &= vmask[4 + j];                                                            \
                     }                                                                                               \
                 }                                                                                                   \
-                st.o[db] = f8_mfma(f8_join(fr[Plan::buffer(k)][0], fr[Plan::buffer(k)][1]), pb, st.o[db]);                              \
+                st.o[db] = f8_mfma(f8_join(fr[Plan::buffer(k)][0], fr[Plan::buffer(k)][1]), pb, st.o[db]);          \
+                if (LOGLIN && k == NK) lacc = f8_mfma(ones, pb, lacc);     /* row sums of the 8-bit weights */       \
             }                                                                                                       \
             if (k >= DMA_FIRST && (k - DMA_FIRST) % DMA_STEP == 0 && (k - DMA_FIRST) / DMA_STEP < LPW) {            \
                 const int v = min((I) + PF, ve - 1);                                                                \
@@ -523,18 +552,28 @@ __device__ __forceinline__ void f8_segment_sp(const AttnParams& p, const AttnChu
             if (k < NK) {                                                                                           \
                 _Pragma("unroll") for (int g = k * QPS; g < (k + 1) * QPS; ++g) {                                   \
                     const int R = g / 4, r = 4 * (g % 4);                                                           \
-                    const float e0 = __builtin_amdgcn_exp2f(S_CUR[R][r]), e1 = __builtin_amdgcn_exp2f(S_CUR[R][r + 1]);     \
-                    const float e2 = __builtin_amdgcn_exp2f(S_CUR[R][r + 2]), e3 = __builtin_amdgcn_exp2f(S_CUR[R][r + 3]); \
-                    lsum0 += e0;                                                                                    \
-                    lsum1 += e1;                                                                                    \
-                    lsum0 += e2;                                                                                    \
-                    lsum1 += e3;                                                                                    \
-                    int w = __builtin_amdgcn_cvt_pk_fp8_f32(e0, e1, 0, false);                                      \
-                    w = __builtin_amdgcn_cvt_pk_fp8_f32(e2, e3, w, true);                                           \
-                    pb[g] = w;                                                                                      \
-                    F8_PIN(w);                                                                                      \
-                    F8_PIN(lsum0);                                                                                  \
-                    F8_PIN(lsum1);                                                                                  \
+                    if (LOGLIN) {                                                                                   \
+                        unsigned w = 0;                                                                             \
+                        w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf(S_CUR[R][r], 8.0f, bias), 0, w);          \
+                        w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf(S_CUR[R][r + 1], 8.0f, bias), 1, w);      \
+                        w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf(S_CUR[R][r + 2], 8.0f, bias), 2, w);      \
+                        w = __builtin_amdgcn_cvt_pk_u8_f32(__builtin_fmaf(S_CUR[R][r + 3], 8.0f, bias), 3, w);      \
+                        pb[g] = int(w);                                                                             \
+                        F8_PIN(w);                                                                                  \
+                    } else {                                                                                        \
+                        const float e0 = __builtin_amdgcn_exp2f(S_CUR[R][r]), e1 = __builtin_amdgcn_exp2f(S_CUR[R][r + 1]);     \
+                        const float e2 = __builtin_amdgcn_exp2f(S_CUR[R][r + 2]), e3 = __builtin_amdgcn_exp2f(S_CUR[R][r + 3]); \
+                        lsum0 += e0;                                                                                \
+                        lsum1 += e1;                                                                                \
+                        lsum0 += e2;                                                                                \
+                        lsum1 += e3;                                                                                \
+                        int w = __builtin_amdgcn_cvt_pk_fp8_f32(e0, e1, 0, false);                                  \
+                        w = __builtin_amdgcn_cvt_pk_fp8_f32(e2, e3, w, true);                                       \
+                        pb[g] = w;                                                                                  \
+                        F8_PIN(w);                                                                                  \
+                        F8_PIN(lsum0);                                                                              \
+                        F8_PIN(lsum1);                                                                              \
+                    }                                                                                               \
                 }                                                                                                   \
             } else {                                                                                                \
                 _Pragma("unroll") for (int b = (k - NK) * MPS; b < (k - NK + 1) * MPS; b += 2)                      \
@@ -543,7 +582,7 @@ __device__ __forceinline__ void f8_segment_sp(const AttnParams& p, const AttnChu
             __builtin_amdgcn_sched_barrier(0);                                                                      \
         }                                                                                                           \
         mx = m_run;                                                                                                 \
-        vote = __any(mx > F8_SHIFT + F8_SLACK);                                                                     \
+        vote = __any(mx - (LOGLIN ? mref : F8_SHIFT) > F8_SLACK);                                                   \
         if (EDGE && edge) {                                                                                         \
             _Pragma("unroll") for (int j = 0; j < 8; ++j) vmask[j] = 0xFFFFFFFFu;                                   \
         }                                                                                                           \
@@ -575,7 +614,8 @@ __device__ __forceinline__ void f8_segment_sp(const AttnParams& p, const AttnChu
 #undef F8_PHYS_KB
 #undef F8_LIVE
     __builtin_amdgcn_s_waitcnt(0);
-    st.l = lsum0 + lsum1;
+    // LOGLIN: the MFMA has summed over both key halves already, and both lanes of a query hold that sum
+    st.l = LOGLIN ? 0.5f * lacc[0] : lsum0 + lsum1;
 }
 
 // A wave without queries in a chunk's short last tile: its share of the loads, waits and barriers only.
@@ -647,7 +687,9 @@ __device__ __forceinline__ void f8_store_out(const AttnParams& p, int head, int 
 }
 
 // ---- one workgroup per (head, query tile); placement on the XCDs as in attn_stream.hip
-template <int D, bool PIPE>
+// MODE 0: compiler-scheduled form, 1: explicit pipeline with exact exponentials, 2: explicit pipeline with the
+// log-linear weights
+template <int D, int MODE>
 __global__ __launch_bounds__(F8_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_attn_fp8_kernel(const AttnParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -683,16 +725,19 @@ __global__ __launch_bounds__(F8_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
         return;
     }
     F8State<D> st;
-    if (PIPE) f8_segment_sp<D>(p, ch, head, q0, lds, st);
+    if (MODE == 2) f8_segment_sp<D, true>(p, ch, head, q0, lds, st);
+    else if (MODE == 1) f8_segment_sp<D, false>(p, ch, head, q0, lds, st);
     else f8_segment<D>(p, ch, head, q0, lds, st);
     f8_store_out<D>(p, head, q0, ch.q_end, st);
 }
 
 const AttnVariant kFp8Variants[] = {
-    {"d128_fp8", 128, 256, 8 * 2 * KBLOCK8 * 128, ll_attn_fp8_kernel<128, true>, F8_THREADS, KBLOCK8},
-    {"d64_fp8", 64, 256, 8 * 2 * KBLOCK8 * 64, ll_attn_fp8_kernel<64, true>, F8_THREADS, KBLOCK8},
-    {"d128_fp8_simple", 128, 256, 8 * 2 * KBLOCK8 * 128, ll_attn_fp8_kernel<128, false>, F8_THREADS, KBLOCK8},
-    {"d64_fp8_simple", 64, 256, 8 * 2 * KBLOCK8 * 64, ll_attn_fp8_kernel<64, false>, F8_THREADS, KBLOCK8},
+    {"d128_fp8", 128, 256, 8 * 2 * KBLOCK8 * 128, ll_attn_fp8_kernel<128, 1>, F8_THREADS, KBLOCK8},
+    {"d64_fp8", 64, 256, 8 * 2 * KBLOCK8 * 64, ll_attn_fp8_kernel<64, 1>, F8_THREADS, KBLOCK8},
+    {"d128_fp8_simple", 128, 256, 8 * 2 * KBLOCK8 * 128, ll_attn_fp8_kernel<128, 0>, F8_THREADS, KBLOCK8},
+    {"d64_fp8_simple", 64, 256, 8 * 2 * KBLOCK8 * 64, ll_attn_fp8_kernel<64, 0>, F8_THREADS, KBLOCK8},
+    {"d128_fp8_loglin", 128, 256, 8 * 2 * KBLOCK8 * 128, ll_attn_fp8_kernel<128, 2>, F8_THREADS, KBLOCK8},
+    {"d64_fp8_loglin", 64, 256, 8 * 2 * KBLOCK8 * 64, ll_attn_fp8_kernel<64, 2>, F8_THREADS, KBLOCK8},
 };
 const int kNumFp8Variants = sizeof(kFp8Variants) / sizeof(kFp8Variants[0]);
 

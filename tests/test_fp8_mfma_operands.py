@@ -29,12 +29,12 @@ def test_no_result_over_operand():
         d, a, b = (int(d0), int(d1)), (int(a0), int(a1)), (int(b0), int(b1))
         assert d[1] < a[0] or a[1] < d[0], f"result v[{d0}:{d1}] overlaps operand A v[{a0}:{a1}]"
         assert d[1] < b[0] or b[1] < d[0], f"result v[{d0}:{d1}] overlaps operand B v[{b0}:{b1}]"
-        assert c.startswith("v["), f"accumulator input is not a register tuple: {c}"
+        assert c.startswith("v[") or c == "0", f"accumulator input is neither a register tuple nor zero: {c}"
     # the pipelined kernels issue LDS reads whose destination registers stay pending until a counted wait: a spill
     # of such a register in between would store stale data, so these kernels must not spill at all
     spills = dict(re.findall(r"\.name:\s+(\S+)[\s\S]*?\.vgpr_spill_count:\s+(\d+)", text))
-    piped = {k: int(v) for k, v in spills.items() if "ll_attn_fp8_kernel" in k and "ELb1E" in k}
-    assert len(piped) == 2 and all(v == 0 for v in piped.values()), f"spills in the pipelined kernels: {piped}"
+    piped = {k: int(v) for k, v in spills.items() if "ll_attn_fp8_kernel" in k and ("ELi1E" in k or "ELi2E" in k)}
+    assert len(piped) == 4 and all(v == 0 for v in piped.values()), f"spills in the pipelined kernels: {piped}"
 
 
 def test_bf16_stream_kernels_do_not_spill():
