@@ -102,7 +102,7 @@ def single_layer_stats(w, gen, warmup=10, iters=50, kv_format="bf16", sink_relat
     return res
 
 
-def fp8_cache_stats(w_loop, gen, q, k, v, steps, only_step=False):
+def fp8_cache_stats(w_loop, gen, q, k, v, steps, only_step=False, variant=0):
     """The 8-bit (E4M3) cache variant: a different accuracy tier, reported next to the bf16 figures and never as
     `value`.  Single-layer launch statistics, the 30-layer chunk step (append + attention, wall clock), and the
     distance between the two paths' outputs on the same inputs."""
@@ -117,6 +117,13 @@ def fp8_cache_stats(w_loop, gen, q, k, v, steps, only_step=False):
     if not only_step:
         res["single_layer"] = {"cfg2": single_layer_stats(synth.WAN_LAYER, gen, kv_format="fp8_e4m3"),
                                "cfg4": single_layer_stats(synth.LONG_WINDOW, gen, kv_format="fp8_e4m3")}
+        names = {n: i for i, n in binding.attn_variant_names().items()}
+        if "d128_fp8_loglin" in names:      # the cheaper weights (a linear map to the E4M3 code instead of exp2)
+            binding.set_attn_variant(names["d128_fp8_loglin"])
+            try:
+                res["single_layer"]["cfg2_loglin_weights"] = single_layer_stats(synth.WAN_LAYER, gen, kv_format="fp8_e4m3")
+            finally:
+                binding.set_attn_variant(variant)
         res.update(_fp8_vs_bf16(q, k, v, L, Hh, D, Cf))
     return _fp8_step(res, w, q, k, v, steps)
 
@@ -287,7 +294,7 @@ def main():
         return t
     q, k, v = gen_bf16(), gen_bf16(), gen_bf16()
     if args.fp8_only:
-        print(json.dumps({"fp8_cache": fp8_cache_stats(w, gen, q, k, v, args.steps, only_step=True)}))
+        print(json.dumps({"fp8_cache": fp8_cache_stats(w, gen, q, k, v, args.steps, only_step=True, variant=args.variant)}))
         return
     qr = torch.empty((L, nq, Hh, D), dtype=torch.bfloat16, device="cuda")
     out = torch.empty((L, nq, Hh, D), dtype=torch.bfloat16, device="cuda")
@@ -446,7 +453,7 @@ def main():
                          "attn_kernel_vs_random_operand_probe": round(attn_tflops / pr_t, 4)}
 
     if not args.no_fp8:
-        res["fp8_cache"] = fp8_cache_stats(w, gen, q, k, v, args.steps)
+        res["fp8_cache"] = fp8_cache_stats(w, gen, q, k, v, args.steps, variant=args.variant)
 
     if args.probe_copy:
         src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(3)
