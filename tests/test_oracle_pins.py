@@ -553,3 +553,84 @@ def test_sink_relative_is_invariant_under_window_position():
     a = Oracle(cfg).recache_prefill(0, True, 400, W + C, qz_bits, k, v)
     b = SinkRelativeOracle(cfg).recache_prefill(0, True, 400, W + C, qz_bits, k, v)
     assert np.abs(a - b).max() < 1e-12
+
+
+# ---- P20-P23: the prompt side of KV-recache (Sec. 3.1, Fig. 2 right): cross-attention over the prompt's keys ----
+from oracle.prompt_cross_attention import PromptOracle, cross_attention  # noqa: E402
+
+
+def _randn(shape, seed):
+    return np.random.Generator(np.random.Philox(key=seed)).standard_normal(shape)
+
+
+# P20: the definition as loops, and a library's scaled-dot-product attention (fp64, CPU)
+def test_cross_attention_loops_and_library():
+    nq, nt, H, D = 7, 5, 2, 6
+    q, k, v = _randn((nq, H, D), 50), _randn((nt, H, D), 51), _randn((nt, H, D), 52)
+    got = cross_attention(q, k, v)
+    for i in range(nq):
+        for h in range(H):
+            s = [sum(q[i, h, d] * k[j, h, d] for d in range(D)) / math.sqrt(D) for j in range(nt)]
+            w = [math.exp(x) for x in s]
+            for d in range(D):
+                ref = sum(w[j] * v[j, h, d] for j in range(nt)) / sum(w)
+                assert abs(got[i, h, d] - ref) < 1e-12
+    nq, nt, H, D = 70, 45, 3, 32
+    q, k, v = _randn((nq, H, D), 53), 3.0 * _randn((nt, H, D), 54), _randn((nt, H, D), 55)
+    tq, tk, tv = (torch.from_numpy(a).permute(1, 0, 2) for a in (q, k, v))
+    lib = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv).permute(1, 0, 2).numpy()
+    assert np.abs(cross_attention(q, k, v) - lib).max() < 1e-12
+
+
+# P21: closed forms
+def test_cross_attention_closed_forms():
+    nq, H, D = 9, 2, 8
+    q = _randn((nq, H, D), 56)
+    v = _randn((6, H, D), 57)
+    one = cross_attention(q, _randn((1, H, D), 58), v[:1])              # one token: its value, whatever the scores
+    assert np.abs(one - v[:1]).max() < 1e-15
+    same = cross_attention(q, np.repeat(_randn((1, H, D), 59), 6, axis=0), v)   # equal keys: the mean of the values
+    assert np.abs(same - v.mean(axis=0, keepdims=True)).max() < 1e-14
+    # a key aligned with the query and scaled up takes all the weight, for that query and head only
+    k = np.zeros((6, H, D))
+    k[4, 1] = 200.0 * q[3, 1] / np.linalg.norm(q[3, 1])
+    out = cross_attention(q[3:4], k, v)
+    assert np.abs(out[0, 1] - v[4, 1]).max() < 1e-12
+    assert np.abs(out[0, 0] - v[:, 0].mean(axis=0)).max() < 1e-14       # head 0 has all-zero keys
+    # the scale: with orthonormal keys e_j and q = t sqrt(D) e_0 the weights are softmax((t, 0, ..., 0))
+    t = 1.7
+    k = np.eye(D)[:4].reshape(4, 1, D)
+    qq = (t * math.sqrt(D) * np.eye(D)[0]).reshape(1, 1, D)
+    vv = np.eye(4).reshape(4, 1, 4)
+    vv = np.concatenate([vv, np.zeros((4, 1, D - 4))], axis=2)
+    w = cross_attention(qq, k, vv)[0, 0, :4]
+    assert np.abs(w - np.array([math.exp(t), 1, 1, 1]) / (math.exp(t) + 3)).max() < 1e-15
+
+
+# P22: the prompt's tokens carry no position: any order of them gives the same output
+def test_cross_attention_ignores_token_order():
+    nq, nt, H, D = 11, 13, 2, 16
+    q, k, v = _randn((nq, H, D), 60), _randn((nt, H, D), 61), _randn((nt, H, D), 62)
+    perm = np.random.Generator(np.random.Philox(key=63)).permutation(nt)
+    assert np.abs(cross_attention(q, k, v) - cross_attention(q, k[perm], v[perm])).max() < 1e-13
+    assert np.abs(cross_attention(q, k, v) - cross_attention(q, k[perm], v)).max() > 1e-3   # pairs stay together
+
+
+# P23: after a switch nothing of the former prompt is left, also when the new prompt is shorter
+def test_prompt_recache_replaces_everything():
+    L, H, D = 2, 2, 8
+    q = _randn((5, H, D), 64)
+    k_new, v_new = _randn((3, H, D), 65), _randn((3, H, D), 66)
+    outs = []
+    for old_seed, old_len in ((67, 9), (68, 3), (69, 1)):
+        o = PromptOracle(L, H, D)
+        o.recache(1, 50.0 * _randn((old_len, H, D), old_seed), _randn((old_len, H, D), old_seed + 10))
+        before = o.cross_attn(1, q)
+        o.recache(1, k_new, v_new)
+        assert o.tokens(1) == 3 and o.tokens(0) == 0
+        outs.append(o.cross_attn(1, q))
+        assert np.abs(outs[-1] - before).max() > 1e-3
+    assert np.abs(outs[0] - outs[1]).max() == 0 and np.abs(outs[0] - outs[2]).max() == 0
+    assert np.abs(outs[0] - cross_attention(q, k_new, v_new)).max() == 0
+    with pytest.raises(RuntimeError):
+        PromptOracle(L, H, D).cross_attn(0, q)
