@@ -169,6 +169,36 @@ ll_status ll_cache_read_frame(const ll_cache* cache, int layer, int64_t frame, v
  * if a kernel variant without this mode was selected with ll_set_attn_variant. */
 ll_status ll_cache_set_sink_relative(ll_cache* cache, int on);
 
+/* ---- The prompt side of KV-recache (Sec. 3.1 "KV Recache", Fig. 2 right).  The prompt reaches the video tokens
+ * through the cross-attention layers; at a prompt switch the cached state is rebuilt from the generated frames paired
+ * with the NEW prompt: ll_recache_prefill rebuilds the self-attention side, and the calls below hold, replace and
+ * read the per-layer keys and values projected from the prompt's embeddings (the projections belong to the model;
+ * k and v come in as tensors).  No mask and no positional embedding: every query sees every prompt token,
+ *     out = softmax(q k^T / sqrt(D)) v   per head.
+ * A handle is independent of any ll_cache.  Calls for one layer must be made in program order. */
+typedef struct ll_prompt ll_prompt;
+
+/* Bytes of device memory ll_prompt_create needs; 0 if the shapes are invalid (head_dim 64 or 128, max_tokens in
+ * [1, 65536]). */
+size_t ll_prompt_bytes(int layers, int heads, int head_dim, int max_tokens);
+/* dev_buffer: device, 256-byte aligned, at least ll_prompt_bytes(...) bytes, owned by the caller, must outlive the
+ * handle; it is zeroed (synchronous, null stream).  NULL with dev_bytes == 0 makes an index-only handle whose
+ * compute calls take NULL tensors and enqueue nothing. */
+ll_status ll_prompt_create(int layers, int heads, int head_dim, int max_tokens, void* dev_buffer, size_t dev_bytes,
+                           ll_prompt** out);
+ll_status ll_prompt_destroy(ll_prompt* prompt);
+/* Replace layer `layer`'s prompt keys and values by those of a (new) prompt of n_tokens tokens, 1 <= n_tokens <=
+ * max_tokens.  k, v: device, bf16 [n_tokens, H, D].  Nothing of the former prompt remains visible, also when the new
+ * one is shorter.  Enqueues one kernel; later ll_cross_attn calls on the same stream read the new prompt. */
+ll_status ll_prompt_recache(ll_prompt* prompt, int layer, const void* k, const void* v, int n_tokens, void* stream);
+/* Tokens of layer `layer`'s current prompt (0 before the first ll_prompt_recache). */
+ll_status ll_prompt_tokens(const ll_prompt* prompt, int layer, int* n_tokens);
+/* Cross-attention of n_q query rows over layer `layer`'s prompt.  q: device, bf16 [n_q, H, D], as the model's query
+ * projection made them (the kernel multiplies by log2(e)/sqrt(D) itself and rounds the product to bf16 once);
+ * out: device, bf16 [n_q, H, D]; out may be q itself (a wave reads exactly the rows it writes), any other overlap is
+ * an error the library cannot detect.  1 <= n_q <= 2^24.  LL_ERR_STATE if the layer has no prompt yet. */
+ll_status ll_cross_attn(const ll_prompt* prompt, int layer, const void* q, int n_q, void* out, void* stream);
+
 /* Attention kernel variant: 0 = default for the shape, otherwise a variant id listed by
  * ll_attn_variant_name.  Process-wide tuning knob for benchmarking. */
 ll_status ll_set_attn_variant(int variant);

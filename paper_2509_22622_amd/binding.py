@@ -34,6 +34,12 @@ SIGNATURES = {
     "ll_cache_live_ranges": (_i, [_vp, _i, C.POINTER(_i64), _i, C.POINTER(_i)]),
     "ll_cache_read_frame": (_i, [_vp, _i, _i64, _vp, _vp, _vp]),
     "ll_cache_set_sink_relative": (_i, [_vp, _i]),
+    "ll_prompt_bytes": (_sz, [_i] * 4),
+    "ll_prompt_create": (_i, [_i] * 4 + [_vp, _sz, C.POINTER(_vp)]),
+    "ll_prompt_destroy": (_i, [_vp]),
+    "ll_prompt_recache": (_i, [_vp, _i, _vp, _vp, _i, _vp]),
+    "ll_prompt_tokens": (_i, [_vp, _i, C.POINTER(_i)]),
+    "ll_cross_attn": (_i, [_vp, _i, _vp, _i, _vp, _vp]),
     "ll_set_attn_variant": (_i, [_i]),
     "ll_attn_variant_name": (C.c_char_p, [_i]),
     "ll_probe_mfma_rate": (_i, [C.c_void_p, C.c_size_t, _i, _i, _i, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
@@ -204,3 +210,57 @@ class Cache:
 
     def read_frame(self, layer, frame, k_out, v_out):
         _check(lib().ll_cache_read_frame(self._h, layer, frame, _ptr(k_out), _ptr(v_out), _stream()))
+
+
+class Prompt:
+    """Handle on the per-layer keys and values of the active prompt (``ll_prompt_*``, ``ll_cross_attn``).
+    ``device=None`` makes an index-only handle."""
+
+    def __init__(self, layers, heads, head_dim, max_tokens, device="cuda"):
+        self.layers, self.heads, self.head_dim, self.max_tokens = layers, heads, head_dim, max_tokens
+        self._h = C.c_void_p()
+        self.buffer = None
+        nbytes = lib().ll_prompt_bytes(layers, heads, head_dim, max_tokens)
+        if device is not None:
+            import torch
+            if nbytes == 0:
+                raise LongLiveError(1, "invalid shape")
+            self.buffer = torch.empty(nbytes, dtype=torch.uint8, device=device)
+            ptr, size = C.c_void_p(self.buffer.data_ptr()), nbytes
+        else:
+            ptr, size = None, 0
+        _check(lib().ll_prompt_create(layers, heads, head_dim, max_tokens, ptr, size, C.byref(self._h)))
+
+    def close(self):
+        if self._h:
+            lib().ll_prompt_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def recache(self, layer, k, v, n_tokens=None):
+        """Replace the layer's prompt keys and values: k, v bf16 [n_tokens, H, D] on the device."""
+        if n_tokens is None:
+            n_tokens = k.shape[0]
+        if self.buffer is not None:
+            _check(lib().ll_prompt_recache(self._h, layer, _ptr(k), _ptr(v), n_tokens, _stream()))
+        else:
+            _check(lib().ll_prompt_recache(self._h, layer, None, None, n_tokens, None))
+
+    def tokens(self, layer) -> int:
+        n = C.c_int()
+        _check(lib().ll_prompt_tokens(self._h, layer, C.byref(n)))
+        return n.value
+
+    def cross_attn(self, layer, q, out, n_q=None):
+        """out = softmax(q k^T / sqrt(D)) v over the layer's prompt; q, out bf16 [n_q, H, D] on the device."""
+        if n_q is None:
+            n_q = q.shape[0]
+        if self.buffer is not None:
+            _check(lib().ll_cross_attn(self._h, layer, _ptr(q), n_q, _ptr(out), _stream()))
+        else:
+            _check(lib().ll_cross_attn(self._h, layer, None, n_q, None, None))

@@ -65,7 +65,9 @@ __global__ __launch_bounds__(256) void ll_append_kernel(const AppendParams p) {
         const int tok = tok0 + ti;
         const int y = tok / p.grid_w, x = tok % p.grid_w;
         const int64_t src = ((row0 + ti) * p.H + head) * D + c * 8;
-        const u16x8 qv = *reinterpret_cast<const u16x8*>(p.q + src);
+        const bool has_q = p.q != nullptr;                              // uniform: keys and values only otherwise
+        u16x8 qv = {};
+        if (has_q) qv = *reinterpret_cast<const u16x8*>(p.q + src);
         const u16x8 kv = *reinterpret_cast<const u16x8*>(p.k + src);
         const u16x8 vv = *reinterpret_cast<const u16x8*>(p.v + src);
         u16x8 qo, ko;
@@ -83,7 +85,7 @@ __global__ __launch_bounds__(256) void ll_append_kernel(const AppendParams p) {
             ko[2 * e] = f32_to_bf16(kr * cs.x - ki * cs.y);
             ko[2 * e + 1] = f32_to_bf16(kr * cs.y + ki * cs.x);
         }
-        *reinterpret_cast<u16x8*>(p.q_out + src) = qo;
+        if (has_q) *reinterpret_cast<u16x8*>(p.q_out + src) = qo;
         *reinterpret_cast<u16x8*>(k_img + (c * 32 + swap23(k_lo + ti)) * 8) = ko;
         *reinterpret_cast<u16x8*>(v_rows + (k_lo + ti) * VROW + c * 8) = vv;
     }

@@ -286,7 +286,9 @@ int attn_variant_default(int D, int kblock) {
 int attn_variant_qtile(int v) { return variant(v)->qtile; }
 bool attn_variant_supports(int v, int D, int kblock) { return variant(v) && variant(v)->D == D && variant(v)->kblock == kblock; }
 // only the software-pipelined bf16 kernels take queries turned back for the sink range (AttnChunk::sink_shift)
-bool attn_variant_sink_shift(int v) { return v > kNumSimple && v <= kNumSimple + kNumStreamVariants; }
+bool attn_variant_sink_shift(int v) { return v > kNumSimple && v <= kNumSimple + 2; }
+// the software-pipelined kernel that multiplies the queries by AttnParams::scale_log2e itself
+int attn_variant_qscale(int D) { return kNumSimple + (D == 128 ? 3 : 4); }
 
 hipError_t launch_attn(const AttnParams& p_in, int variant, hipStream_t s) {
     if (!attn_variant_supports(variant, p_in.D, p_in.kblock)) return hipErrorInvalidValue;

@@ -129,7 +129,7 @@ struct SpState {
 };
 
 // Virtual kblocks [vb, ve) of chunk `ch` for the 32 queries starting at row q0 of head `head`.
-template <int D>
+template <int D, bool QSCALE = false>
 __device__ __forceinline__ void sp_segment(const AttnParams& p, const AttnChunk& ch, int head, int q0, int vb, int ve,
                                            char* lds, SpState<D>& st, const float2* shift_cs) {
     constexpr int KS = D / 16;                  // k-steps of S^T = K Q^T, also fragments per K kblock
@@ -173,6 +173,13 @@ __device__ __forceinline__ void sp_segment(const AttnParams& p, const AttnChunk&
     const uint16_t* q_src = p.q + (int64_t(min(q0 + col, q_end - 1)) * p.H + head) * D + half * 8;
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) qf[ks] = *reinterpret_cast<const bf16x8*>(q_src + ks * 16);
+    if constexpr (QSCALE) {                     // queries that come as the model made them: fold the factor in here,
+        const float c = p.scale_log2e;          // one rounding of the scaled value, as the append kernel does
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks)
+#pragma unroll
+            for (int j = 0; j < 8; ++j) qf[ks][j] = __bf16(float(qf[ks][j]) * c);
+    }
     // Sink at a fixed rotary distance: range 0 is the sink, and its scores are taken with the queries turned back
     // by sink_shift frames on the frame axis: pair i (features 2i, 2i+1) times exp(-i * shift * freq_i), from the
     // table the workgroup prepared.  The scores of kblock v are computed one step ahead, so the unturned queries
@@ -489,7 +496,7 @@ __device__ __forceinline__ void sp_store_out(const AttnParams& p, int head, int 
 }
 
 // ---- one workgroup per (head, query tile)
-template <int D>
+template <int D, bool QSCALE>
 __global__ __launch_bounds__(SP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_attn_stream_kernel(const AttnParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     __shared__ float2 shift_cs[64];              // (cos, sin) of sink_shift * frame-axis frequency, per rotary pair
@@ -543,13 +550,17 @@ __global__ __launch_bounds__(SP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
         return;
     }
     SpState<D> st;
-    sp_segment<D>(p, ch, head, q0, 0, ch.n_kblocks, lds, st, shift_cs);
+    sp_segment<D, QSCALE>(p, ch, head, q0, 0, ch.n_kblocks, lds, st, shift_cs);
     sp_store_out<D>(p, head, q0, ch.q_end, st);
 }
 
 const AttnVariant kStreamVariants[] = {
-    {"d128_stream", 128, 256, 8 * 2 * KBLOCK * 128 * 2, ll_attn_stream_kernel<128>, SP_THREADS, KBLOCK},
-    {"d64_stream", 64, 256, 8 * 2 * KBLOCK * 64 * 2, ll_attn_stream_kernel<64>, SP_THREADS, KBLOCK},
+    {"d128_stream", 128, 256, 8 * 2 * KBLOCK * 128 * 2, ll_attn_stream_kernel<128, false>, SP_THREADS, KBLOCK},
+    {"d64_stream", 64, 256, 8 * 2 * KBLOCK * 64 * 2, ll_attn_stream_kernel<64, false>, SP_THREADS, KBLOCK},
+    // the same kernels for queries not yet multiplied by log2(e)/sqrt(D) (AttnParams::scale_log2e): cross-attention
+    // over the prompt's keys, whose queries pass through no rotary step that could fold the factor in
+    {"d128_stream_qscale", 128, 256, 8 * 2 * KBLOCK * 128 * 2, ll_attn_stream_kernel<128, true>, SP_THREADS, KBLOCK},
+    {"d64_stream_qscale", 64, 256, 8 * 2 * KBLOCK * 64 * 2, ll_attn_stream_kernel<64, true>, SP_THREADS, KBLOCK},
 };
 const int kNumStreamVariants = sizeof(kStreamVariants) / sizeof(kStreamVariants[0]);
 

@@ -64,7 +64,7 @@ struct RopeTables {            // device pointers into the cache buffer's tail
 };
 
 struct AppendParams {
-    const uint16_t* q; const uint16_t* k; const uint16_t* v;   // [n_frames*P, H, D]
+    const uint16_t* q; const uint16_t* k; const uint16_t* v;   // [n_frames*P, H, D]; q null (bf16 cache only): K, V only
     uint16_t* q_out;                                            // same shape; rotated q times q_scale
     float q_scale;                                              // log2(e) / sqrt(D), folded into q_out
     uint16_t* k_cache; uint16_t* v_cache;                       // layer base (head 0)
@@ -96,7 +96,8 @@ struct AttnParams {
     const uint16_t* k_cache; const uint16_t* v_cache;   // layer base (head 0)
     int64_t head_stride;
     int H, D;
-    float scale_log2e;           // factor still to apply to q.k in the log2 domain (1 when q is pre-scaled)
+    float scale_log2e;           // factor still to apply to q.k in the log2 domain (1 when q is pre-scaled); only
+                                 // the simple kernels and the *_qscale kernels apply it
     int n_chunks, n_tiles;       // n_tiles = query tiles over all chunks
     // Placement on the 8 XCDs (filled in by launch_attn; workgroup b runs on XCD b % 8).  n_groups == 0: the
     // (head, tile) items are split into 8 contiguous runs.  Otherwise (launches of several chunks, whose tiles
@@ -142,6 +143,7 @@ int attn_variant_default(int D, int kblock);
 int attn_variant_qtile(int v);                 // query rows per workgroup
 bool attn_variant_supports(int v, int D, int kblock);
 bool attn_variant_sink_shift(int v);          // the variant honours AttnChunk::sink_shift
+int attn_variant_qscale(int D);                // the variant for queries not yet scaled (honours scale_log2e)
 
 hipError_t launch_append(const AppendParams& p, hipStream_t s);
 hipError_t launch_append8(const AppendParams& p, hipStream_t s);

@@ -22,6 +22,16 @@ int main(void) {
     if (strlen(ll_last_error()) == 0 || strcmp(ll_status_string(LL_ERR_STATE), "LL_ERR_STATE") != 0) return 10;
     if (ll_sink_window_attn(c, 0, NULL, NULL, NULL) != LL_ERR_INVALID_ARG) return 11;   /* no device cache */
     if (ll_cache_destroy(c) != LL_OK) return 12;
+    {                                                                        /* the prompt side, index-only */
+        ll_prompt* pr = NULL;
+        if (ll_prompt_bytes(2, 2, 64, 77) == 0 || ll_prompt_bytes(2, 2, 64, 0) != 0) return 13;
+        if (ll_prompt_create(2, 2, 64, 77, NULL, 0, &pr) != LL_OK) return 14;
+        if (ll_cross_attn(pr, 1, NULL, 10, NULL, NULL) != LL_ERR_STATE) return 15;
+        if (ll_prompt_recache(pr, 1, NULL, NULL, 40, NULL) != LL_OK) return 16;
+        if (ll_prompt_tokens(pr, 1, &n) != LL_OK || n != 40) return 17;
+        if (ll_cross_attn(pr, 1, NULL, 10, NULL, NULL) != LL_OK) return 18;
+        if (ll_prompt_destroy(pr) != LL_OK) return 19;
+    }
     printf("c abi ok\n");
     return 0;
 }

@@ -221,3 +221,44 @@ def test_fp8_and_sink_relative_handles_share_the_bookkeeping():
         h8.set_sink_relative(True)
     assert e.value.status == B.LL_ERR_UNSUPPORTED
     h8.close()
+
+
+def test_prompt_handle_bookkeeping_and_errors():
+    """The prompt side's host logic on an index-only handle: sizes, argument checks, call order."""
+    L = B.lib()
+    assert L.ll_prompt_bytes(30, 12, 128, 512) >= 30 * 12 * 2 * 512 * 128 * 2
+    for bad in ((0, 12, 128, 512), (1, 0, 128, 512), (1, 12, 96, 512), (1, 12, 128, 0), (1, 12, 128, 65537)):
+        assert L.ll_prompt_bytes(*bad) == 0, bad
+    with pytest.raises(B.LongLiveError) as e:
+        B.Prompt(1, 12, 96, 512, device=None)
+    assert e.value.status == 4
+    h = C.c_void_p()
+    assert L.ll_prompt_create(1, 2, 64, 77, None, 16, C.byref(h)) == 1          # null buffer with a size
+    assert L.ll_prompt_create(1, 2, 64, 77, None, 0, None) == 1
+    p = B.Prompt(3, 2, 64, 77, device=None)
+    assert [p.tokens(l) for l in range(3)] == [0, 0, 0]
+    with pytest.raises(B.LongLiveError) as e:
+        p.cross_attn(1, None, None, n_q=10)                                     # no prompt yet
+    assert e.value.status == 2
+    for bad in (lambda: p.recache(3, None, None, 5), lambda: p.recache(-1, None, None, 5),
+                lambda: p.recache(0, None, None, 0), lambda: p.recache(0, None, None, 78),
+                lambda: p.tokens(3)):
+        with pytest.raises(B.LongLiveError) as e:
+            bad()
+        assert e.value.status == 1
+    p.recache(1, None, None, 77)
+    p.recache(1, None, None, 40)                                                # the switch: shorter prompt
+    assert [p.tokens(l) for l in range(3)] == [0, 40, 0]                        # layers are independent
+    p.cross_attn(1, None, None, n_q=4680)
+    for n_q in (0, -3, (1 << 24) + 1):
+        with pytest.raises(B.LongLiveError) as e:
+            p.cross_attn(1, None, None, n_q=n_q)
+        assert e.value.status == 1
+    with pytest.raises(B.LongLiveError) as e:
+        p.cross_attn(0, None, None, n_q=10)
+    assert e.value.status == 2
+    one = C.c_int(1)                                                            # any non-null pointer: refused before use
+    with pytest.raises(B.LongLiveError) as e:
+        B._check(L.ll_prompt_recache(p._h, 0, C.cast(C.pointer(one), C.c_void_p), None, 5, None))
+    assert e.value.status == 1
+    p.close()
