@@ -102,6 +102,55 @@ def single_layer_stats(w, gen, warmup=10, iters=50, kv_format="bf16", sink_relat
     return res
 
 
+def prompt_side_stats(w, gen, n_text=512, reps=5):
+    """The prompt side of KV-recache: cross-attention of one chunk's and of one re-prefill's queries over a prompt of
+    `n_text` tokens, 30 layers back to back (HIP events around the 30 launches), and the replacement of the prompt's
+    keys and values in all layers."""
+    import torch
+    from paper_2509_22622_amd import binding
+    L, Hh, D = w.layers, w.heads, w.head_dim
+    prompt = binding.Prompt(L, Hh, D, n_text)
+    k, v = (torch.randn((n_text, Hh, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16) for _ in range(2))
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+
+    def timed(fn):
+        fn()
+        best = []
+        for _ in range(reps):
+            e0.record()
+            fn()
+            e1.record()
+            torch.cuda.synchronize()
+            best.append(e0.elapsed_time(e1))
+        return sorted(best)[len(best) // 2]
+
+    def switch():
+        for l in range(L):
+            prompt.recache(l, k, v)
+
+    res = {"what": "cross-attention over the active prompt's keys (bf16, no mask, no rotary step) and the replacement "
+                   "of those keys at a prompt switch; not part of `value`",
+           "prompt_tokens": n_text,
+           "switch_ms_30_layers": round(timed(switch), 4)}
+    for name, nq in (("chunk", w.chunk_tokens), ("reprefill", 5 * w.chunk_tokens)):
+        q = torch.randn((nq, Hh, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+        out = torch.empty_like(q)
+
+        def run():
+            for l in range(L):
+                prompt.cross_attn(l, q, out)
+
+        ms = timed(run)
+        fl = attn_flops(nq, n_text, D, Hh) * L
+        by = (2 * nq + 2 * n_text) * Hh * D * 2 * L
+        res[name] = {"queries": nq, "ms_30_layers": round(ms, 4), "us_per_layer": round(ms * 1e3 / L, 2),
+                     "TFLOP/s": round(fl / (ms * 1e-3) / 1e12, 1),
+                     "pct_of_bf16_mfma_peak": round(100 * fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+                     "algorithmic_GBps": round(by / (ms * 1e-3) / 1e9, 1)}
+    prompt.close()
+    return res
+
+
 def fp8_cache_stats(w_loop, gen, q, k, v, steps, only_step=False, variant=0):
     """The 8-bit (E4M3) cache variant: a different accuracy tier, reported next to the bf16 figures and never as
     `value`.  Single-layer launch statistics, the 30-layer chunk step (append + attention, wall clock), and the
@@ -451,6 +500,8 @@ def main():
                          "constant_operands": {"TFLOP/s": round(pc_t, 1), "clock_GHz": round(pc_c, 3)},
                          "workload": "256 workgroups x 8 waves, 32x32x16 bf16 MFMAs back to back",
                          "attn_kernel_vs_random_operand_probe": round(attn_tflops / pr_t, 4)}
+
+    res["prompt_side"] = prompt_side_stats(w, gen)
 
     if not args.no_fp8:
         res["fp8_cache"] = fp8_cache_stats(w, gen, q, k, v, args.steps, variant=args.variant)

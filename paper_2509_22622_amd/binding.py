@@ -61,6 +61,10 @@ def lib() -> C.CDLL:
     if _lib is None:
         if not os.path.exists(LIB_PATH):
             raise FileNotFoundError(f"{LIB_PATH} not built: run `python -m paper_2509_22622_amd.build`")
+        # torch first: it ships its own copy of the HIP runtime, and the library must bind to the copy that owns
+        # the process's device memory and streams.  Loaded the other way round, the process holds two runtimes and
+        # the library's own one finds no device.
+        import torch  # noqa: F401
         L = C.CDLL(LIB_PATH)
         for name, (res, args) in SIGNATURES.items():
             fn = getattr(L, name)
