@@ -283,6 +283,8 @@ def main():
                     help="only the 30-layer step over the 8-bit cache (for profiler runs: one launch shape)")
     ap.add_argument("--probe-issue", action="store_true",
                     help="only run the library's MFMA probe with each kind of companion instruction and print a table")
+    ap.add_argument("--prompt-only", action="store_true",
+                    help="only the prompt side (cross-attention over the prompt, prompt switch), for profiler runs")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the graph replay, the single-layer statistics and the MFMA probe (for profiler runs)")
     ap.add_argument("--full-loop", action="store_true",
@@ -341,6 +343,9 @@ def main():
             for l in range(L):
                 t[i, l] = torch.randn((nq, Hh, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
         return t
+    if args.prompt_only:
+        print(json.dumps({"prompt_side": prompt_side_stats(w, gen)}))
+        return
     q, k, v = gen_bf16(), gen_bf16(), gen_bf16()
     if args.fp8_only:
         print(json.dumps({"fp8_cache": fp8_cache_stats(w, gen, q, k, v, args.steps, only_step=True, variant=args.variant)}))
