@@ -102,7 +102,7 @@ def single_layer_stats(w, gen, warmup=10, iters=50, kv_format="bf16", sink_relat
     return res
 
 
-def prompt_side_stats(w, gen, n_text=512, reps=5):
+def prompt_side_stats(w, gen, n_text=512, reps=10):
     """The prompt side of KV-recache: cross-attention of one chunk's and of one re-prefill's queries over a prompt of
     `n_text` tokens, 30 layers back to back (HIP events around the 30 launches), and the replacement of the prompt's
     keys and values in all layers."""
@@ -114,7 +114,8 @@ def prompt_side_stats(w, gen, n_text=512, reps=5):
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
 
     def timed(fn):
-        fn()
+        for _ in range(3):
+            fn()
         best = []
         for _ in range(reps):
             e0.record()

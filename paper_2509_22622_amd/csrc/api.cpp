@@ -590,7 +590,14 @@ ll_status ll_cross_attn(const ll_prompt* prompt, int layer, const void* q, int n
     }
     if (!q || !out) return fail(LL_ERR_INVALID_ARG, "null tensor");
     if (!aligned16(q, out)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
-    const int variant = attn_variant_qscale(prompt->D);
+    // these queries carry no factor yet: only kernels that apply AttnParams::scale_log2e themselves qualify
+    // A workgroup meets few kblocks here, and most of its life is the load of its queries and the store of its
+    // outputs.  With one round of workgroups on the chip (a chunk's queries) the pipelined kernel is the quicker one;
+    // with several rounds (a re-prefill's queries) small workgroups, three to a CU in different phases, are.
+    int variant = attn_variant_qscale(prompt->D);
+    if ((int64_t(n_q) + 255) / 256 * prompt->H > 512) variant = attn_variant_short_keys(prompt->D);
+    if (g_variant != 0 && attn_variant_supports(g_variant, prompt->D, KBLOCK) && attn_variant_applies_scale(g_variant))
+        variant = g_variant;
     AttnParams p{};
     p.q = static_cast<const uint16_t*>(q); p.out = static_cast<uint16_t*>(out);
     p.k_cache = prompt_k(prompt, layer); p.v_cache = prompt_v(prompt, layer);

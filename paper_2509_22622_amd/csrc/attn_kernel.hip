@@ -35,8 +35,9 @@ __device__ inline unsigned pack_bf16(float a, float b) {
 }
 
 // D: head_dim.  QB: 32-query blocks per wave.  NW: waves per workgroup.  KT: kblocks per tile.
-template <int D, int QB, int NW, int KT>
-__global__ __launch_bounds__(NW * 64) void ll_attn_kernel(const AttnParams p) {
+// OCC: waves per SIMD the register allocation must leave room for (several small workgroups per CU).
+template <int D, int QB, int NW, int KT, int OCC = 1>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(OCC, 8))) void ll_attn_kernel(const AttnParams p) {
     constexpr int KS = D / 16;                  // MFMA k-steps of the QK^T product
     constexpr int DB = D / 32;                  // 32-row blocks of O^T
     constexpr int KB_BYTES = KBLOCK * D * 2;    // one kblock of K (or of V)
@@ -263,8 +264,15 @@ static const AttnVariant kSimpleVariants[] = {
     LL_VARIANT(128, 1, 8, 2),   // 4: 256 queries, 8 waves
     LL_VARIANT(64, 2, 4, 2),    // 5
     LL_VARIANT(64, 1, 4, 2),    // 6
+    // 128 queries per workgroup and room for 2 or 3 workgroups per CU: for short key sets (cross-attention over a
+    // prompt), where a workgroup's life is mostly the load of its queries and the store of its outputs
+    { "d128_q1x4_k2_occ2", 128, 128, 2 * 2 * 2 * KBLOCK * 128 * 2, ll_attn_kernel<128, 1, 4, 2, 2>, 256, KBLOCK },   // 7
+    { "d128_q1x4_k1_occ3", 128, 128, 2 * 2 * 1 * KBLOCK * 128 * 2, ll_attn_kernel<128, 1, 4, 1, 3>, 256, KBLOCK },   // 8
+    { "d64_q1x4_k2_occ2", 64, 128, 2 * 2 * 2 * KBLOCK * 64 * 2, ll_attn_kernel<64, 1, 4, 2, 2>, 256, KBLOCK },       // 9
+    { "d64_q1x4_k1_occ3", 64, 128, 2 * 2 * 1 * KBLOCK * 64 * 2, ll_attn_kernel<64, 1, 4, 1, 3>, 256, KBLOCK },       // 10
 };
 constexpr int kNumSimple = sizeof(kSimpleVariants) / sizeof(kSimpleVariants[0]);
+static_assert(kNumSimple == 10, "attn_variant_short_keys names table positions 8 and 10");
 
 // variant ids: 1..kNumSimple are the kernels of this file, then the software-pipelined kernels, then the
 // kernels of the 8-bit cache
@@ -289,6 +297,9 @@ bool attn_variant_supports(int v, int D, int kblock) { return variant(v) && vari
 bool attn_variant_sink_shift(int v) { return v > kNumSimple && v <= kNumSimple + 2; }
 // the software-pipelined kernel that multiplies the queries by AttnParams::scale_log2e itself
 int attn_variant_qscale(int D) { return kNumSimple + (D == 128 ? 3 : 4); }
+// the 128-query kernel that leaves room for three workgroups per CU (short key sets, many query tiles)
+int attn_variant_short_keys(int D) { return D == 128 ? 8 : 10; }
+bool attn_variant_applies_scale(int v) { return (v >= 1 && v <= kNumSimple) || v == kNumSimple + 3 || v == kNumSimple + 4; }
 
 hipError_t launch_attn(const AttnParams& p_in, int variant, hipStream_t s) {
     if (!attn_variant_supports(variant, p_in.D, p_in.kblock)) return hipErrorInvalidValue;

@@ -144,6 +144,8 @@ int attn_variant_qtile(int v);                 // query rows per workgroup
 bool attn_variant_supports(int v, int D, int kblock);
 bool attn_variant_sink_shift(int v);          // the variant honours AttnChunk::sink_shift
 int attn_variant_qscale(int D);                // the variant for queries not yet scaled (honours scale_log2e)
+int attn_variant_short_keys(int D);            // small workgroups, three per CU: for short key sets
+bool attn_variant_applies_scale(int v);        // the variant multiplies the scores (or queries) by scale_log2e itself
 
 hipError_t launch_append(const AppendParams& p, hipStream_t s);
 hipError_t launch_append8(const AppendParams& p, hipStream_t s);

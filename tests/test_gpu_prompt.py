@@ -56,6 +56,34 @@ def test_cross_attn_parity(heads, head_dim, n_q, n_t):
     p.close()
 
 
+def _scaling_variants(head_dim):
+    """Kernel variants that apply the factor log2(e)/sqrt(D) themselves: the ones ll_cross_attn accepts."""
+    return [n for n in B.attn_variant_names().values()
+            if n.startswith(f"d{head_dim}_") and "fp8" not in n and (n.endswith("_qscale") or "_q" in n)]
+
+
+@pytest.mark.parametrize("name", _scaling_variants(128) + _scaling_variants(64))
+def test_every_kernel_variant_the_call_accepts(name):
+    """ll_cross_attn picks a kernel by the launch's size; here each candidate is forced in turn (and a variant that
+    expects pre-scaled queries, if selected, is ignored rather than used)."""
+    heads, head_dim, n_q, n_t = 3, int(name[1:name.index("_")]), 700, 226
+    ids = {n: v for v, n in B.attn_variant_names().items()}
+    q, k, v = bits((n_q, heads, head_dim), 30, "q"), bits((n_t, heads, head_dim), 30, "k"), bits((n_t, heads, head_dim), 30, "v")
+    p = B.Prompt(1, heads, head_dim, 256)
+    p.recache(0, H.to_dev(k), H.to_dev(v))
+    want = cross_attention(bf16_bits_to_f64(q), bf16_bits_to_f64(k), bf16_bits_to_f64(v))
+    try:
+        for forced in (name, f"d{head_dim}_stream"):
+            B.set_attn_variant(ids[forced])
+            out = torch.empty((n_q, heads, head_dim), dtype=torch.bfloat16, device="cuda")
+            p.cross_attn(0, H.to_dev(q), out)
+            torch.cuda.synchronize()
+            assert_parity_prompt(H.to_bits(out), want, v, f"variant {forced}")
+    finally:
+        B.set_attn_variant(0)
+    p.close()
+
+
 @pytest.mark.parametrize("head_dim", [64, 128])
 def test_values_and_keys_stay_paired_bit_exact(head_dim):
     """Keys 40 e_j and queries 40 e_i: query i puts all its weight on token i (the others get 2^-288, zero in
@@ -118,16 +146,22 @@ def test_switch_to_a_shorter_prompt_leaves_no_trace():
     fresh.close()
 
 
-def test_output_over_the_queries():
+@pytest.mark.parametrize("forced", [None, "d128_q1x4_k1_occ3"])
+def test_output_over_the_queries(forced):
     heads, head_dim, n_q, n_t = 4, 128, 600, 90
     q, k, v = bits((n_q, heads, head_dim), 14, "q"), bits((n_t, heads, head_dim), 14, "k"), bits((n_t, heads, head_dim), 14, "v")
     p = B.Prompt(1, heads, head_dim, 128)
     p.recache(0, H.to_dev(k), H.to_dev(v))
     qd = H.to_dev(q)
     out = torch.empty_like(qd)
-    p.cross_attn(0, qd, out)
-    p.cross_attn(0, qd, qd)                                 # in place
-    torch.cuda.synchronize()
+    try:
+        if forced:
+            B.set_attn_variant({n: i for i, n in B.attn_variant_names().items()}[forced])
+        p.cross_attn(0, qd, out)
+        p.cross_attn(0, qd, qd)                             # in place
+        torch.cuda.synchronize()
+    finally:
+        B.set_attn_variant(0)
     assert torch.equal(qd.view(torch.int16), out.view(torch.int16))
     p.close()
 
