@@ -634,3 +634,109 @@ def test_prompt_recache_replaces_everything():
     assert np.abs(outs[0] - cross_attention(q, k_new, v_new)).max() == 0
     with pytest.raises(RuntimeError):
         PromptOracle(L, H, D).cross_attn(0, q)
+
+
+# ---- P24-P27: the train-time rule (Sec. 3.2, Sec. 3.3 "Consistency between Training and Inference") and its gradients
+from oracle.clip_backward import ClipOracle  # noqa: E402
+
+
+def _clip_case(seed, cfg, ctx_start, n_ctx, n_clip):
+    P = cfg.tokens_per_frame
+    o = ClipOracle(cfg)
+    nf = len(o.frames(ctx_start, n_ctx, n_clip))
+    q = _randn((n_clip * P, cfg.heads, cfg.head_dim), seed)
+    k = _randn((nf * P, cfg.heads, cfg.head_dim), seed + 1)
+    v = _randn((nf * P, cfg.heads, cfg.head_dim), seed + 2)
+    dout = _randn((n_clip * P, cfg.heads, cfg.head_dim), seed + 3)
+    return o, q, k, v, dout, nf
+
+
+# P24: central finite differences of the forward alone, in random directions of the clip's q, k and v
+@pytest.mark.parametrize("ctx_start,n_ctx,n_clip", [(5, 2, 5), (0, 0, 6), (1, 3, 4)])
+def test_clip_backward_matches_finite_differences(ctx_start, n_ctx, n_clip):
+    cfg = OracleConfig(1, 2, 24, 2, 3, 2, 1, 2)                      # C 2, S 1, W 2: the window slides inside the clip
+    P = cfg.tokens_per_frame
+    o, q, k, v, dout, nf = _clip_case(70, cfg, ctx_start, n_ctx, n_clip)
+    o.forward(ctx_start, n_ctx, n_clip, q, k, v)
+    dq, dk, dv = o.backward(dout)
+    first = (nf - n_clip) * P
+    loss = lambda q_, k_, v_: float((ClipOracle(cfg).forward(ctx_start, n_ctx, n_clip, q_, k_, v_) * dout).sum())
+    eps = 1e-5
+    for trial in range(4):
+        uq, uk, uv = (_randn(q.shape, 80 + 3 * trial + i) for i in range(3))
+        uk_all, uv_all = np.zeros_like(k), np.zeros_like(v)
+        uk_all[first:], uv_all[first:] = uk, uv                      # only the clip's own rows move
+        for sel in ((1, 0, 0), (0, 1, 0), (0, 0, 1), (1, 1, 1)):
+            a, b, c = sel
+            num = (loss(q + eps * a * uq, k + eps * b * uk_all, v + eps * c * uv_all)
+                   - loss(q - eps * a * uq, k - eps * b * uk_all, v - eps * c * uv_all)) / (2 * eps)
+            ana = a * (dq * uq).sum() + b * (dk * uk).sum() + c * (dv * uv).sum()
+            assert abs(num - ana) <= 1e-7 * max(1.0, abs(ana)), (sel, num, ana)
+
+
+# P25: a library's reverse-mode differentiation of the same rule written with library ops (complex rotation, masked
+# softmax); the key sets come from the closed form "sink, or within W frames before the chunk, or in the chunk"
+def test_clip_backward_matches_library_autograd():
+    cfg = OracleConfig(1, 2, 24, 2, 3, 2, 1, 3)
+    P, S, W, C, D = cfg.tokens_per_frame, 1, 3, 2, 24
+    ctx_start, n_ctx, n_clip = 4, 3, 7
+    o, q, k, v, dout, nf = _clip_case(90, cfg, ctx_start, n_ctx, n_clip)
+    o.forward(ctx_start, n_ctx, n_clip, q, k, v)
+    dq, dk, dv = o.backward(dout)
+    frames = o.frames(ctx_start, n_ctx, n_clip)
+    clip_start = ctx_start + n_ctx
+
+    def angles(fs):
+        return torch.tensor(np.stack([rope_angles(cfg, f, t // cfg.grid_w, t % cfg.grid_w) for f in fs for t in range(P)]))
+
+    def rot(x, fs):
+        z = torch.view_as_complex(x.reshape(x.shape[0], x.shape[1], D // 2, 2).contiguous())
+        return torch.view_as_real(z * torch.polar(torch.ones_like(angles(fs)), angles(fs))[:, None, :]).reshape(x.shape)
+
+    tq, tk, tv = (torch.tensor(a, requires_grad=True) for a in (q, k, v))
+    qr, kr = rot(tq, range(clip_start, clip_start + n_clip)), rot(tk, frames)
+    qf = np.repeat(np.arange(clip_start, clip_start + n_clip), P)
+    kf = np.repeat(np.array(frames), P)
+    f0 = clip_start + ((qf - clip_start) // C) * C                      # first frame of the query's chunk
+    allowed = (kf[None, :] < S) | ((kf[None, :] >= f0[:, None] - W) & (kf[None, :] < f0[:, None] + C))
+    z = torch.einsum("qhd,khd->hqk", qr, kr) / math.sqrt(D)
+    z = z.masked_fill(~torch.tensor(allowed)[None], float("-inf"))
+    out = torch.einsum("hqk,khd->qhd", torch.softmax(z, dim=-1), tv)
+    (out * torch.tensor(dout)).sum().backward()
+    first = (nf - n_clip) * P
+    assert np.abs(dq - tq.grad.numpy()).max() < 1e-11
+    assert np.abs(dk - tk.grad.numpy()[first:]).max() < 1e-11
+    assert np.abs(dv - tv.grad.numpy()[first:]).max() < 1e-11
+    assert np.abs(tk.grad.numpy()[:first]).max() > 1e-3                  # the context does matter; it is just not returned
+
+
+# P26: a key receives gradient only from the chunks that see it (the window slides inside a long clip)
+def test_clip_backward_respects_the_window():
+    cfg = OracleConfig(1, 2, 24, 2, 3, 2, 1, 2)
+    P = cfg.tokens_per_frame
+    ctx_start, n_ctx, n_clip = 3, 2, 8                                   # clip frames 5..12, chunks at 5, 7, 9, 11
+    o, q, k, v, dout, nf = _clip_case(100, cfg, ctx_start, n_ctx, n_clip)
+    o.forward(ctx_start, n_ctx, n_clip, q, k, v)
+    d = np.zeros_like(dout)
+    d[6 * P:] = dout[6 * P:]                                             # only the last chunk (frames 11, 12) has a loss
+    dq, dk, dv = o.backward(d)
+    seen = np.zeros(n_clip, dtype=bool)
+    seen[4:] = True                                                      # its keys: frames 9, 10 (window) and 11, 12
+    for i in range(n_clip):
+        blk = slice(i * P, (i + 1) * P)
+        assert (np.abs(dk[blk]).max() > 1e-6) == seen[i] and (np.abs(dv[blk]).max() > 1e-6) == seen[i], i
+        assert (np.abs(dq[blk]).max() > 1e-6) == (i >= 6), i
+
+
+# P27: the forward of a video's first clip is the inference rule streamed from frame 0
+def test_clip_forward_equals_streaming_inference():
+    cfg = OracleConfig(1, 2, 24, 2, 3, 2, 2, 2)
+    P, n_clip = cfg.tokens_per_frame, 8
+    shape = (n_clip * P, cfg.heads, cfg.head_dim)
+    qb, kb, vb = _bits(shape, 110), _bits(shape, 111), _bits(shape, 112)
+    got = ClipOracle(cfg).forward(0, 0, n_clip, bf16_bits_to_f64(qb), bf16_bits_to_f64(kb), bf16_bits_to_f64(vb))
+    inf = Oracle(cfg)
+    for c in range(n_clip // 2):
+        rows = slice(2 * c * P, 2 * (c + 1) * P)
+        inf.append(0, 2 * c, qb[rows], kb[rows], vb[rows])
+        assert np.abs(got[rows] - inf.attn(0)).max() < 1e-12
