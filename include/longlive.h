@@ -199,6 +199,43 @@ ll_status ll_prompt_tokens(const ll_prompt* prompt, int layer, int* n_tokens);
  * an error the library cannot detect.  1 <= n_q <= 2^24.  LL_ERR_STATE if the layer has no prompt yet. */
 ll_status ll_cross_attn(const ll_prompt* prompt, int layer, const void* q, int n_q, void* out, void* stream);
 
+/* ---- The train-time rule and its backward pass (Sec. 3.2 streaming long tuning; Sec. 3.3 "Consistency between
+ * Training and Inference").  One training step supervises a clip of n_clip frames that follows the frames generated
+ * so far.  Resident keys and values: the S sink frames, the last n_ctx <= W frames of the preceding context (constants:
+ * no gradient), and the clip's own frames (with gradient).  The clip is processed chunk by chunk under the inference
+ * rule: the chunk starting at frame f0 attends to the sink, to the frames within W before f0 (context or clip) and to
+ * itself.  ll_clip_forward computes that attention; ll_clip_backward the gradients of sum(out * dout) with respect
+ * to the clip's own q, k and v (before the rotary embedding), in bf16:
+ *     P = softmax(q' K'^T / sqrt(D)),  dV = P^T dO,  dZ = P * (dO V^T - rowsum(dO * O)),
+ *     dq' = dZ K' / sqrt(D),  dK' = dZ^T q' / sqrt(D),  then back through the rotary turn of each pair.
+ * One handle serves one layer at a time: the backward pass differentiates the handle's last forward pass.  All
+ * intermediate tensors live in the caller's buffer; nothing is allocated. */
+typedef struct ll_clip ll_clip;
+
+/* Bytes of device memory ll_clip_create needs; 0 if the shapes are invalid.  clip_frames is the largest n_clip. */
+size_t ll_clip_bytes(int heads, int head_dim, int tokens_per_frame, int sink_frames, int window_frames,
+                     int clip_frames, int chunk_frames);
+/* Arguments as for ll_cache_create (one layer).  dev_buffer: device, 256-byte aligned, at least ll_clip_bytes(...)
+ * bytes, zeroed here (synchronous, null stream); NULL with dev_bytes == 0 makes an index-only handle. */
+ll_status ll_clip_create(int heads, int head_dim, int tokens_per_frame, int sink_frames, int window_frames,
+                         int clip_frames, int chunk_frames, int grid_h, int grid_w, float rope_theta,
+                         void* dev_buffer, size_t dev_bytes, ll_clip** out);
+ll_status ll_clip_destroy(ll_clip* clip);
+/* Forward.  The context is frames [ctx_start, ctx_start + n_ctx), 0 <= n_ctx <= window_frames, the clip the n_clip
+ * frames after it.  ctx_start >= sink_frames, or ctx_start == 0 with n_ctx == 0 for a video's first clip, which
+ * contains the sink frames itself (they then receive gradients like any clip frame).
+ *   q: device bf16 [n_clip * P, H, D], the clip's queries.
+ *   k, v: device bf16 [n_frames * P, H, D] for all resident frames in ascending order: the sink frames (unless they
+ *         belong to the clip), the context, the clip; all before the rotary embedding.
+ *   out: device bf16 [n_clip * P, H, D].  q, k, v, out must stay unchanged until ll_clip_backward has run. */
+ll_status ll_clip_forward(ll_clip* clip, int64_t ctx_start, int n_ctx, int n_clip, const void* q, const void* k,
+                          const void* v, void* out, void* stream);
+/* Backward of the handle's last forward.  out: what ll_clip_forward wrote; dout: device bf16 [n_clip * P, H, D];
+ * dq, dk, dv: device bf16 [n_clip * P, H, D], gradients for the clip's own frames (context and sink frames outside
+ * the clip are constants).  LL_ERR_STATE without a forward pass. */
+ll_status ll_clip_backward(ll_clip* clip, const void* out, const void* dout, void* dq, void* dk, void* dv,
+                           void* stream);
+
 /* Attention kernel variant: 0 = default for the shape, otherwise a variant id listed by
  * ll_attn_variant_name.  Process-wide tuning knob for benchmarking. */
 ll_status ll_set_attn_variant(int variant);

@@ -25,7 +25,8 @@ clip of a video (no context yet) contains the sink frames itself and they then r
 
 Pins (tests/test_oracle_pins.py): central finite differences of the forward in random directions, a library's
 reverse-mode differentiation of a masked attention written with library ops, zero gradient to anything outside the
-key set (window eviction inside a long clip), and equality of the forward with the inference oracle's re-prefill.
+key set (window eviction inside a long clip), and equality of a first clip's forward with the inference oracle
+streamed from frame 0.
 """
 from __future__ import annotations
 
@@ -85,16 +86,18 @@ class ClipOracle:
             keys = key_frames(cfg, f0, n, [f for f in fr if f < f0 + n])
             kidx = np.concatenate([np.arange(pos[f] * P, (pos[f] + 1) * P) for f in keys])
             rows = slice((f0 - clip_start) * P, (f0 - clip_start + n) * P)
-            Pm = np.empty((cfg.heads, n * P, kidx.size))
             for h in range(cfg.heads):
-                z = (q_rot[rows, h, :] @ k_rot[kidx, h, :].T) * scale
-                z -= z.max(axis=1, keepdims=True)
-                e = np.exp(z)
-                Pm[h] = e / e.sum(axis=1, keepdims=True)
-                out[rows, h, :] = Pm[h] @ v[kidx, h, :]
-            steps.append((rows, kidx, Pm))
+                out[rows, h, :] = self._softmax(q_rot[rows, h, :], k_rot[kidx, h, :], scale) @ v[kidx, h, :]
+            steps.append((rows, kidx))
         self._saved = (ctx_start, n_ctx, n_clip, fr, pos, q_rot, k_rot, v, steps)
         return out
+
+    @staticmethod
+    def _softmax(qh: np.ndarray, kh: np.ndarray, scale: float) -> np.ndarray:
+        z = (qh @ kh.T) * scale
+        z -= z.max(axis=1, keepdims=True)
+        e = np.exp(z)
+        return e / e.sum(axis=1, keepdims=True)
 
     def backward(self, dout: np.ndarray):
         """dout [n_clip*P, H, D] -> (dq, dk, dv), each [n_clip*P, H, D]: gradients of sum(out * dout) with respect to
@@ -106,9 +109,9 @@ class ClipOracle:
         dq_rot = np.zeros_like(q_rot)
         dk_rot = np.zeros_like(k_rot)
         dv_all = np.zeros_like(v)
-        for rows, kidx, Pm in steps:
+        for rows, kidx in steps:
             for h in range(cfg.heads):
-                p = Pm[h]
+                p = self._softmax(q_rot[rows, h, :], k_rot[kidx, h, :], scale)      # the forward's weights again
                 do = dout[rows, h, :]
                 dv_all[kidx, h, :] += p.T @ do
                 dp = do @ v[kidx, h, :].T

@@ -40,6 +40,11 @@ SIGNATURES = {
     "ll_prompt_recache": (_i, [_vp, _i, _vp, _vp, _i, _vp]),
     "ll_prompt_tokens": (_i, [_vp, _i, C.POINTER(_i)]),
     "ll_cross_attn": (_i, [_vp, _i, _vp, _i, _vp, _vp]),
+    "ll_clip_bytes": (_sz, [_i] * 7),
+    "ll_clip_create": (_i, [_i] * 9 + [C.c_float, _vp, _sz, C.POINTER(_vp)]),
+    "ll_clip_destroy": (_i, [_vp]),
+    "ll_clip_forward": (_i, [_vp, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp]),
+    "ll_clip_backward": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "ll_set_attn_variant": (_i, [_i]),
     "ll_attn_variant_name": (C.c_char_p, [_i]),
     "ll_probe_mfma_rate": (_i, [C.c_void_p, C.c_size_t, _i, _i, _i, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
@@ -268,3 +273,44 @@ class Prompt:
             _check(lib().ll_cross_attn(self._h, layer, _ptr(q), n_q, _ptr(out), _stream()))
         else:
             _check(lib().ll_cross_attn(self._h, layer, None, n_q, None, None))
+
+
+class Clip:
+    """Handle on one layer's training step: attention of a supervised clip over sink + detached window + itself
+    (``ll_clip_forward``) and its gradients (``ll_clip_backward``).  ``device=None`` makes an index-only handle."""
+
+    def __init__(self, heads, head_dim, grid_h, grid_w, chunk_frames, sink_frames, window_frames, clip_frames,
+                 rope_theta=10000.0, device="cuda"):
+        self.heads, self.head_dim, self.P = heads, head_dim, grid_h * grid_w
+        self._h = C.c_void_p()
+        self.buffer = None
+        nbytes = lib().ll_clip_bytes(heads, head_dim, self.P, sink_frames, window_frames, clip_frames, chunk_frames)
+        if device is not None:
+            import torch
+            if nbytes == 0:
+                raise LongLiveError(1, "invalid shape")
+            self.buffer = torch.empty(nbytes, dtype=torch.uint8, device=device)
+            ptr, size = C.c_void_p(self.buffer.data_ptr()), nbytes
+        else:
+            ptr, size = None, 0
+        _check(lib().ll_clip_create(heads, head_dim, self.P, sink_frames, window_frames, clip_frames, chunk_frames,
+                                    grid_h, grid_w, rope_theta, ptr, size, C.byref(self._h)))
+
+    def close(self):
+        if self._h:
+            lib().ll_clip_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def forward(self, ctx_start, n_ctx, n_clip, q=None, k=None, v=None, out=None):
+        stream = _stream() if self.buffer is not None else None
+        _check(lib().ll_clip_forward(self._h, ctx_start, n_ctx, n_clip, _ptr(q), _ptr(k), _ptr(v), _ptr(out), stream))
+
+    def backward(self, out=None, dout=None, dq=None, dk=None, dv=None):
+        stream = _stream() if self.buffer is not None else None
+        _check(lib().ll_clip_backward(self._h, _ptr(out), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), stream))

@@ -297,6 +297,7 @@ bool attn_variant_supports(int v, int D, int kblock) { return variant(v) && vari
 bool attn_variant_sink_shift(int v) { return v > kNumSimple && v <= kNumSimple + 2; }
 // the software-pipelined kernel that multiplies the queries by AttnParams::scale_log2e itself
 int attn_variant_qscale(int D) { return kNumSimple + (D == 128 ? 3 : 4); }
+int attn_variant_lse(int D) { return kNumSimple + (D == 128 ? 5 : 6); }
 // the 128-query kernel that leaves room for three workgroups per CU (short key sets, many query tiles)
 int attn_variant_short_keys(int D) { return D == 128 ? 8 : 10; }
 bool attn_variant_applies_scale(int v) { return (v >= 1 && v <= kNumSimple) || v == kNumSimple + 3 || v == kNumSimple + 4; }

@@ -496,7 +496,7 @@ __device__ __forceinline__ void sp_store_out(const AttnParams& p, int head, int 
 }
 
 // ---- one workgroup per (head, query tile)
-template <int D, bool QSCALE>
+template <int D, bool QSCALE, bool LSE = false>
 __global__ __launch_bounds__(SP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_attn_stream_kernel(const AttnParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     __shared__ float2 shift_cs[64];              // (cos, sin) of sink_shift * frame-axis frequency, per rotary pair
@@ -552,6 +552,13 @@ __global__ __launch_bounds__(SP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
     SpState<D> st;
     sp_segment<D, QSCALE>(p, ch, head, q0, 0, ch.n_kblocks, lds, st, shift_cs);
     sp_store_out<D>(p, head, q0, ch.q_end, st);
+    if constexpr (LSE) {                         // log2 of the row's sum of 2^score, for the backward pass
+        const int lane = threadIdx.x & 63;
+        const float l = st.l + __shfl_xor(st.l, 32);
+        // v_log_f32 is the base-2 logarithm; callers that want no row sums leave the pointer null
+        if (p.lse != nullptr && lane < 32 && q0 + lane < ch.q_end)
+            p.lse[int64_t(head) * p.lse_stride + q0 + lane] = st.m + __builtin_amdgcn_logf(l);
+    }
 }
 
 const AttnVariant kStreamVariants[] = {
@@ -561,6 +568,10 @@ const AttnVariant kStreamVariants[] = {
     // over the prompt's keys, whose queries pass through no rotary step that could fold the factor in
     {"d128_stream_qscale", 128, 256, 8 * 2 * KBLOCK * 128 * 2, ll_attn_stream_kernel<128, true>, SP_THREADS, KBLOCK},
     {"d64_stream_qscale", 64, 256, 8 * 2 * KBLOCK * 64 * 2, ll_attn_stream_kernel<64, true>, SP_THREADS, KBLOCK},
+    // the same kernels with one more output, the log2 of each row's sum of 2^score (AttnParams::lse): the forward of
+    // the train-time rule, whose backward pass rebuilds the softmax weights from it
+    {"d128_stream_lse", 128, 256, 8 * 2 * KBLOCK * 128 * 2, ll_attn_stream_kernel<128, false, true>, SP_THREADS, KBLOCK},
+    {"d64_stream_lse", 64, 256, 8 * 2 * KBLOCK * 64 * 2, ll_attn_stream_kernel<64, false, true>, SP_THREADS, KBLOCK},
 };
 const int kNumStreamVariants = sizeof(kStreamVariants) / sizeof(kStreamVariants[0]);
 

@@ -110,6 +110,8 @@ struct AttnParams {
     int kblock;                  // key slots per kblock: 32 (bf16 cache) or 64 (8-bit cache)
     const double* inv_freq_t;    // frame-axis rotary frequencies [n_t] (used when a chunk has a sink_shift)
     int n_t;
+    float* lse;                  // *_lse kernels: log2 of each row's sum of 2^score, [H][lse_stride] (null otherwise)
+    int64_t lse_stride;
     uint16_t xcd_first[9];
     uint16_t xcd_group[MAX_XCD_GROUPS];
     AttnChunk chunk[MAX_ATTN_CHUNKS];
@@ -122,6 +124,43 @@ struct ReadFrameParams {
     const uint8_t* k8_cache; const uint8_t* v8_cache;   // 8-bit cache: codes go to k8_out / v8_out
     uint8_t* k8_out; uint8_t* v8_out;
 };
+
+// ---- backward pass of the train-time rule (attn_bwd.hip)
+constexpr int MAX_BWD_GROUPS = 32;
+struct BwdGroup {                // column tiles that share one set of streamed rows
+    int c_begin, c_end;          // columns: query rows (dQ kernel) or clip-token indices of keys (dK/dV kernel)
+    int tile_begin;              // first 128-column tile of the group in the launch
+    int n_ranges;
+    int rs[2], re[2];            // streamed rows: key token slots (dQ kernel), query rows (dK/dV kernel: one range)
+};
+struct BwdParams {
+    const uint16_t* q; const uint16_t* dout;            // dQ kernel: rotated, scaled queries and dO, [rows, H, D]
+    const float* lse; const float* delta;               // [H][row_stride]
+    int64_t row_stride;
+    // streamed fragment regions (head 0; element strides between heads): two K-style, two V^T-style
+    const uint16_t* s_k1; const uint16_t* s_k2; const uint16_t* s_t1; const uint16_t* s_t2;
+    int64_t hs_k1, hs_k2, hs_t1, hs_t2;
+    // dK/dV kernel: K-style regions holding the columns' own K' and V rows, and the token slot of clip token 0
+    const uint16_t* c_k1; const uint16_t* c_k2;
+    int64_t hc_k1, hc_k2, col_slot0;
+    float* g1;                   // fp32 [rows, H, D]: Gq (dQ kernel) or Gk (dK/dV kernel)
+    uint16_t* dv;                // dK/dV kernel: bf16 [rows, H, D]
+    int H, D, n_groups, n_tiles;
+    BwdGroup group[MAX_BWD_GROUPS];
+};
+struct BwdFinishParams {
+    const float* gq; const float* gk;                   // [n_frames * P, H, D]
+    uint16_t* dq; uint16_t* dk;
+    RopeTables rope;
+    int H, D, P, grid_w, n_frames;
+    int64_t frame0;              // absolute index of the first frame
+    float q_mul, k_mul;          // 1/sqrt(D), ln 2
+};
+hipError_t launch_bwd_dq(const BwdParams& p, hipStream_t s);
+hipError_t launch_bwd_dkv(const BwdParams& p, hipStream_t s);
+hipError_t launch_bwd_delta(const uint16_t* out, const uint16_t* dout, float* delta, int rows, int H, int D,
+                            int64_t row_stride, hipStream_t s);
+hipError_t launch_bwd_finish(const BwdFinishParams& p, hipStream_t s);
 
 // One attention kernel instantiation.
 struct AttnVariant {
@@ -143,6 +182,7 @@ int attn_variant_default(int D, int kblock);
 int attn_variant_qtile(int v);                 // query rows per workgroup
 bool attn_variant_supports(int v, int D, int kblock);
 bool attn_variant_sink_shift(int v);          // the variant honours AttnChunk::sink_shift
+int attn_variant_lse(int D);                   // the variant that also writes AttnParams::lse
 int attn_variant_qscale(int D);                // the variant for queries not yet scaled (honours scale_log2e)
 int attn_variant_short_keys(int D);            // small workgroups, three per CU: for short key sets
 bool attn_variant_applies_scale(int v);        // the variant multiplies the scores (or queries) by scale_log2e itself

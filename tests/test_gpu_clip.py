@@ -1,0 +1,108 @@
+"""The train-time rule on the GPU (ll_clip_forward, ll_clip_backward) against the fp64 oracle.
+
+Tolerances.  Forward: those of the inference path (max-abs 1e-2, relative L2 5e-3).  Gradients: the backward kernels
+rebuild the softmax weights P from bf16 operands, round P and dZ = P (dP - delta) to bf16 for the second products and
+the results to bf16 again; each rounding is 2^-9 relative and they add up over three stages in which errors of
+different keys average out.  Relative L2 <= 1e-2 per gradient tensor, and no element further off than 2 % of the
+tensor's largest magnitude.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle.clip_backward import ClipOracle
+from oracle.longlive_oracle import OracleConfig, bf16_bits_to_f64, error_metrics
+from paper_2509_22622_amd import binding as B
+from paper_2509_22622_amd import synth
+
+import gpu_harness as H
+
+pytestmark = pytest.mark.gpu
+
+GRAD_REL_L2 = 1e-2
+GRAD_MAX_FRAC = 2e-2
+
+
+def bits(shape, stream, tensor, cfg_id=41):
+    return synth.normal_bf16(shape, cfg_id, 0, stream, tensor)
+
+
+def run_case(heads, head_dim, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip, seed=0, dout_rows=None):
+    cfg = OracleConfig(1, heads, head_dim, gh, gw, C, S, W)
+    P = gh * gw
+    oracle = ClipOracle(cfg)
+    nf = len(oracle.frames(ctx_start, n_ctx, n_clip))
+    q = bits((n_clip * P, heads, head_dim), 4 * seed, "q")
+    k = bits((nf * P, heads, head_dim), 4 * seed, "k")
+    v = bits((nf * P, heads, head_dim), 4 * seed, "v")
+    dout = bits((n_clip * P, heads, head_dim), 4 * seed + 1, "q")
+    if dout_rows is not None:                                  # a loss on some rows only
+        keep = np.zeros(n_clip * P, dtype=bool)
+        keep[dout_rows] = True
+        dout = np.where(keep[:, None, None], dout, np.uint16(0))
+    clip = B.Clip(heads, head_dim, gh, gw, C, S, W, T)
+    out, dq, dk, dv = (torch.empty((n_clip * P, heads, head_dim), dtype=torch.bfloat16, device="cuda") for _ in range(4))
+    clip.forward(ctx_start, n_ctx, n_clip, H.to_dev(q), H.to_dev(k), H.to_dev(v), out)
+    clip.backward(out, H.to_dev(dout), dq, dk, dv)
+    torch.cuda.synchronize()
+    want_out = oracle.forward(ctx_start, n_ctx, n_clip, bf16_bits_to_f64(q), bf16_bits_to_f64(k), bf16_bits_to_f64(v))
+    what = f"H{heads} D{head_dim} P{P} C{C} S{S} W{W} ctx {ctx_start}+{n_ctx} clip {n_clip}"
+    H.assert_parity(H.to_bits(out), want_out, what + " forward")
+    want = oracle.backward(bf16_bits_to_f64(dout))
+    got = {}
+    for name, t, w in zip(("dq", "dk", "dv"), (dq, dk, dv), want):
+        g = bf16_bits_to_f64(H.to_bits(t))
+        assert np.isfinite(g).all(), f"{what} {name}: non-finite"
+        max_abs, rel = error_metrics(g, w)
+        assert rel <= GRAD_REL_L2 and max_abs <= GRAD_MAX_FRAC * np.abs(w).max(), f"{what} {name}: max_abs {max_abs:.3e} of {np.abs(w).max():.3e}, rel_l2 {rel:.3e}"
+        got[name] = g
+    clip.close()
+    return got, want
+
+
+@pytest.mark.parametrize("heads,head_dim,gh,gw,C,S,W,T,ctx_start,n_ctx,n_clip", [
+    (2, 64, 3, 5, 2, 1, 3, 7, 5, 3, 7),       # window slides inside the clip, short last chunk
+    (2, 64, 3, 5, 2, 1, 3, 7, 0, 0, 6),       # a video's first clip: the sink is part of the clip
+    (3, 128, 5, 8, 3, 3, 6, 9, 9, 6, 9),      # the tiny inference config's window and sink, D 128
+    (2, 128, 7, 9, 3, 2, 5, 6, 20, 2, 5),     # P 63: nothing aligned; fewer context frames than the window holds
+    (2, 64, 9, 15, 2, 2, 4, 6, 30, 4, 6),     # P 135: two column tiles per frame, the second ragged
+    (1, 128, 4, 8, 1, 0, 2, 5, 0, 2, 5),      # no sink, chunks of one frame, context from frame 0
+    (2, 64, 2, 3, 3, 2, 0, 6, 2, 0, 6),       # no window at all: sink and own chunk only
+])
+def test_clip_forward_and_gradients(heads, head_dim, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip):
+    run_case(heads, head_dim, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip)
+
+
+def test_gradient_reaches_only_the_keys_a_chunk_sees():
+    """A loss on the last chunk only: keys outside its window get exactly zero, its queries alone get dq."""
+    gh, gw, C, S, W = 3, 5, 2, 1, 2
+    P, n_clip = gh * gw, 8
+    rows = np.arange(6 * P, 8 * P)
+    got, want = run_case(2, 64, gh, gw, C, S, W, 8, 3, 2, n_clip, seed=3, dout_rows=rows)
+    for i in range(n_clip):
+        blk = slice(i * P, (i + 1) * P)
+        seen = i >= 4                                          # frames 9, 10 (window) and 11, 12 (the chunk) of 5..12
+        assert (np.abs(got["dk"][blk]).max() > 0) == seen and (np.abs(got["dv"][blk]).max() > 0) == seen, i
+        assert (np.abs(got["dq"][blk]).max() > 0) == (i >= 6), i
+
+
+def test_second_step_with_a_shorter_clip_reuses_the_handle():
+    """The handle's regions keep the former step's contents; a later, shorter step must not see them."""
+    heads, head_dim, gh, gw, C, S, W, T = 2, 64, 3, 5, 2, 1, 3, 7
+    cfg = OracleConfig(1, heads, head_dim, gh, gw, C, S, W)
+    P = gh * gw
+    clip = B.Clip(heads, head_dim, gh, gw, C, S, W, T)
+    for step, (ctx_start, n_ctx, n_clip) in enumerate([(5, 3, 7), (12, 2, 3)]):
+        oracle = ClipOracle(cfg)
+        nf = len(oracle.frames(ctx_start, n_ctx, n_clip))
+        q, k, v = bits((n_clip * P, heads, head_dim), 20 + step, "q"), bits((nf * P, heads, head_dim), 20 + step, "k"), bits((nf * P, heads, head_dim), 20 + step, "v")
+        dout = bits((n_clip * P, heads, head_dim), 30 + step, "q")
+        out, dq, dk, dv = (torch.empty((n_clip * P, heads, head_dim), dtype=torch.bfloat16, device="cuda") for _ in range(4))
+        clip.forward(ctx_start, n_ctx, n_clip, H.to_dev(q), H.to_dev(k), H.to_dev(v), out)
+        clip.backward(out, H.to_dev(dout), dq, dk, dv)
+        torch.cuda.synchronize()
+        H.assert_parity(H.to_bits(out), oracle.forward(ctx_start, n_ctx, n_clip, *(bf16_bits_to_f64(t) for t in (q, k, v))), f"step {step}")
+        for name, t, w in zip(("dq", "dk", "dv"), (dq, dk, dv), oracle.backward(bf16_bits_to_f64(dout))):
+            max_abs, rel = error_metrics(bf16_bits_to_f64(H.to_bits(t)), w)
+            assert rel <= GRAD_REL_L2, f"step {step} {name}: rel_l2 {rel:.3e}"
+    clip.close()
