@@ -152,6 +152,47 @@ def prompt_side_stats(w, gen, n_text=512, reps=10):
     return res
 
 
+def train_step_stats(w, gen, clip_frames=21, reps=5):
+    """The train-time rule at the benchmark model's layer shape: forward of a supervised clip of `clip_frames` frames
+    over sink + a full detached window + itself, and the backward pass (HIP events; one layer)."""
+    import torch
+    from paper_2509_22622_amd import binding
+    Hh, D, C, S, W, T = w.heads, w.head_dim, w.chunk_frames, w.sink_frames, w.window_frames, clip_frames
+    P = w.tokens_per_frame
+    clip = binding.Clip(Hh, D, w.grid_h, w.grid_w, C, S, W, T)
+    rnd = lambda n: torch.randn((n * P, Hh, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    q, k, v, dout = rnd(T), rnd(S + W + T), rnd(S + W + T), rnd(T)
+    out, dq, dk, dv = (torch.empty_like(q) for _ in range(4))
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    tf, tb = [], []
+    for _ in range(reps + 1):
+        a, b, c = ev(), ev(), ev()
+        a.record()
+        clip.forward(60, W, T, q, k, v, out)
+        b.record()
+        clip.backward(out, dout, dq, dk, dv)
+        c.record()
+        torch.cuda.synchronize()
+        tf.append(a.elapsed_time(b))
+        tb.append(b.elapsed_time(c))
+    tf, tb = sorted(tf[1:])[reps // 2], sorted(tb[1:])[reps // 2]
+    pairs = ((T + C - 1) // C) * (C * P) * ((S + W + C) * P)          # every chunk sees sink + W frames + itself
+    fl = attn_flops(1, 1, D, Hh) * pairs
+    res = {"what": "attention of a supervised clip over sink + detached window + itself and its gradients (bf16; one "
+                   "layer); not part of `value`",
+           "workload": f"{w.name}-shaped clip: {T} frames in chunks of {C}, sink {S}, window {W}: {T * P} queries, "
+                       f"{(S + W + T) * P} resident keys, {Hh} heads x {D}",
+           "workspace_bytes": int(clip.buffer.numel()),
+           "forward_ms": round(tf, 3), "forward_TFLOP/s": round(fl / (tf * 1e-3) / 1e12, 1),
+           "backward_ms": round(tb, 3),
+           "backward_TFLOP/s": round(2.5 * fl / (tb * 1e-3) / 1e12, 1),
+           "backward_pct_of_bf16_mfma_peak": round(100 * 2.5 * fl / (tb * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+           "flops": "forward 4 Nq Nk D H over unmasked pairs; backward 2.5 x that (five products; the kernels run "
+                    "seven, scores and dP in both)"}
+    clip.close()
+    return res
+
+
 def fp8_cache_stats(w_loop, gen, q, k, v, steps, only_step=False, variant=0):
     """The 8-bit (E4M3) cache variant: a different accuracy tier, reported next to the bf16 figures and never as
     `value`.  Single-layer launch statistics, the 30-layer chunk step (append + attention, wall clock), and the
@@ -286,6 +327,8 @@ def main():
                     help="only run the library's MFMA probe with each kind of companion instruction and print a table")
     ap.add_argument("--prompt-only", action="store_true",
                     help="only the prompt side (cross-attention over the prompt, prompt switch), for profiler runs")
+    ap.add_argument("--clip-only", action="store_true",
+                    help="only the train-time rule (clip forward and backward), for profiler runs")
     ap.add_argument("--no-extras", action="store_true",
                     help="skip the graph replay, the single-layer statistics and the MFMA probe (for profiler runs)")
     ap.add_argument("--full-loop", action="store_true",
@@ -344,6 +387,9 @@ def main():
             for l in range(L):
                 t[i, l] = torch.randn((nq, Hh, D), generator=gen, device="cuda", dtype=torch.float32).to(torch.bfloat16)
         return t
+    if args.clip_only:
+        print(json.dumps({"train_step": train_step_stats(w, gen)}))
+        return
     if args.prompt_only:
         print(json.dumps({"prompt_side": prompt_side_stats(w, gen)}))
         return
@@ -508,6 +554,7 @@ def main():
                          "attn_kernel_vs_random_operand_probe": round(attn_tflops / pr_t, 4)}
 
     res["prompt_side"] = prompt_side_stats(w, gen)
+    res["train_step"] = train_step_stats(w, gen)
 
     if not args.no_fp8:
         res["fp8_cache"] = fp8_cache_stats(w, gen, q, k, v, args.steps, variant=args.variant)

@@ -75,7 +75,7 @@ __device__ inline void bw_load_kstyle_row(const uint16_t* region, int64_t slot, 
 
 // ---------------------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void ll_bwd_dq_kernel(const BwdParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_bwd_dq_kernel(const BwdParams p) {
     constexpr int KS = D / 16, DB = D / 32;
     constexpr int KB_BYTES = KBLOCK * D * 2;
     constexpr int NREG = 3;                           // streamed regions per block
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(256) void ll_bwd_dq_kernel(const BwdParams p) {
 
 // ---------------------------------------------------------------------------------------------------------------
 template <int D>
-__global__ __launch_bounds__(256) void ll_bwd_dkv_kernel(const BwdParams p) {
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_bwd_dkv_kernel(const BwdParams p) {
     constexpr int KS = D / 16, DB = D / 32;
     constexpr int KB_BYTES = KBLOCK * D * 2;
     constexpr int NREG = 4;

@@ -106,3 +106,9 @@ def test_second_step_with_a_shorter_clip_reuses_the_handle():
             max_abs, rel = error_metrics(bf16_bits_to_f64(H.to_bits(t)), w)
             assert rel <= GRAD_REL_L2, f"step {step} {name}: rel_l2 {rel:.3e}"
     clip.close()
+
+
+def test_wan_frame_size():
+    """The benchmark model's frame (30 x 52 tokens), head width, chunk, sink and window; two heads and a clip of two
+    chunks keep the oracle's fp64 products to seconds.  Every element of out, dq, dk and dv is compared."""
+    run_case(2, 128, 30, 52, 3, 3, 9, 6, 60, 9, 6, seed=5)
