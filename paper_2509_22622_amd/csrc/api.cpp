@@ -941,8 +941,26 @@ ll_status ll_clip_backward(ll_clip* clip, const void* out, const void* dout, voi
         e = launch_bwd_dq(p, s);
         if (e != hipSuccess) return hip_fail(e, "dQ kernel launch");
     }
-    // 3. Gk and dV: the clip's keys as columns, frame by frame over the query rows of the chunks that see the frame
-    for (int base = 0; base < n_clip; base += MAX_BWD_GROUPS) {
+    // 3. Gk and dV: the clip's keys as columns over the query rows of the chunks that see them.  A frame is seen by its
+    //    own chunk and by the later chunks that start within W frames after it (a sink frame by all later chunks);
+    //    neighbouring frames with the same rows form one group of columns.
+    std::vector<BwdGroup> groups;
+    for (int gc = 0; gc < n_clip; ++gc) {
+        const int64_t gframe = clip_start + gc;
+        const int c_first = gc / c->C;
+        const int c_last = gframe < c->S ? n_chunks - 1 : std::min(n_chunks - 1, (gc + c->W) / c->C);
+        const int rs = c_first * c->C * c->P;
+        const int re = int(std::min<int64_t>(n_clip, int64_t(c_last + 1) * c->C) * c->P);
+        if (!groups.empty() && groups.back().rs[0] == rs && groups.back().re[0] == re) {
+            groups.back().c_end += c->P;
+            continue;
+        }
+        BwdGroup g{};
+        g.c_begin = gc * c->P; g.c_end = g.c_begin + c->P;
+        g.n_ranges = 1; g.rs[0] = rs; g.re[0] = re;
+        groups.push_back(g);
+    }
+    for (size_t base = 0; base < groups.size(); base += MAX_BWD_GROUPS) {
         BwdParams p{};
         p.lse = clip_f32(c, c->o_lse); p.delta = clip_f32(c, c->o_delta); p.row_stride = c->row_stride;
         p.s_k1 = clip_u16(c, c->o_cq); p.hs_k1 = c->hs_clip;                  // q'   K-style
@@ -954,20 +972,15 @@ ll_status ll_clip_backward(ll_clip* clip, const void* out, const void* dout, voi
         p.col_slot0 = col_slot0;
         p.g1 = clip_f32(c, c->o_gk); p.dv = static_cast<uint16_t*>(dv);
         p.H = c->H; p.D = c->D;
-        const int m = std::min(MAX_BWD_GROUPS, n_clip - base);
+        const int m = int(std::min<size_t>(MAX_BWD_GROUPS, groups.size() - base));
+        // longest streams first
+        std::vector<BwdGroup> part(groups.begin() + base, groups.begin() + base + m);
+        std::stable_sort(part.begin(), part.end(), [](const BwdGroup& a, const BwdGroup& b) { return a.re[0] - a.rs[0] > b.re[0] - b.rs[0]; });
         int tiles = 0;
         for (int i = 0; i < m; ++i) {
-            const int gc = base + i;                                          // frame of the clip
-            const int64_t gframe = clip_start + gc;
-            const int c_first = gc / c->C;
-            // a sink frame is seen by every later chunk, any other frame while it is within W frames before a chunk
-            const int c_last = gframe < c->S ? n_chunks - 1 : std::min(n_chunks - 1, (gc + c->W) / c->C);
-            BwdGroup& g = p.group[i];
-            g.c_begin = gc * c->P; g.c_end = g.c_begin + c->P; g.tile_begin = tiles;
-            g.n_ranges = 1;
-            g.rs[0] = c_first * c->C * c->P;
-            g.re[0] = int(std::min<int64_t>(n_clip, int64_t(c_last + 1) * c->C) * c->P);
-            tiles += (c->P + 127) / 128;
+            p.group[i] = part[i];
+            p.group[i].tile_begin = tiles;
+            tiles += (part[i].c_end - part[i].c_begin + 127) / 128;
         }
         p.n_groups = m; p.n_tiles = tiles;
         e = launch_bwd_dkv(p, s);

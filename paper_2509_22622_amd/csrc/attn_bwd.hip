@@ -240,8 +240,11 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
                              reinterpret_cast<const char*>(p.s_k2 + head * p.hs_k2),    // dO   K-style
                              reinterpret_cast<const char*>(p.s_t1 + head * p.hs_t1),    // dO^T V^T-style
                              reinterpret_cast<const char*>(p.s_t2 + head * p.hs_t2)};   // q'^T V^T-style
-    const float* lse_h = p.lse + int64_t(head) * p.row_stride;
-    const float* delta_h = p.delta + int64_t(head) * p.row_stride;
+    // Read-only for the whole launch and addressed uniformly over the wave: as pointers into the constant address
+    // space their loads go through the scalar unit and its cache instead of the vector memory pipe.
+    typedef const float __attribute__((address_space(4))) * const_f32_ptr;
+    const const_f32_ptr lse_h = (const_f32_ptr)(uintptr_t)(p.lse + int64_t(head) * p.row_stride);
+    const const_f32_ptr delta_h = (const_f32_ptr)(uintptr_t)(p.delta + int64_t(head) * p.row_stride);
 
     const int qb_begin = g.rs[0] / KBLOCK, qb_end = (g.re[0] + KBLOCK - 1) / KBLOCK;   // one range of query rows
     const int n_blocks = qb_end - qb_begin;
@@ -287,26 +290,27 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, kf[ks], s, 0, 0, 0);
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad, vf[ks], dp, 0, 0, 0);
         }
-        // register r stands for query row0 + 16(r/8) + 8 half + r%8: its lse and delta (rows past the clip read the
-        // zero padding of the two vectors; they are dead rows)
+        // register r stands for query row0 + 16(r/8) + 8 half + r%8.  The block's 32 lse and 32 delta values sit at
+        // wave-uniform addresses (scalar loads); each lane then picks its half's (rows past the clip read the zero
+        // padding of the two vectors; they are dead rows)
         unsigned pw[2][4], dz[2][4];
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
-            const int rbase = row0 + 16 * t + 8 * half;
-            const f32x4 l0 = *reinterpret_cast<const f32x4*>(lse_h + rbase), l1 = *reinterpret_cast<const f32x4*>(lse_h + rbase + 4);
-            const f32x4 d0 = *reinterpret_cast<const f32x4*>(delta_h + rbase), d1 = *reinterpret_cast<const f32x4*>(delta_h + rbase + 4);
-            const float lv[8] = {l0[0], l0[1], l0[2], l0[3], l1[0], l1[1], l1[2], l1[3]};
-            const float dl[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float pv[2], zv[2];
 #pragma unroll
                 for (int k = 0; k < 2; ++k) {
                     const int r = 8 * t + 2 * e + k;
+                    const int lo = row0 + 16 * t + 2 * e + k;          // uniform; the other half's row is 8 further
+                    float l0 = lse_h[lo], l1 = lse_h[lo + 8], d0 = delta_h[lo], d1 = delta_h[lo + 8];
+                    asm volatile("" : "+s"(l0), "+s"(l1), "+s"(d0), "+s"(d1));   // values in scalar registers: scalar loads
+                    const float lv = half ? l1 : l0;
+                    const float dl = half ? d1 : d0;
                     const bool on = (live >> r) & 1;
-                    const float pr = on ? __builtin_amdgcn_exp2f(s[r] - lv[2 * e + k]) : 0.f;
+                    const float pr = on ? __builtin_amdgcn_exp2f(s[r] - lv) : 0.f;
                     pv[k] = pr;
-                    zv[k] = on ? pr * (dp[r] - dl[2 * e + k]) : 0.f;
+                    zv[k] = on ? pr * (dp[r] - dl) : 0.f;
                 }
                 pw[t][e] = bw_pack_bf16(pv[0], pv[1]);
                 dz[t][e] = bw_pack_bf16(zv[0], zv[1]);

@@ -3,7 +3,7 @@
 Tolerances.  Forward: those of the inference path (max-abs 1e-2, relative L2 5e-3).  Gradients: the backward kernels
 rebuild the softmax weights P from bf16 operands, round P and dZ = P (dP - delta) to bf16 for the second products and
 the results to bf16 again; each rounding is 2^-9 relative and they add up over three stages in which errors of
-different keys average out.  Relative L2 <= 1e-2 per gradient tensor, and no element further off than 2 % of the
+different keys average out (measured: 3.1e-3 to 3.8e-3).  Relative L2 <= 6e-3 per gradient tensor, and no element further off than 2 % of the
 tensor's largest magnitude.
 """
 import numpy as np
@@ -19,7 +19,7 @@ import gpu_harness as H
 
 pytestmark = pytest.mark.gpu
 
-GRAD_REL_L2 = 1e-2
+GRAD_REL_L2 = 6e-3
 GRAD_MAX_FRAC = 2e-2
 
 
