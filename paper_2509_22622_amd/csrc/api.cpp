@@ -913,6 +913,7 @@ ll_status ll_clip_backward(ll_clip* clip, const void* out, const void* dout, voi
     if (e == hipSuccess) e = clip_write_pair(c, dO, qrot, rows, clip_u16(c, c->o_cd), c->kb_clip, c->hs_clip, s);   // dO K-style, q'^T
     if (e != hipSuccess) return hip_fail(e, "clip backward preparation kernels launch");
     const int64_t v_off_all = c->kb_all * KBLOCK * c->D, v_off_clip = c->kb_clip * KBLOCK * c->D;
+    const int cols = bwd_tile_cols(c->D);
     // 2. Gq: queries as columns, chunk by chunk over each chunk's key ranges
     const int n_chunks = (n_clip + c->C - 1) / c->C;
     for (int base = 0; base < n_chunks; base += MAX_BWD_GROUPS) {
@@ -935,7 +936,7 @@ ll_status ll_clip_backward(ll_clip* clip, const void* out, const void* dout, voi
             g.c_begin = ci * c->C * c->P; g.c_end = g.c_begin + n * c->P; g.tile_begin = tiles;
             g.n_ranges = int(ranges.size());
             for (int r = 0; r < g.n_ranges; ++r) { g.rs[r] = int(ranges[r].begin); g.re[r] = int(ranges[r].end); }
-            tiles += (g.c_end - g.c_begin + 127) / 128;
+            tiles += (g.c_end - g.c_begin + cols - 1) / cols;
         }
         p.n_groups = m; p.n_tiles = tiles;
         e = launch_bwd_dq(p, s);
@@ -980,7 +981,7 @@ ll_status ll_clip_backward(ll_clip* clip, const void* out, const void* dout, voi
         for (int i = 0; i < m; ++i) {
             p.group[i] = part[i];
             p.group[i].tile_begin = tiles;
-            tiles += (part[i].c_end - part[i].c_begin + 127) / 128;
+            tiles += (part[i].c_end - part[i].c_begin + cols - 1) / cols;
         }
         p.n_groups = m; p.n_tiles = tiles;
         e = launch_bwd_dkv(p, s);

@@ -74,13 +74,14 @@ __device__ inline void bw_load_kstyle_row(const uint16_t* region, int64_t slot, 
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_bwd_dq_kernel(const BwdParams p) {
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_bwd_dq_kernel(const BwdParams p) {
     constexpr int KS = D / 16, DB = D / 32;
     constexpr int KB_BYTES = KBLOCK * D * 2;
     constexpr int NREG = 3;                           // streamed regions per block
-    constexpr int CPT = KB_BYTES / 16 / 256;          // 16-byte chunks per thread per region and block
-    static_assert(KB_BYTES % (16 * 256) == 0, "a kblock must split evenly over the threads");
+    constexpr int NT = NW * 64;
+    constexpr int CPT = KB_BYTES / 16 / NT;           // 16-byte chunks per thread per region and block
+    static_assert(KB_BYTES % (16 * NT) == 0, "a kblock must split evenly over the threads");
     extern __shared__ __attribute__((aligned(16))) char lds[];   // [2][NREG][KB_BYTES]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -90,7 +91,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     int gi = 0;
     while (gi + 1 < p.n_groups && tile >= p.group[gi + 1].tile_begin) ++gi;
     const BwdGroup& g = p.group[gi];
-    const int q0 = g.c_begin + (tile - g.tile_begin) * 128 + wave * 32;
+    const int q0 = g.c_begin + (tile - g.tile_begin) * (NW * 32) + wave * 32;
     const int row = min(q0 + col, g.c_end - 1);
 
     bf16x8 qf[KS], dof[KS];
@@ -126,14 +127,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         for (int s = 0; s < NREG; ++s)
 #pragma unroll
             for (int i = 0; i < CPT; ++i)
-                reg[s][i] = *reinterpret_cast<const u32x4*>(src[s] + int64_t(kblk) * KB_BYTES + (tid + i * 256) * 16);
+                reg[s][i] = *reinterpret_cast<const u32x4*>(src[s] + int64_t(kblk) * KB_BYTES + (tid + i * NT) * 16);
     };
     auto stash = [&](int buf) {
 #pragma unroll
         for (int s = 0; s < NREG; ++s)
 #pragma unroll
             for (int i = 0; i < CPT; ++i)
-                *reinterpret_cast<u32x4*>(lds + (buf * NREG + s) * KB_BYTES + (tid + i * 256) * 16) = reg[s][i];
+                *reinterpret_cast<u32x4*>(lds + (buf * NREG + s) * KB_BYTES + (tid + i * NT) * 16) = reg[s][i];
     };
     fetch(kb);
     stash(0);
@@ -207,12 +208,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-template <int D>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_bwd_dkv_kernel(const BwdParams p) {
+template <int D, int NW>
+__global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_bwd_dkv_kernel(const BwdParams p) {
     constexpr int KS = D / 16, DB = D / 32;
     constexpr int KB_BYTES = KBLOCK * D * 2;
     constexpr int NREG = 4;
-    constexpr int CPT = KB_BYTES / 16 / 256;
+    constexpr int NT = NW * 64;
+    constexpr int CPT = KB_BYTES / 16 / NT;
+    static_assert(KB_BYTES % (16 * NT) == 0, "a kblock must split evenly over the threads");
     extern __shared__ __attribute__((aligned(16))) char lds[];   // [2][NREG][KB_BYTES]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -222,7 +225,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
     int gi = 0;
     while (gi + 1 < p.n_groups && tile >= p.group[gi + 1].tile_begin) ++gi;
     const BwdGroup& g = p.group[gi];
-    const int k0 = g.c_begin + (tile - g.tile_begin) * 128 + wave * 32;     // clip token index of this wave's first key
+    const int k0 = g.c_begin + (tile - g.tile_begin) * (NW * 32) + wave * 32;     // clip token index of this wave's first key
     const int key = min(k0 + col, g.c_end - 1);
 
     // this column's K' and V rows, from the K-style regions of all resident frames (the clip is their tail)
@@ -255,14 +258,14 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) voi
         for (int s = 0; s < NREG; ++s)
 #pragma unroll
             for (int i = 0; i < CPT; ++i)
-                reg[s][i] = *reinterpret_cast<const u32x4*>(src[s] + int64_t(blk) * KB_BYTES + (tid + i * 256) * 16);
+                reg[s][i] = *reinterpret_cast<const u32x4*>(src[s] + int64_t(blk) * KB_BYTES + (tid + i * NT) * 16);
     };
     auto stash = [&](int buf) {
 #pragma unroll
         for (int s = 0; s < NREG; ++s)
 #pragma unroll
             for (int i = 0; i < CPT; ++i)
-                *reinterpret_cast<u32x4*>(lds + (buf * NREG + s) * KB_BYTES + (tid + i * 256) * 16) = reg[s][i];
+                *reinterpret_cast<u32x4*>(lds + (buf * NREG + s) * KB_BYTES + (tid + i * NT) * 16) = reg[s][i];
     };
     if (n_blocks > 0) {
         fetch(qb_begin);
@@ -422,19 +425,22 @@ static hipError_t set_lds(const void* fn, int bytes, bool& done) {
     return e;
 }
 
+// Columns per workgroup: 8 waves (one staged block serves 256 columns) where a kblock splits over 512 threads.
+int bwd_tile_cols(int D) { return D == 128 ? 256 : 128; }
+
 hipError_t launch_bwd_dq(const BwdParams& p, hipStream_t s) {
     const int total = p.n_tiles * p.H;
     if (total <= 0) return hipSuccess;
     const int grid = ((total + 7) / 8) * 8, lds = 2 * 3 * KBLOCK * p.D * 2;
     static bool done128 = false, done64 = false;
     if (p.D == 128) {
-        hipError_t e = set_lds(reinterpret_cast<const void*>(ll_bwd_dq_kernel<128>), lds, done128);
+        hipError_t e = set_lds(reinterpret_cast<const void*>(ll_bwd_dq_kernel<128, 8>), lds, done128);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(ll_bwd_dq_kernel<128>, dim3(grid), dim3(256), lds, s, p);
+        hipLaunchKernelGGL((ll_bwd_dq_kernel<128, 8>), dim3(grid), dim3(512), lds, s, p);
     } else if (p.D == 64) {
-        hipError_t e = set_lds(reinterpret_cast<const void*>(ll_bwd_dq_kernel<64>), lds, done64);
+        hipError_t e = set_lds(reinterpret_cast<const void*>(ll_bwd_dq_kernel<64, 4>), lds, done64);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(ll_bwd_dq_kernel<64>, dim3(grid), dim3(256), lds, s, p);
+        hipLaunchKernelGGL((ll_bwd_dq_kernel<64, 4>), dim3(grid), dim3(256), lds, s, p);
     } else return hipErrorInvalidValue;
     return hipGetLastError();
 }
@@ -445,13 +451,13 @@ hipError_t launch_bwd_dkv(const BwdParams& p, hipStream_t s) {
     const int grid = ((total + 7) / 8) * 8, lds = 2 * 4 * KBLOCK * p.D * 2;
     static bool done128 = false, done64 = false;
     if (p.D == 128) {
-        hipError_t e = set_lds(reinterpret_cast<const void*>(ll_bwd_dkv_kernel<128>), lds, done128);
+        hipError_t e = set_lds(reinterpret_cast<const void*>(ll_bwd_dkv_kernel<128, 8>), lds, done128);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(ll_bwd_dkv_kernel<128>, dim3(grid), dim3(256), lds, s, p);
+        hipLaunchKernelGGL((ll_bwd_dkv_kernel<128, 8>), dim3(grid), dim3(512), lds, s, p);
     } else if (p.D == 64) {
-        hipError_t e = set_lds(reinterpret_cast<const void*>(ll_bwd_dkv_kernel<64>), lds, done64);
+        hipError_t e = set_lds(reinterpret_cast<const void*>(ll_bwd_dkv_kernel<64, 4>), lds, done64);
         if (e != hipSuccess) return e;
-        hipLaunchKernelGGL(ll_bwd_dkv_kernel<64>, dim3(grid), dim3(256), lds, s, p);
+        hipLaunchKernelGGL((ll_bwd_dkv_kernel<64, 4>), dim3(grid), dim3(256), lds, s, p);
     } else return hipErrorInvalidValue;
     return hipGetLastError();
 }

@@ -129,7 +129,7 @@ struct ReadFrameParams {
 constexpr int MAX_BWD_GROUPS = 32;
 struct BwdGroup {                // column tiles that share one set of streamed rows
     int c_begin, c_end;          // columns: query rows (dQ kernel) or clip-token indices of keys (dK/dV kernel)
-    int tile_begin;              // first 128-column tile of the group in the launch
+    int tile_begin;              // first tile (bwd_tile_cols columns) of the group in the launch
     int n_ranges;
     int rs[2], re[2];            // streamed rows: key token slots (dQ kernel), query rows (dK/dV kernel: one range)
 };
@@ -156,6 +156,7 @@ struct BwdFinishParams {
     int64_t frame0;              // absolute index of the first frame
     float q_mul, k_mul;          // 1/sqrt(D), ln 2
 };
+int bwd_tile_cols(int D);     // columns per workgroup of the two kernels below
 hipError_t launch_bwd_dq(const BwdParams& p, hipStream_t s);
 hipError_t launch_bwd_dkv(const BwdParams& p, hipStream_t s);
 hipError_t launch_bwd_delta(const uint16_t* out, const uint16_t* dout, float* delta, int rows, int H, int D,
