@@ -14,7 +14,8 @@
 //   ll_bwd_dq_kernel:  columns = queries;  streams K' (K-style), V (K-style), K'^T (V^T-style);   Gq^T += K'^T dZ^T
 //   ll_bwd_dkv_kernel: columns = clip keys; streams q', dO (K-style), dO^T, q'^T (V^T-style);
 //                      dV^T += dO^T P,  Gk^T += q'^T dZ
-// Plain double-buffered staging through LDS (global -> registers -> LDS), one workgroup of 4 waves per 128 columns.
+// The streamed blocks reach LDS by direct loads into a ring of stages, two blocks ahead; one workgroup of 8 waves
+// (4 at head_dim 64) per 256 (128) columns.
 #include "kernels.h"
 
 namespace ll {
@@ -53,6 +54,40 @@ __device__ inline bf16x8 bw_masked_fragment(u32x4 av, unsigned live, int t) {
     return __builtin_bit_cast(bf16x8, av);
 }
 
+// s_waitcnt that only waits for vector-memory loads: at most N outstanding.
+template <int N>
+__device__ __forceinline__ void bw_wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
+}
+
+// Barrier without the fence of __syncthreads (which would wait for every outstanding load, the prefetched blocks
+// included); the "memory" clobber keeps the compiler from moving LDS reads across it.
+__device__ __forceinline__ void bw_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// Walks the 32-row blocks of a group's streamed ranges in order; past the end it stays on the last block.
+struct BwIter { int rng, kb, kb_end; };
+__device__ inline void bw_iter_init(const BwdGroup& g, BwIter& it) {
+    it.rng = 0;
+    it.kb = g.rs[0] / KBLOCK;
+    it.kb_end = (g.re[0] + KBLOCK - 1) / KBLOCK;
+}
+__device__ inline void bw_iter_advance(const BwdGroup& g, BwIter& it) {
+    if (it.kb + 1 < it.kb_end) {
+        ++it.kb;
+    } else if (it.rng + 1 < g.n_ranges) {
+        ++it.rng;
+        it.kb = g.rs[it.rng] / KBLOCK;
+        it.kb_end = (g.re[it.rng] + KBLOCK - 1) / KBLOCK;
+    }
+}
+
+// The streamed blocks go from memory straight into a ring of LDS stages (global_load_lds, one 1 KB fragment per wave
+// and load), PF blocks ahead of the block being worked on.  Per block: issue the loads of block it + PF, wait until
+// this wave's loads of block it have landed (all but the PF * LPW youngest), barrier (every wave's have), compute.
+// A wave can be one block ahead of the slowest one, so the stage it writes, (it + 1 + PF) mod NS, must differ from the
+// one still being read, it mod NS: NS = PF + 2.
+constexpr int BW_PF = 2, BW_NS = 4;
+
 // Workgroup -> (head, column tile): contiguous runs of items per XCD, as in the forward kernels.
 __device__ inline bool bw_item(int n_tiles, int H, int& head, int& tile) {
     const int total = n_tiles * H;
@@ -79,10 +114,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     constexpr int KS = D / 16, DB = D / 32;
     constexpr int KB_BYTES = KBLOCK * D * 2;
     constexpr int NREG = 3;                           // streamed regions per block
-    constexpr int NT = NW * 64;
-    constexpr int CPT = KB_BYTES / 16 / NT;           // 16-byte chunks per thread per region and block
-    static_assert(KB_BYTES % (16 * NT) == 0, "a kblock must split evenly over the threads");
-    extern __shared__ __attribute__((aligned(16))) char lds[];   // [2][NREG][KB_BYTES]
+    extern __shared__ __attribute__((aligned(16))) char lds[];   // [BW_NS][NREG][KB_BYTES]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -118,41 +150,39 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
     int n_blocks = 0;
     for (int r = 0; r < g.n_ranges; ++r) n_blocks += (g.re[r] + KBLOCK - 1) / KBLOCK - g.rs[r] / KBLOCK;
-    int rng = 0;
-    int kb = g.rs[0] / KBLOCK, kb_end = (g.re[0] + KBLOCK - 1) / KBLOCK;
 
-    u32x4 reg[NREG][CPT];
-    auto fetch = [&](int kblk) {
+    constexpr int FPR = KB_BYTES / 1024;              // 1 KB fragments per region and block
+    constexpr int LPW = NREG * FPR / NW;              // loads per wave and block
+    static_assert((NREG * FPR) % NW == 0, "fragments must split over the waves");
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    auto issue = [&](int kblk, int stage) {
 #pragma unroll
-        for (int s = 0; s < NREG; ++s)
-#pragma unroll
-            for (int i = 0; i < CPT; ++i)
-                reg[s][i] = *reinterpret_cast<const u32x4*>(src[s] + int64_t(kblk) * KB_BYTES + (tid + i * NT) * 16);
+        for (int l = 0; l < LPW; ++l) {
+            const int f = wave_u + NW * l, region = f / FPR, fr = f % FPR;      // wave-uniform
+            const char* from = src[region] + int64_t(kblk) * KB_BYTES + fr * 1024 + lane * 16;
+            char* to = lds + (stage * NREG + region) * KB_BYTES + fr * 1024;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(from),
+                                             (__attribute__((address_space(3))) void*)(to), 16, 0, 0);
+        }
     };
-    auto stash = [&](int buf) {
+    BwIter li, ci;
+    bw_iter_init(g, li);
+    bw_iter_init(g, ci);
 #pragma unroll
-        for (int s = 0; s < NREG; ++s)
-#pragma unroll
-            for (int i = 0; i < CPT; ++i)
-                *reinterpret_cast<u32x4*>(lds + (buf * NREG + s) * KB_BYTES + (tid + i * NT) * 16) = reg[s][i];
-    };
-    fetch(kb);
-    stash(0);
-    __syncthreads();
+    for (int j = 0; j < BW_PF; ++j) {
+        issue(li.kb, j);
+        bw_iter_advance(g, li);
+    }
 
     for (int it = 0; it < n_blocks; ++it) {
-        const int cur_kb = kb, cur_rs = g.rs[rng], cur_re = g.re[rng];
-        ++kb;
-        if (kb >= kb_end && rng + 1 < g.n_ranges) {
-            ++rng;
-            kb = g.rs[rng] / KBLOCK;
-            kb_end = (g.re[rng] + KBLOCK - 1) / KBLOCK;
-        }
-        const bool more = it + 1 < n_blocks;
-        if (more) fetch(kb);
+        issue(li.kb, (it + BW_PF) & (BW_NS - 1));
+        bw_iter_advance(g, li);
+        bw_wait_vmcnt<BW_PF * LPW>();
+        bw_barrier();
 
-        const char* blk = lds + (it & 1) * NREG * KB_BYTES;
-        const int key0 = cur_kb * KBLOCK;
+        const char* blk = lds + (it & (BW_NS - 1)) * NREG * KB_BYTES;
+        const int key0 = ci.kb * KBLOCK, cur_rs = g.rs[ci.rng], cur_re = g.re[ci.rng];
+        bw_iter_advance(g, ci);
         const bool edge = key0 < cur_rs || key0 + KBLOCK > cur_re;
         const unsigned live = edge ? bw_live_mask(key0, cur_rs, cur_re, half) : 0xFFFFu;
 
@@ -190,9 +220,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, bv), acc[db], 0, 0, 0);
             }
         }
-        if (more) stash((it + 1) & 1);
-        __syncthreads();
     }
+    bw_wait_vmcnt<0>();                               // the loads issued past the end have landed before the wave leaves
 
     // Gq[row][head][32 db + 8 g + 4 half + i] = accumulator register 4 g + i
     if (q0 + col < g.c_end) {
@@ -213,10 +242,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     constexpr int KS = D / 16, DB = D / 32;
     constexpr int KB_BYTES = KBLOCK * D * 2;
     constexpr int NREG = 4;
-    constexpr int NT = NW * 64;
-    constexpr int CPT = KB_BYTES / 16 / NT;
-    static_assert(KB_BYTES % (16 * NT) == 0, "a kblock must split evenly over the threads");
-    extern __shared__ __attribute__((aligned(16))) char lds[];   // [2][NREG][KB_BYTES]
+    extern __shared__ __attribute__((aligned(16))) char lds[];   // [BW_NS][NREG][KB_BYTES]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -252,33 +278,30 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int qb_begin = g.rs[0] / KBLOCK, qb_end = (g.re[0] + KBLOCK - 1) / KBLOCK;   // one range of query rows
     const int n_blocks = qb_end - qb_begin;
 
-    u32x4 reg[NREG][CPT];
-    auto fetch = [&](int blk) {
+    constexpr int FPR = KB_BYTES / 1024;
+    constexpr int LPW = NREG * FPR / NW;
+    static_assert((NREG * FPR) % NW == 0, "fragments must split over the waves");
+    const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    auto issue = [&](int blk_i, int stage) {
 #pragma unroll
-        for (int s = 0; s < NREG; ++s)
-#pragma unroll
-            for (int i = 0; i < CPT; ++i)
-                reg[s][i] = *reinterpret_cast<const u32x4*>(src[s] + int64_t(blk) * KB_BYTES + (tid + i * NT) * 16);
+        for (int l = 0; l < LPW; ++l) {
+            const int f = wave_u + NW * l, region = f / FPR, fr = f % FPR;
+            const char* from = src[region] + int64_t(blk_i) * KB_BYTES + fr * 1024 + lane * 16;
+            char* to = lds + (stage * NREG + region) * KB_BYTES + fr * 1024;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(from),
+                                             (__attribute__((address_space(3))) void*)(to), 16, 0, 0);
+        }
     };
-    auto stash = [&](int buf) {
 #pragma unroll
-        for (int s = 0; s < NREG; ++s)
-#pragma unroll
-            for (int i = 0; i < CPT; ++i)
-                *reinterpret_cast<u32x4*>(lds + (buf * NREG + s) * KB_BYTES + (tid + i * NT) * 16) = reg[s][i];
-    };
-    if (n_blocks > 0) {
-        fetch(qb_begin);
-        stash(0);
-    }
-    __syncthreads();
+    for (int j = 0; j < BW_PF; ++j) issue(min(qb_begin + j, qb_end - 1), j);
 
     for (int it = 0; it < n_blocks; ++it) {
         const int qb = qb_begin + it;
-        const bool more = it + 1 < n_blocks;
-        if (more) fetch(qb + 1);
+        issue(min(qb + BW_PF, qb_end - 1), (it + BW_PF) & (BW_NS - 1));
+        bw_wait_vmcnt<BW_PF * LPW>();
+        bw_barrier();
 
-        const char* blk = lds + (it & 1) * NREG * KB_BYTES;
+        const char* blk = lds + (it & (BW_NS - 1)) * NREG * KB_BYTES;
         const int row0 = qb * KBLOCK;
         const bool edge = row0 < g.rs[0] || row0 + KBLOCK > g.re[0];
         const unsigned live = edge ? bw_live_mask(row0, g.rs[0], g.re[0], half) : 0xFFFFu;
@@ -333,9 +356,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 acc_k[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_q, __builtin_bit_cast(bf16x8, bz), acc_k[db], 0, 0, 0);
             }
         }
-        if (more) stash((it + 1) & 1);
-        __syncthreads();
     }
+    bw_wait_vmcnt<0>();
 
     if (k0 + col < g.c_end) {
         const int64_t off = (int64_t(k0 + col) * p.H + head) * D + half * 4;
@@ -431,7 +453,7 @@ int bwd_tile_cols(int D) { return D == 128 ? 256 : 128; }
 hipError_t launch_bwd_dq(const BwdParams& p, hipStream_t s) {
     const int total = p.n_tiles * p.H;
     if (total <= 0) return hipSuccess;
-    const int grid = ((total + 7) / 8) * 8, lds = 2 * 3 * KBLOCK * p.D * 2;
+    const int grid = ((total + 7) / 8) * 8, lds = BW_NS * 3 * KBLOCK * p.D * 2;
     static bool done128 = false, done64 = false;
     if (p.D == 128) {
         hipError_t e = set_lds(reinterpret_cast<const void*>(ll_bwd_dq_kernel<128, 8>), lds, done128);
@@ -448,7 +470,7 @@ hipError_t launch_bwd_dq(const BwdParams& p, hipStream_t s) {
 hipError_t launch_bwd_dkv(const BwdParams& p, hipStream_t s) {
     const int total = p.n_tiles * p.H;
     if (total <= 0) return hipSuccess;
-    const int grid = ((total + 7) / 8) * 8, lds = 2 * 4 * KBLOCK * p.D * 2;
+    const int grid = ((total + 7) / 8) * 8, lds = BW_NS * 4 * KBLOCK * p.D * 2;
     static bool done128 = false, done64 = false;
     if (p.D == 128) {
         hipError_t e = set_lds(reinterpret_cast<const void*>(ll_bwd_dkv_kernel<128, 8>), lds, done128);
