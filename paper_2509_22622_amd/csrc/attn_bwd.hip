@@ -173,20 +173,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         issue(li.kb, j);
         bw_iter_advance(g, li);
     }
-
-    for (int it = 0; it < n_blocks; ++it) {
-        issue(li.kb, (it + BW_PF) & (BW_NS - 1));
-        bw_iter_advance(g, li);
-        bw_wait_vmcnt<BW_PF * LPW>();
-        bw_barrier();
-
-        const char* blk = lds + (it & (BW_NS - 1)) * NREG * KB_BYTES;
-        const int key0 = ci.kb * KBLOCK, cur_rs = g.rs[ci.rng], cur_re = g.re[ci.rng];
-        bw_iter_advance(g, ci);
-        const bool edge = key0 < cur_rs || key0 + KBLOCK > cur_re;
-        const unsigned live = edge ? bw_live_mask(key0, cur_rs, cur_re, half) : 0xFFFFu;
-
-        f32x16 s, dp;
+    // Software pipeline: the two feature-contracting products of block it + 1 are issued before the vector work of
+    // block it (exp2, dZ, packing), which does not depend on them, so the matrix pipe runs under that work.
+    auto scores = [&](const char* blk, f32x16& s, f32x16& dp) {
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
 #pragma unroll
@@ -196,6 +185,28 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ak, qf[ks], s, 0, 0, 0);
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, dof[ks], dp, 0, 0, 0);
         }
+    };
+    f32x16 s, dp;
+    bw_wait_vmcnt<(BW_PF - 1) * LPW>();              // block 0 has landed
+    bw_barrier();
+    scores(lds, s, dp);
+
+    for (int it = 0; it < n_blocks; ++it) {
+        issue(li.kb, (it + BW_PF) & (BW_NS - 1));
+        bw_iter_advance(g, li);
+        bw_wait_vmcnt<(BW_PF - 1) * LPW>();          // this wave's loads of block it + 1 have landed
+        bw_barrier();
+
+        const char* blk = lds + (it & (BW_NS - 1)) * NREG * KB_BYTES;
+        const int key0 = ci.kb * KBLOCK, cur_rs = g.rs[ci.rng], cur_re = g.re[ci.rng];
+        bw_iter_advance(g, ci);
+        const bool edge = key0 < cur_rs || key0 + KBLOCK > cur_re;
+        const unsigned live = edge ? bw_live_mask(key0, cur_rs, cur_re, half) : 0xFFFFu;
+
+        // block it + 1 (past the end: the last block again, its result unused)
+        f32x16 s_next, dp_next;
+        scores(lds + ((it + 1) & (BW_NS - 1)) * NREG * KB_BYTES, s_next, dp_next);
+
         unsigned dz[2][4];
 #pragma unroll
         for (int t = 0; t < 2; ++t)
@@ -220,6 +231,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, bv), acc[db], 0, 0, 0);
             }
         }
+        s = s_next;
+        dp = dp_next;
     }
     bw_wait_vmcnt<0>();                               // the loads issued past the end have landed before the wave leaves
 
