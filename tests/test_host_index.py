@@ -262,3 +262,38 @@ def test_prompt_handle_bookkeeping_and_errors():
         B._check(L.ll_prompt_recache(p._h, 0, C.cast(C.pointer(one), C.c_void_p), None, 5, None))
     assert e.value.status == 1
     p.close()
+
+
+def test_clip_handle_bookkeeping_and_errors():
+    """The train-time handle's host logic on an index-only handle: sizes, argument checks, call order."""
+    L = B.lib()
+    assert L.ll_clip_bytes(12, 128, 1560, 3, 9, 21, 3) > 21 * 1560 * 12 * 128 * 2
+    for bad in ((0, 128, 60, 3, 6, 9, 3), (4, 96, 60, 3, 6, 9, 3), (4, 64, 0, 3, 6, 9, 3), (4, 64, 60, -1, 6, 9, 3),
+                (4, 64, 60, 3, 6, 0, 3), (4, 64, 60, 3, 6, 9, 0)):
+        assert L.ll_clip_bytes(*bad) == 0, bad
+    with pytest.raises(B.LongLiveError) as e:
+        B.Clip(4, 96, 6, 10, 3, 3, 6, 9, device=None)
+    assert e.value.status == 4
+    h = C.c_void_p()
+    assert L.ll_clip_create(4, 64, 61, 3, 6, 9, 3, 6, 10, 10000.0, None, 0, C.byref(h)) == 1     # P != grid
+    assert L.ll_clip_create(4, 64, 60, 3, 6, 9, 3, 6, 10, 10000.0, None, 16, C.byref(h)) == 1    # null buffer with a size
+    c = B.Clip(4, 64, 6, 10, 3, 3, 6, 9, device=None)
+    with pytest.raises(B.LongLiveError) as e:
+        c.backward()                                                              # nothing to differentiate yet
+    assert e.value.status == 2
+    for bad in (lambda: c.forward(9, 6, 10), lambda: c.forward(9, 6, 0), lambda: c.forward(9, 7, 9),
+                lambda: c.forward(-1, 0, 3), lambda: c.forward(2, 1, 3),          # context cuts into the sink
+                lambda: c.forward(0, 2, 3)):                                      # a context that would hold the sink
+        with pytest.raises(B.LongLiveError) as e:
+            bad()
+        assert e.value.status == 1
+    with pytest.raises(B.LongLiveError) as e:
+        c.backward()                                                              # a refused forward leaves no state
+    assert e.value.status == 2
+    c.forward(9, 6, 9)
+    c.backward()
+    c.forward(0, 0, 7)                                                            # a video's first clip
+    c.backward()
+    c.forward(3, 0, 4)                                                            # right after the sink, no context
+    c.backward()
+    c.close()
