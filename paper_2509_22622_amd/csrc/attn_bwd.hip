@@ -44,14 +44,17 @@ __device__ inline unsigned bw_live_mask(int row0, int lo, int hi, int half) {
     return live;
 }
 
-// a V^T-style fragment with the elements of dead rows cleared (they may hold anything)
-__device__ inline bf16x8 bw_masked_fragment(u32x4 av, unsigned live, int t) {
+// Dead rows (outside the streamed range, in the blocks at its ends) get weight exactly zero: score -inf, so that
+// P = 2^(-inf - lse) = 0 and dZ = 0 * (0 - delta) = 0.  The fragments they multiply are not cleared: every resident
+// frame of a step holds finite values written by this step, so 0 * fragment = 0.  (The inference kernels do clear
+// them, since a ring slot outside the key set may hold anything.)
+__device__ inline void bw_kill_dead_rows(f32x16& s, f32x16& dp, unsigned live) {
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        const unsigned b0 = (live >> (8 * t + 2 * e)) & 1, b1 = (live >> (8 * t + 2 * e + 1)) & 1;
-        av[e] &= (b0 ? 0x0000FFFFu : 0u) | (b1 ? 0xFFFF0000u : 0u);
-    }
-    return __builtin_bit_cast(bf16x8, av);
+    for (int r = 0; r < 16; ++r)
+        if (!((live >> r) & 1)) {
+            s[r] = -INFINITY;
+            dp[r] = 0.f;
+        }
 }
 
 // s_waitcnt that only waits for vector-memory loads: at most N outstanding.
@@ -203,6 +206,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         const bool edge = key0 < cur_rs || key0 + KBLOCK > cur_re;
         const unsigned live = edge ? bw_live_mask(key0, cur_rs, cur_re, half) : 0xFFFFu;
 
+        if (edge) bw_kill_dead_rows(s, dp, live);    // uniform branch: only the blocks at the ends of a range
+
         // block it + 1 (past the end: the last block again, its result unused)
         f32x16 s_next, dp_next;
         scores(lds + ((it + 1) & (BW_NS - 1)) * NREG * KB_BYTES, s_next, dp_next);
@@ -217,7 +222,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 for (int k = 0; k < 2; ++k) {
                     const int r = 8 * t + 2 * e + k;
                     const float pr = __builtin_amdgcn_exp2f(s[r] - lse);
-                    z[k] = ((live >> r) & 1) ? pr * (dp[r] - delta) : 0.f;
+                    z[k] = pr * (dp[r] - delta);
                 }
                 dz[t][e] = bw_pack_bf16(z[0], z[1]);
             }
@@ -226,8 +231,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
             const u32x4 bv = {dz[t][0], dz[t][1], dz[t][2], dz[t][3]};
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                const u32x4 raw = *reinterpret_cast<const u32x4*>(blk + 2 * KB_BYTES + (db * 2 + t) * 1024 + lane * 16);
-                const bf16x8 a = edge ? bw_masked_fragment(raw, live, t) : __builtin_bit_cast(bf16x8, raw);
+                const bf16x8 a = *reinterpret_cast<const bf16x8*>(blk + 2 * KB_BYTES + (db * 2 + t) * 1024 + lane * 16);
                 acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, bv), acc[db], 0, 0, 0);
             }
         }
@@ -329,6 +333,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, kf[ks], s, 0, 0, 0);
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad, vf[ks], dp, 0, 0, 0);
         }
+        if (edge) bw_kill_dead_rows(s, dp, live);    // uniform branch: only the blocks at the ends of the range
         // register r stands for query row0 + 16(r/8) + 8 half + r%8.  The block's 32 lse and 32 delta values sit at
         // wave-uniform addresses (scalar loads); each lane then picks its half's (rows past the clip read the zero
         // padding of the two vectors; they are dead rows)
@@ -346,10 +351,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
                     asm volatile("" : "+s"(l0), "+s"(l1), "+s"(d0), "+s"(d1));   // values in scalar registers: scalar loads
                     const float lv = half ? l1 : l0;
                     const float dl = half ? d1 : d0;
-                    const bool on = (live >> r) & 1;
-                    const float pr = on ? __builtin_amdgcn_exp2f(s[r] - lv) : 0.f;
+                    const float pr = __builtin_amdgcn_exp2f(s[r] - lv);
                     pv[k] = pr;
-                    zv[k] = on ? pr * (dp[r] - dl) : 0.f;
+                    zv[k] = pr * (dp[r] - dl);
                 }
                 pw[t][e] = bw_pack_bf16(pv[0], pv[1]);
                 dz[t][e] = bw_pack_bf16(zv[0], zv[1]);
@@ -361,10 +365,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
             const u32x4 bz = {dz[t][0], dz[t][1], dz[t][2], dz[t][3]};
 #pragma unroll
             for (int db = 0; db < DB; ++db) {
-                const u32x4 rd = *reinterpret_cast<const u32x4*>(blk + 2 * KB_BYTES + (db * 2 + t) * 1024 + lane * 16);
-                const u32x4 rq = *reinterpret_cast<const u32x4*>(blk + 3 * KB_BYTES + (db * 2 + t) * 1024 + lane * 16);
-                const bf16x8 a_d = edge ? bw_masked_fragment(rd, live, t) : __builtin_bit_cast(bf16x8, rd);
-                const bf16x8 a_q = edge ? bw_masked_fragment(rq, live, t) : __builtin_bit_cast(bf16x8, rq);
+                const bf16x8 a_d = *reinterpret_cast<const bf16x8*>(blk + 2 * KB_BYTES + (db * 2 + t) * 1024 + lane * 16);
+                const bf16x8 a_q = *reinterpret_cast<const bf16x8*>(blk + 3 * KB_BYTES + (db * 2 + t) * 1024 + lane * 16);
                 acc_v[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_d, __builtin_bit_cast(bf16x8, bp), acc_v[db], 0, 0, 0);
                 acc_k[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_q, __builtin_bit_cast(bf16x8, bz), acc_k[db], 0, 0, 0);
             }
