@@ -32,29 +32,19 @@ __device__ inline unsigned bw_pack_bf16(float a, float b) {
     return __builtin_bit_cast(unsigned, __builtin_convertvector(v, bf16x2));
 }
 
-// bit r: the streamed row that accumulator register r of a lane in half `half` stands for, row0 + 16(r/8) + 8 half +
-// r%8, lies in [lo, hi)
-__device__ inline unsigned bw_live_mask(int row0, int lo, int hi, int half) {
-    unsigned live = 0;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) {
-        const int row = row0 + 16 * (r >> 3) + 8 * half + (r & 7);
-        if (row >= lo && row < hi) live |= 1u << r;
-    }
-    return live;
-}
-
 // Dead rows (outside the streamed range, in the blocks at its ends) get weight exactly zero: score -inf, so that
 // P = 2^(-inf - lse) = 0 and dZ = 0 * (0 - delta) = 0.  The fragments they multiply are not cleared: every resident
 // frame of a step holds finite values written by this step, so 0 * fragment = 0.  (The inference kernels do clear
 // them, since a ring slot outside the key set may hold anything.)
-__device__ inline void bw_kill_dead_rows(f32x16& s, f32x16& dp, unsigned live) {
+__device__ inline void bw_kill_dead_rows(f32x16& s, f32x16& dp, int row0, int lo, int hi, int half) {
 #pragma unroll
-    for (int r = 0; r < 16; ++r)
-        if (!((live >> r) & 1)) {
+    for (int r = 0; r < 16; ++r) {
+        const int row = row0 + 16 * (r >> 3) + 8 * half + (r & 7);      // the row register r stands for
+        if (row < lo || row >= hi) {
             s[r] = -INFINITY;
             dp[r] = 0.f;
         }
+    }
 }
 
 // s_waitcnt that only waits for vector-memory loads: at most N outstanding.
@@ -189,12 +179,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, dof[ks], dp, 0, 0, 0);
         }
     };
-    f32x16 s, dp;
-    bw_wait_vmcnt<(BW_PF - 1) * LPW>();              // block 0 has landed
-    bw_barrier();
-    scores(lds, s, dp);
-
-    for (int it = 0; it < n_blocks; ++it) {
+    // One block: the vector work and the row-contracting product of block `it` from its scores (s, dp), and the scores
+    // of block it + 1 (past the end: the last block again, unused) into (s_next, dp_next).
+    auto block = [&](int it, f32x16& s, f32x16& dp, f32x16& s_next, f32x16& dp_next) {
         issue(li.kb, (it + BW_PF) & (BW_NS - 1));
         bw_iter_advance(g, li);
         bw_wait_vmcnt<(BW_PF - 1) * LPW>();          // this wave's loads of block it + 1 have landed
@@ -203,13 +190,9 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         const char* blk = lds + (it & (BW_NS - 1)) * NREG * KB_BYTES;
         const int key0 = ci.kb * KBLOCK, cur_rs = g.rs[ci.rng], cur_re = g.re[ci.rng];
         bw_iter_advance(g, ci);
-        const bool edge = key0 < cur_rs || key0 + KBLOCK > cur_re;
-        const unsigned live = edge ? bw_live_mask(key0, cur_rs, cur_re, half) : 0xFFFFu;
+        if (key0 < cur_rs || key0 + KBLOCK > cur_re)  // uniform: only the blocks at the ends of a range
+            bw_kill_dead_rows(s, dp, key0, cur_rs, cur_re, half);
 
-        if (edge) bw_kill_dead_rows(s, dp, live);    // uniform branch: only the blocks at the ends of a range
-
-        // block it + 1 (past the end: the last block again, its result unused)
-        f32x16 s_next, dp_next;
         scores(lds + ((it + 1) & (BW_NS - 1)) * NREG * KB_BYTES, s_next, dp_next);
 
         unsigned dz[2][4];
@@ -235,8 +218,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
                 acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, bv), acc[db], 0, 0, 0);
             }
         }
-        s = s_next;
-        dp = dp_next;
+    };
+    f32x16 s0, dp0, s1, dp1;
+    bw_wait_vmcnt<(BW_PF - 1) * LPW>();              // block 0 has landed
+    bw_barrier();
+    scores(lds, s0, dp0);
+    for (int it = 0; it < n_blocks; it += 2) {       // two blocks per trip: the two score sets swap roles, no copies
+        block(it, s0, dp0, s1, dp1);
+        if (it + 1 < n_blocks) block(it + 1, s1, dp1, s0, dp0);
     }
     bw_wait_vmcnt<0>();                               // the loads issued past the end have landed before the wave leaves
 
@@ -320,8 +309,6 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
         const char* blk = lds + (it & (BW_NS - 1)) * NREG * KB_BYTES;
         const int row0 = qb * KBLOCK;
-        const bool edge = row0 < g.rs[0] || row0 + KBLOCK > g.re[0];
-        const unsigned live = edge ? bw_live_mask(row0, g.rs[0], g.re[0], half) : 0xFFFFu;
 
         f32x16 s, dp;
 #pragma unroll
@@ -333,7 +320,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, kf[ks], s, 0, 0, 0);
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad, vf[ks], dp, 0, 0, 0);
         }
-        if (edge) bw_kill_dead_rows(s, dp, live);    // uniform branch: only the blocks at the ends of the range
+        if (row0 < g.rs[0] || row0 + KBLOCK > g.re[0])   // uniform: only the blocks at the ends of the range
+            bw_kill_dead_rows(s, dp, row0, g.rs[0], g.re[0], half);
         // register r stands for query row0 + 16(r/8) + 8 half + r%8.  The block's 32 lse and 32 delta values sit at
         // wave-uniform addresses (scalar loads); each lane then picks its half's (rows past the clip read the zero
         // padding of the two vectors; they are dead rows)
