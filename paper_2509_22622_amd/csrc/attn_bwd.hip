@@ -57,20 +57,27 @@ __device__ __forceinline__ void bw_wait_vmcnt() {
 // included); the "memory" clobber keeps the compiler from moving LDS reads across it.
 __device__ __forceinline__ void bw_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
-// Walks the 32-row blocks of a group's streamed ranges in order; past the end it stays on the last block.
-struct BwIter { int rng, kb, kb_end; };
-__device__ inline void bw_iter_init(const BwdGroup& g, BwIter& it) {
-    it.rng = 0;
-    it.kb = g.rs[0] / KBLOCK;
-    it.kb_end = (g.re[0] + KBLOCK - 1) / KBLOCK;
+// Walks the 32-row blocks of a group's streamed ranges in order; past the end it stays on the last block.  The ranges
+// are copied into registers once (no kernel-argument loads inside the loop).
+struct BwRanges { int n, rs0, re0, rs1, re1; };
+__device__ inline BwRanges bw_ranges(const BwdGroup& g) {
+    BwRanges r{g.n_ranges, g.rs[0], g.re[0], g.rs[1], g.re[1]};
+    if (r.n < 2) r.rs1 = r.re1 = 0;
+    return r;
 }
-__device__ inline void bw_iter_advance(const BwdGroup& g, BwIter& it) {
+struct BwIter { int rng, kb, kb_end; };
+__device__ inline void bw_iter_init(const BwRanges& g, BwIter& it) {
+    it.rng = 0;
+    it.kb = g.rs0 / KBLOCK;
+    it.kb_end = (g.re0 + KBLOCK - 1) / KBLOCK;
+}
+__device__ inline void bw_iter_advance(const BwRanges& g, BwIter& it) {
     if (it.kb + 1 < it.kb_end) {
         ++it.kb;
-    } else if (it.rng + 1 < g.n_ranges) {
-        ++it.rng;
-        it.kb = g.rs[it.rng] / KBLOCK;
-        it.kb_end = (g.re[it.rng] + KBLOCK - 1) / KBLOCK;
+    } else if (it.rng + 1 < g.n) {
+        it.rng = 1;
+        it.kb = g.rs1 / KBLOCK;
+        it.kb_end = (g.re1 + KBLOCK - 1) / KBLOCK;
     }
 }
 
@@ -158,13 +165,14 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
                                              (__attribute__((address_space(3))) void*)(to), 16, 0, 0);
         }
     };
+    const BwRanges gr = bw_ranges(g);
     BwIter li, ci;
-    bw_iter_init(g, li);
-    bw_iter_init(g, ci);
+    bw_iter_init(gr, li);
+    bw_iter_init(gr, ci);
 #pragma unroll
     for (int j = 0; j < BW_PF; ++j) {
         issue(li.kb, j);
-        bw_iter_advance(g, li);
+        bw_iter_advance(gr, li);
     }
     // Software pipeline: the two feature-contracting products of block it + 1 are issued before the vector work of
     // block it (exp2, dZ, packing), which does not depend on them, so the matrix pipe runs under that work.
@@ -183,13 +191,13 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // of block it + 1 (past the end: the last block again, unused) into (s_next, dp_next).
     auto block = [&](int it, f32x16& s, f32x16& dp, f32x16& s_next, f32x16& dp_next) {
         issue(li.kb, (it + BW_PF) & (BW_NS - 1));
-        bw_iter_advance(g, li);
+        bw_iter_advance(gr, li);
         bw_wait_vmcnt<(BW_PF - 1) * LPW>();          // this wave's loads of block it + 1 have landed
         bw_barrier();
 
         const char* blk = lds + (it & (BW_NS - 1)) * NREG * KB_BYTES;
-        const int key0 = ci.kb * KBLOCK, cur_rs = g.rs[ci.rng], cur_re = g.re[ci.rng];
-        bw_iter_advance(g, ci);
+        const int key0 = ci.kb * KBLOCK, cur_rs = ci.rng ? gr.rs1 : gr.rs0, cur_re = ci.rng ? gr.re1 : gr.re0;
+        bw_iter_advance(gr, ci);
         if (key0 < cur_rs || key0 + KBLOCK > cur_re)  // uniform: only the blocks at the ends of a range
             bw_kill_dead_rows(s, dp, key0, cur_rs, cur_re, half);
 
@@ -281,7 +289,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const const_f32_ptr lse_h = (const_f32_ptr)(uintptr_t)(p.lse + int64_t(head) * p.row_stride);
     const const_f32_ptr delta_h = (const_f32_ptr)(uintptr_t)(p.delta + int64_t(head) * p.row_stride);
 
-    const int qb_begin = g.rs[0] / KBLOCK, qb_end = (g.re[0] + KBLOCK - 1) / KBLOCK;   // one range of query rows
+    const int row_lo = g.rs[0], row_hi = g.re[0];                                 // one range of query rows
+    const int qb_begin = row_lo / KBLOCK, qb_end = (row_hi + KBLOCK - 1) / KBLOCK;
     const int n_blocks = qb_end - qb_begin;
 
     constexpr int FPR = KB_BYTES / 1024;
@@ -320,8 +329,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
             s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, kf[ks], s, 0, 0, 0);
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad, vf[ks], dp, 0, 0, 0);
         }
-        if (row0 < g.rs[0] || row0 + KBLOCK > g.re[0])   // uniform: only the blocks at the ends of the range
-            bw_kill_dead_rows(s, dp, row0, g.rs[0], g.re[0], half);
+        if (row0 < row_lo || row0 + KBLOCK > row_hi)     // uniform: only the blocks at the ends of the range
+            bw_kill_dead_rows(s, dp, row0, row_lo, row_hi, half);
         // register r stands for query row0 + 16(r/8) + 8 half + r%8.  The block's 32 lse and 32 delta values sit at
         // wave-uniform addresses (scalar loads); each lane then picks its half's (rows past the clip read the zero
         // padding of the two vectors; they are dead rows)
