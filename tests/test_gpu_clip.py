@@ -148,3 +148,21 @@ def test_graph_replay_of_a_training_step():
         assert float(dq.float().abs().max()) > 0
     eager.close()
     graphed.close()
+
+
+@pytest.mark.parametrize("idx", range(10))
+def test_random_geometries(idx):
+    """Seeded random small geometries: nothing aligned on purpose (P from 15 to 96, any S, W, C, clip and context
+    lengths, first clips and later ones)."""
+    rng = np.random.Generator(np.random.Philox(key=9000 + idx))
+    D = int(rng.choice([64, 128]))
+    gh, gw = int(rng.integers(3, 9)), int(rng.integers(5, 13))
+    C, S, W = int(rng.integers(1, 5)), int(rng.integers(0, 5)), int(rng.integers(0, 9))
+    T = int(rng.integers(3, 11))
+    n_clip = int(rng.integers(1, T + 1))
+    if idx % 4 == 0:
+        ctx_start, n_ctx = 0, 0                                   # a video's first clip
+    else:
+        n_ctx = int(rng.integers(0, W + 1))
+        ctx_start = S + int(rng.integers(0, 40))
+    run_case(int(rng.integers(1, 4)), D, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip, seed=10 + idx)
