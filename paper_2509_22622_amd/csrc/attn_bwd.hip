@@ -256,7 +256,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     constexpr int KS = D / 16, DB = D / 32;
     constexpr int KB_BYTES = KBLOCK * D * 2;
     constexpr int NREG = 4;
-    extern __shared__ __attribute__((aligned(16))) char lds[];   // [BW_NS][NREG][KB_BYTES]
+    extern __shared__ __attribute__((aligned(16))) char lds[];   // [BW_NS][NREG x KB_BYTES | 256]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -283,11 +283,8 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
                              reinterpret_cast<const char*>(p.s_k2 + head * p.hs_k2),    // dO   K-style
                              reinterpret_cast<const char*>(p.s_t1 + head * p.hs_t1),    // dO^T V^T-style
                              reinterpret_cast<const char*>(p.s_t2 + head * p.hs_t2)};   // q'^T V^T-style
-    // Read-only for the whole launch and addressed uniformly over the wave: as pointers into the constant address
-    // space their loads go through the scalar unit and its cache instead of the vector memory pipe.
-    typedef const float __attribute__((address_space(4))) * const_f32_ptr;
-    const const_f32_ptr lse_h = (const_f32_ptr)(uintptr_t)(p.lse + int64_t(head) * p.row_stride);
-    const const_f32_ptr delta_h = (const_f32_ptr)(uintptr_t)(p.delta + int64_t(head) * p.row_stride);
+    const float* lse_h = p.lse + int64_t(head) * p.row_stride;
+    const float* delta_h = p.delta + int64_t(head) * p.row_stride;
 
     const int row_lo = g.rs[0], row_hi = g.re[0];                                 // one range of query rows
     const int qb_begin = row_lo / KBLOCK, qb_end = (row_hi + KBLOCK - 1) / KBLOCK;
@@ -297,26 +294,34 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     constexpr int LPW = NREG * FPR / NW;
     static_assert((NREG * FPR) % NW == 0, "fragments must split over the waves");
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    // A stage holds the block's four fragment regions and, behind them, the 32 lse and 32 delta values of its rows
+    // (256 bytes, one dword per lane; every wave loads them, all the same values, so that all waves count the same
+    // number of loads).
+    constexpr int STAGE_BYTES = NREG * KB_BYTES + 256;
+    const float* aux_src = (lane < 32 ? lse_h : delta_h - 32) + lane;
     auto issue = [&](int blk_i, int stage) {
 #pragma unroll
         for (int l = 0; l < LPW; ++l) {
             const int f = wave_u + NW * l, region = f / FPR, fr = f % FPR;
             const char* from = src[region] + int64_t(blk_i) * KB_BYTES + fr * 1024 + lane * 16;
-            char* to = lds + (stage * NREG + region) * KB_BYTES + fr * 1024;
+            char* to = lds + stage * STAGE_BYTES + region * KB_BYTES + fr * 1024;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(from),
                                              (__attribute__((address_space(3))) void*)(to), 16, 0, 0);
         }
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(aux_src + blk_i * KBLOCK),
+                                         (__attribute__((address_space(3))) void*)(lds + stage * STAGE_BYTES + NREG * KB_BYTES), 4, 0, 0);
     };
+    constexpr int LOADS = LPW + 1;                    // per wave and block
 #pragma unroll
     for (int j = 0; j < BW_PF; ++j) issue(min(qb_begin + j, qb_end - 1), j);
 
     for (int it = 0; it < n_blocks; ++it) {
         const int qb = qb_begin + it;
         issue(min(qb + BW_PF, qb_end - 1), (it + BW_PF) & (BW_NS - 1));
-        bw_wait_vmcnt<BW_PF * LPW>();
+        bw_wait_vmcnt<BW_PF * LOADS>();
         bw_barrier();
 
-        const char* blk = lds + (it & (BW_NS - 1)) * NREG * KB_BYTES;
+        const char* blk = lds + (it & (BW_NS - 1)) * STAGE_BYTES;
         const int row0 = qb * KBLOCK;
 
         f32x16 s, dp;
@@ -331,26 +336,27 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
         if (row0 < row_lo || row0 + KBLOCK > row_hi)     // uniform: only the blocks at the ends of the range
             bw_kill_dead_rows(s, dp, row0, row_lo, row_hi, half);
-        // register r stands for query row0 + 16(r/8) + 8 half + r%8.  The block's 32 lse and 32 delta values sit at
-        // wave-uniform addresses (scalar loads); each lane then picks its half's (rows past the clip read the zero
-        // padding of the two vectors; they are dead rows)
+        // register r stands for query row0 + 16(r/8) + 8 half + r%8: its lse and delta come from the stage's last
+        // 256 bytes, 8 consecutive values per (t, half) (rows past the clip read the zero padding of the two vectors;
+        // they are dead rows)
         unsigned pw[2][4], dz[2][4];
+        const float* aux = reinterpret_cast<const float*>(blk + NREG * KB_BYTES);
 #pragma unroll
         for (int t = 0; t < 2; ++t) {
+            const int rb = 16 * t + 8 * half;
+            const f32x4 l0 = *reinterpret_cast<const f32x4*>(aux + rb), l1 = *reinterpret_cast<const f32x4*>(aux + rb + 4);
+            const f32x4 d0 = *reinterpret_cast<const f32x4*>(aux + 32 + rb), d1 = *reinterpret_cast<const f32x4*>(aux + 32 + rb + 4);
+            const float lv[8] = {l0[0], l0[1], l0[2], l0[3], l1[0], l1[1], l1[2], l1[3]};
+            const float dl[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
 #pragma unroll
             for (int e = 0; e < 4; ++e) {
                 float pv[2], zv[2];
 #pragma unroll
                 for (int k = 0; k < 2; ++k) {
                     const int r = 8 * t + 2 * e + k;
-                    const int lo = row0 + 16 * t + 2 * e + k;          // uniform; the other half's row is 8 further
-                    float l0 = lse_h[lo], l1 = lse_h[lo + 8], d0 = delta_h[lo], d1 = delta_h[lo + 8];
-                    asm volatile("" : "+s"(l0), "+s"(l1), "+s"(d0), "+s"(d1));   // values in scalar registers: scalar loads
-                    const float lv = half ? l1 : l0;
-                    const float dl = half ? d1 : d0;
-                    const float pr = __builtin_amdgcn_exp2f(s[r] - lv);
+                    const float pr = __builtin_amdgcn_exp2f(s[r] - lv[2 * e + k]);
                     pv[k] = pr;
-                    zv[k] = pr * (dp[r] - dl);
+                    zv[k] = pr * (dp[r] - dl[2 * e + k]);
                 }
                 pw[t][e] = bw_pack_bf16(pv[0], pv[1]);
                 dz[t][e] = bw_pack_bf16(zv[0], zv[1]);
@@ -482,7 +488,7 @@ hipError_t launch_bwd_dq(const BwdParams& p, hipStream_t s) {
 hipError_t launch_bwd_dkv(const BwdParams& p, hipStream_t s) {
     const int total = p.n_tiles * p.H;
     if (total <= 0) return hipSuccess;
-    const int grid = ((total + 7) / 8) * 8, lds = BW_NS * 4 * KBLOCK * p.D * 2;
+    const int grid = ((total + 7) / 8) * 8, lds = BW_NS * (4 * KBLOCK * p.D * 2 + 256);
     static bool done128 = false, done64 = false;
     if (p.D == 128) {
         hipError_t e = set_lds(reinterpret_cast<const void*>(ll_bwd_dkv_kernel<128, 8>), lds, done128);
