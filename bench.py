@@ -177,7 +177,14 @@ def train_step_stats(w, gen, clip_frames=21, reps=5):
         tb.append(b.elapsed_time(c))
     tf, tb = sorted(tf[1:])[reps // 2], sorted(tb[1:])[reps // 2]
     pairs = ((T + C - 1) // C) * (C * P) * ((S + W + C) * P)          # every chunk sees sink + W frames + itself
+    # pairs whose key belongs to the clip (only those keys receive dK and dV): a clip frame is seen by its own chunk
+    # and by the later chunks that start within W frames after it
+    n_chunks = (T + C - 1) // C
+    clip_pairs = sum((min(n_chunks - 1, (g + W) // C) - g // C + 1) * C * P * P for g in range(T))
     fl = attn_flops(1, 1, D, Hh) * pairs
+    one = fl / 2                                                      # one product over all unmasked pairs
+    fl_bwd = 3 * one + 2 * one * clip_pairs / pairs                   # scores' dP, dQ over all pairs; dK, dV over the clip's keys
+    fl_bwd_run = 3 * one + 4 * one * clip_pairs / pairs               # what the two kernels execute (scores and dP in both)
     res = {"what": "attention of a supervised clip over sink + detached window + itself and its gradients (bf16; one "
                    "layer); not part of `value`",
            "workload": f"{w.name}-shaped clip: {T} frames in chunks of {C}, sink {S}, window {W}: {T * P} queries, "
@@ -185,10 +192,14 @@ def train_step_stats(w, gen, clip_frames=21, reps=5):
            "workspace_bytes": int(clip.buffer.numel()),
            "forward_ms": round(tf, 3), "forward_TFLOP/s": round(fl / (tf * 1e-3) / 1e12, 1),
            "backward_ms": round(tb, 3),
-           "backward_TFLOP/s": round(2.5 * fl / (tb * 1e-3) / 1e12, 1),
-           "backward_pct_of_bf16_mfma_peak": round(100 * 2.5 * fl / (tb * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
-           "flops": "forward 4 Nq Nk D H over unmasked pairs; backward 2.5 x that (five products; the kernels run "
-                    "seven, scores and dP in both)"}
+           "backward_TFLOP/s": round(fl_bwd / (tb * 1e-3) / 1e12, 1),
+           "backward_pct_of_bf16_mfma_peak": round(100 * fl_bwd / (tb * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+           "backward_executed_TFLOP/s": round(fl_bwd_run / (tb * 1e-3) / 1e12, 1),
+           "flops": "forward: 2 products (4 Nq Nk D H) over the unmasked pairs; backward: dP, dQ and the scores again "
+                    "over all pairs, dK and dV over the pairs whose key is a clip frame (context and sink keys get no "
+                    f"gradient: {clip_pairs / pairs:.3f} of the pairs); executed: scores and dP in both kernels",
+           "forward_TFLOP": round(fl / 1e12, 3), "backward_TFLOP": round(fl_bwd / 1e12, 3),
+           "backward_executed_TFLOP": round(fl_bwd_run / 1e12, 3)}
     clip.close()
     return res
 
