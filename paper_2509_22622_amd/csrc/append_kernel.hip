@@ -16,6 +16,8 @@
 // an axis turns by position * theta^(-2i/d_axis); frame positions are absolute.
 #include "kernels.h"
 
+#include <algorithm>
+
 namespace ll {
 
 typedef unsigned short u16x8 __attribute__((ext_vector_type(8)));
@@ -127,6 +129,18 @@ hipError_t launch_append(const AppendParams& p, hipStream_t s) {
 
 // Copy one frame's K (already rotated) and V out of the cache layout into [P, H, D].
 __global__ __launch_bounds__(256) void ll_read_frame_kernel(const ReadFrameParams p) {
+    if (p.v_out == nullptr) {                   // keys only: 8 features of a row are 16 contiguous bytes on both sides
+        const int64_t units = int64_t(p.P) * p.H * (p.D / 8);
+        for (int64_t u = blockIdx.x * 256LL + threadIdx.x; u < units; u += int64_t(gridDim.x) * 256) {
+            const int c = int(u % (p.D / 8));
+            const int head = int((u / (p.D / 8)) % p.H);
+            const int64_t slot = p.slot + u / (int64_t(p.D / 8) * p.H);
+            const int64_t base = head * p.head_stride + (slot / KBLOCK) * (KBLOCK * p.D);
+            *reinterpret_cast<u16x8*>(p.k_out + u * 8) =
+                *reinterpret_cast<const u16x8*>(p.k_cache + base + k_elem_offset(int(slot % KBLOCK), c * 8));
+        }
+        return;
+    }
     const int64_t n = int64_t(p.P) * p.H * p.D;
     for (int64_t i = blockIdx.x * 256LL + threadIdx.x; i < n; i += int64_t(gridDim.x) * 256) {
         const int d = int(i % p.D);
@@ -141,7 +155,9 @@ __global__ __launch_bounds__(256) void ll_read_frame_kernel(const ReadFrameParam
 }
 
 hipError_t launch_read_frame(const ReadFrameParams& p, hipStream_t s) {
-    hipLaunchKernelGGL(ll_read_frame_kernel, dim3(512), dim3(256), 0, s, p);
+    const int64_t units = int64_t(p.P) * p.H * (p.D / 8);
+    const unsigned grid = unsigned(std::min<int64_t>(std::max<int64_t>((units + 255) / 256, 512), 8192));
+    hipLaunchKernelGGL(ll_read_frame_kernel, dim3(grid), dim3(256), 0, s, p);
     return hipGetLastError();
 }
 

@@ -321,3 +321,24 @@ def test_prefill_beyond_one_launch():
     chunks than one attention launch takes (16), so the library cuts both; streaming goes on afterwards."""
     _prefill_case(MANY, True, 50, 41, pre_chunks=4, follow=3)
     _prefill_case(MANY, False, 7, 20, pre_chunks=3, follow=2)           # 20 chunks: two attention launches
+
+
+def test_read_frame_one_tensor_at_a_time():
+    """ll_cache_read_frame with only k_out or only v_out (either may be NULL) returns the same bits as with both."""
+    w = ODD128
+    cache = H.make_cache(w)
+    q, k, v = synth.chunk_qkv(w, 0, 0)
+    qd = H.to_dev(q)
+    cache.chunk_append(0, 0, w.chunk_frames, qd, H.to_dev(k), H.to_dev(v), torch.empty_like(qd))
+    shape = (w.tokens_per_frame, w.heads, w.head_dim)
+    both_k, both_v, only_k, only_v = (torch.zeros(shape, dtype=torch.bfloat16, device="cuda") for _ in range(4))
+    for frame in range(w.chunk_frames):
+        cache.read_frame(0, frame, both_k, both_v)
+        cache.read_frame(0, frame, only_k, None)
+        cache.read_frame(0, frame, None, only_v)
+        torch.cuda.synchronize()
+        assert torch.equal(both_k.view(torch.int16), only_k.view(torch.int16)), frame
+        assert torch.equal(both_v.view(torch.int16), only_v.view(torch.int16)), frame
+        P = w.tokens_per_frame
+        assert np.array_equal(H.to_bits(only_v), v[frame * P:(frame + 1) * P])      # V is stored bit-exact
+    cache.close()
