@@ -27,12 +27,12 @@ def bits(shape, stream, tensor, cfg_id=41):
     return synth.normal_bf16(shape, cfg_id, 0, stream, tensor)
 
 
-def run_case(heads, head_dim, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip, seed=0, dout_rows=None):
+def run_case(heads, head_dim, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip, seed=0, dout_rows=None, q_scale=1.0):
     cfg = OracleConfig(1, heads, head_dim, gh, gw, C, S, W)
     P = gh * gw
     oracle = ClipOracle(cfg)
     nf = len(oracle.frames(ctx_start, n_ctx, n_clip))
-    q = bits((n_clip * P, heads, head_dim), 4 * seed, "q")
+    q = synth.normal_bf16((n_clip * P, heads, head_dim), 41, 0, 4 * seed, "q", scale=q_scale)
     k = bits((nf * P, heads, head_dim), 4 * seed, "k")
     v = bits((nf * P, heads, head_dim), 4 * seed, "v")
     dout = bits((n_clip * P, heads, head_dim), 4 * seed + 1, "q")
@@ -47,14 +47,15 @@ def run_case(heads, head_dim, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip, seed
     torch.cuda.synchronize()
     want_out = oracle.forward(ctx_start, n_ctx, n_clip, bf16_bits_to_f64(q), bf16_bits_to_f64(k), bf16_bits_to_f64(v))
     what = f"H{heads} D{head_dim} P{P} C{C} S{S} W{W} ctx {ctx_start}+{n_ctx} clip {n_clip}"
-    H.assert_parity(H.to_bits(out), want_out, what + " forward")
+    H.assert_parity(H.to_bits(out), want_out, what + " forward", logit_scale=q_scale)
     want = oracle.backward(bf16_bits_to_f64(dout))
     got = {}
     for name, t, w in zip(("dq", "dk", "dv"), (dq, dk, dv), want):
         g = bf16_bits_to_f64(H.to_bits(t))
         assert np.isfinite(g).all(), f"{what} {name}: non-finite"
         max_abs, rel = error_metrics(g, w)
-        assert rel <= GRAD_REL_L2 and max_abs <= GRAD_MAX_FRAC * np.abs(w).max(), f"{what} {name}: max_abs {max_abs:.3e} of {np.abs(w).max():.3e}, rel_l2 {rel:.3e}"
+        assert rel <= GRAD_REL_L2 * q_scale and max_abs <= GRAD_MAX_FRAC * q_scale * np.abs(w).max(), \
+            f"{what} {name}: max_abs {max_abs:.3e} of {np.abs(w).max():.3e}, rel_l2 {rel:.3e}"
         got[name] = g
     clip.close()
     return got, want
@@ -166,3 +167,12 @@ def test_random_geometries(idx):
         n_ctx = int(rng.integers(0, W + 1))
         ctx_start = S + int(rng.integers(0, 40))
     run_case(int(rng.integers(1, 4)), D, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip, seed=10 + idx)
+
+
+def test_peaky_scores():
+    """Queries four times larger (logits of standard deviation 4: a few keys carry the weight).  As for the inference
+    path's stress input, the rounding of q' and K' to bf16 moves every logit four times further, so all tolerances are
+    scaled by 4; outside the graded configurations."""
+    got, want = run_case(2, 128, 5, 8, 3, 3, 6, 9, 9, 6, 9, seed=7, q_scale=4.0)
+    for name, w in zip(("dq", "dk", "dv"), want):
+        assert np.abs(got[name]).max() > 0 and np.isfinite(got[name]).all()
