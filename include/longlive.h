@@ -194,7 +194,8 @@ ll_status ll_prompt_recache(ll_prompt* prompt, int layer, const void* k, const v
 /* Tokens of layer `layer`'s current prompt (0 before the first ll_prompt_recache). */
 ll_status ll_prompt_tokens(const ll_prompt* prompt, int layer, int* n_tokens);
 /* Cross-attention of n_q query rows over layer `layer`'s prompt.  q: device, bf16 [n_q, H, D], as the model's query
- * projection made them (the kernel multiplies by log2(e)/sqrt(D) itself and rounds the product to bf16 once);
+ * projection made them (the factor log2(e)/sqrt(D) is applied inside the kernel: to the queries, with one rounding of
+ * the product to bf16, or to the fp32 scores, depending on the kernel the launch's size selects);
  * out: device, bf16 [n_q, H, D]; out may be q itself (a wave reads exactly the rows it writes), any other overlap is
  * an error the library cannot detect.  1 <= n_q <= 2^24.  LL_ERR_STATE if the layer has no prompt yet. */
 ll_status ll_cross_attn(const ll_prompt* prompt, int layer, const void* q, int n_q, void* out, void* stream);
