@@ -228,7 +228,8 @@ ll_status ll_clip_destroy(ll_clip* clip);
  *   q: device bf16 [n_clip * P, H, D], the clip's queries.
  *   k, v: device bf16 [n_frames * P, H, D] for all resident frames in ascending order: the sink frames (unless they
  *         belong to the clip), the context, the clip; all before the rotary embedding.
- *   out: device bf16 [n_clip * P, H, D].  q, k, v, out must stay unchanged until ll_clip_backward has run. */
+ *   out: device bf16 [n_clip * P, H, D].  q, k and v are read by the forward pass only (what the backward pass needs
+ *   of them is kept in the handle's buffer); out is passed to ll_clip_backward again and must be unchanged by then. */
 ll_status ll_clip_forward(ll_clip* clip, int64_t ctx_start, int n_ctx, int n_clip, const void* q, const void* k,
                           const void* v, void* out, void* stream);
 /* Backward of the handle's last forward.  out: what ll_clip_forward wrote; dout: device bf16 [n_clip * P, H, D];
