@@ -232,6 +232,12 @@ ll_status ll_clip_destroy(ll_clip* clip);
  *   of them is kept in the handle's buffer); out is passed to ll_clip_backward again and must be unchanged by then. */
 ll_status ll_clip_forward(ll_clip* clip, int64_t ctx_start, int n_ctx, int n_clip, const void* q, const void* k,
                           const void* v, void* out, void* stream);
+/* Introspection (works on index-only handles): the key set of chunk `chunk` (0-based, in clip order) of the handle's
+ * last forward as at most 2 half-open token-slot ranges into the list of resident frames (sink frames outside the
+ * clip, context, clip; P slots per frame), ascending and disjoint.  ranges: host int64[2*cap]; *n = count.
+ * LL_ERR_STATE without a forward pass. */
+ll_status ll_clip_chunk_key_ranges(const ll_clip* clip, int chunk, int64_t* ranges, int cap, int* n);
+
 /* Backward of the handle's last forward.  out: what ll_clip_forward wrote; dout: device bf16 [n_clip * P, H, D];
  * dq, dk, dv: device bf16 [n_clip * P, H, D], gradients for the clip's own frames (context and sink frames outside
  * the clip are constants).  LL_ERR_STATE without a forward pass. */

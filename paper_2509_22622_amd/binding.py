@@ -45,6 +45,7 @@ SIGNATURES = {
     "ll_clip_destroy": (_i, [_vp]),
     "ll_clip_forward": (_i, [_vp, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp]),
     "ll_clip_backward": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "ll_clip_chunk_key_ranges": (_i, [_vp, _i, C.POINTER(_i64), _i, C.POINTER(_i)]),
     "ll_set_attn_variant": (_i, [_i]),
     "ll_attn_variant_name": (C.c_char_p, [_i]),
     "ll_probe_mfma_rate": (_i, [C.c_void_p, C.c_size_t, _i, _i, _i, C.POINTER(C.c_double), C.POINTER(C.c_double), C.c_void_p]),
@@ -310,6 +311,12 @@ class Clip:
     def forward(self, ctx_start, n_ctx, n_clip, q=None, k=None, v=None, out=None):
         stream = _stream() if self.buffer is not None else None
         _check(lib().ll_clip_forward(self._h, ctx_start, n_ctx, n_clip, _ptr(q), _ptr(k), _ptr(v), _ptr(out), stream))
+
+    def chunk_key_ranges(self, chunk):
+        """Key set of one chunk of the last forward: [(begin, end)] token-slot ranges into the resident frames."""
+        buf, n = (C.c_int64 * 4)(), C.c_int()
+        _check(lib().ll_clip_chunk_key_ranges(self._h, chunk, buf, 2, C.byref(n)))
+        return [(buf[2 * i], buf[2 * i + 1]) for i in range(n.value)]
 
     def backward(self, out=None, dout=None, dq=None, dk=None, dv=None):
         stream = _stream() if self.buffer is not None else None

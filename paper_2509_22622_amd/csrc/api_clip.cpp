@@ -281,6 +281,22 @@ ll_status ll_clip_forward(ll_clip* clip, int64_t ctx_start, int n_ctx, int n_cli
     return LL_OK;
 }
 
+ll_status ll_clip_chunk_key_ranges(const ll_clip* clip, int chunk, int64_t* ranges, int cap, int* n) {
+    if (!clip) return fail(LL_ERR_INVALID_ARG, "clip is null");
+    if (!n) return fail(LL_ERR_INVALID_ARG, "n is null");
+    if (!clip->have_fwd) return fail(LL_ERR_STATE, "no forward pass");
+    const int n_chunks = (clip->n_clip + clip->C - 1) / clip->C;
+    if (chunk < 0 || chunk >= n_chunks) return fail(LL_ERR_INVALID_ARG, "chunk %d out of range [0, %d)", chunk, n_chunks);
+    const int64_t clip_start = clip->ctx_start + clip->n_ctx;
+    const int64_t f0 = clip_start + int64_t(chunk) * clip->C;
+    const int len = int(std::min<int64_t>(clip->C, clip_start + clip->n_clip - f0));
+    const std::vector<SlotRange> r = clip_key_ranges(clip, f0, len);
+    *n = int(r.size());
+    if (int(r.size()) > cap || (!ranges && !r.empty())) return fail(LL_ERR_BUFFER_TOO_SMALL, "%zu ranges, capacity %d", r.size(), cap);
+    for (size_t i = 0; i < r.size(); ++i) { ranges[2 * i] = r[i].begin; ranges[2 * i + 1] = r[i].end; }
+    return LL_OK;
+}
+
 ll_status ll_clip_backward(ll_clip* clip, const void* out, const void* dout, void* dq, void* dk, void* dv, void* stream) {
     if (!clip) return fail(LL_ERR_INVALID_ARG, "clip is null");
     ll_clip* c = clip;

@@ -9,6 +9,8 @@ import subprocess
 
 import ctypes as C
 import os
+
+import numpy as np
 import pytest
 
 from oracle.longlive_oracle import OracleConfig, key_frames
@@ -297,3 +299,42 @@ def test_clip_handle_bookkeeping_and_errors():
     c.forward(3, 0, 4)                                                            # right after the sink, no context
     c.backward()
     c.close()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_clip_key_sets_match_oracle(seed):
+    """The train-time handle's key ranges (host logic, index-only) against the oracle's key-set rule over the list
+    of resident frames, for random geometries, first clips and later ones."""
+    from oracle.clip_backward import ClipOracle
+    from oracle.longlive_oracle import OracleConfig, key_frames
+    rng = np.random.Generator(np.random.Philox(key=700 + seed))
+    for trial in range(30):
+        gh, gw = int(rng.integers(1, 4)), int(rng.integers(1, 5))
+        Cc, S, W, T = int(rng.integers(1, 5)), int(rng.integers(0, 5)), int(rng.integers(0, 9)), int(rng.integers(1, 12))
+        n_clip = int(rng.integers(1, T + 1))
+        if trial % 3 == 0:
+            ctx_start, n_ctx = 0, 0
+        else:
+            n_ctx, ctx_start = int(rng.integers(0, W + 1)), S + int(rng.integers(0, 30))
+        cfg = OracleConfig(1, 1, 64, gh, gw, Cc, S, W)
+        P = gh * gw
+        o = ClipOracle(cfg)
+        frames = o.frames(ctx_start, n_ctx, n_clip)
+        pos = {f: i for i, f in enumerate(frames)}
+        clip = B.Clip(1, 64, gh, gw, Cc, S, W, T, device=None)
+        clip.forward(ctx_start, n_ctx, n_clip)
+        clip_start = ctx_start + n_ctx
+        for ci, (f0, n) in enumerate(o.clip_chunks(clip_start, n_clip)):
+            want = set()
+            for f in key_frames(cfg, f0, n, [g for g in frames if g < f0 + n]):
+                want |= set(range(pos[f] * P, (pos[f] + 1) * P))
+            ranges = clip.chunk_key_ranges(ci)
+            assert 1 <= len(ranges) <= 2 and all(a < b for a, b in ranges)
+            assert all(ranges[i][1] < ranges[i + 1][0] for i in range(len(ranges) - 1))      # disjoint, not touching
+            got = set()
+            for a, b in ranges:
+                got |= set(range(a, b))
+            assert got == want, (gh, gw, Cc, S, W, T, ctx_start, n_ctx, n_clip, ci)
+        with pytest.raises(B.LongLiveError):
+            clip.chunk_key_ranges(len(o.clip_chunks(clip_start, n_clip)))
+        clip.close()
