@@ -176,3 +176,11 @@ def test_peaky_scores():
     got, want = run_case(2, 128, 5, 8, 3, 3, 6, 9, 9, 6, 9, seed=7, q_scale=4.0)
     for name, w in zip(("dq", "dk", "dv"), want):
         assert np.abs(got[name]).max() > 0 and np.isfinite(got[name]).all()
+
+
+def test_more_frames_chunks_and_groups_than_one_launch_takes():
+    """47 resident frames (the cache-write kernel takes 32 per launch), 40 chunks of one frame (the attention kernel
+    takes 16 query chunks per launch, the backward kernels 32 column groups): every batching loop runs more than
+    once."""
+    run_case(2, 64, 2, 3, 1, 2, 5, 40, 9, 5, 40, seed=9)
+    run_case(1, 128, 2, 3, 2, 0, 3, 70, 0, 0, 70, seed=10)       # a first clip without a sink: 35 chunks, 70 frames
