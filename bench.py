@@ -170,7 +170,7 @@ def train_step_stats(w, gen, clip_frames=21, reps=5):
         a.record()
         clip.forward(60, W, T, q, k, v, out)
         b.record()
-        clip.backward(out, dout, dq, dk, dv)
+        clip.backward(dout, dq, dk, dv)
         c.record()
         torch.cuda.synchronize()
         tf.append(a.elapsed_time(b))

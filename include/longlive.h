@@ -228,8 +228,9 @@ ll_status ll_clip_destroy(ll_clip* clip);
  *   q: device bf16 [n_clip * P, H, D], the clip's queries.
  *   k, v: device bf16 [n_frames * P, H, D] for all resident frames in ascending order: the sink frames (unless they
  *         belong to the clip), the context, the clip; all before the rotary embedding.
- *   out: device bf16 [n_clip * P, H, D].  q, k and v are read by the forward pass only (what the backward pass needs
- *   of them is kept in the handle's buffer); out is passed to ll_clip_backward again and must be unchanged by then. */
+ *   out: device bf16 [n_clip * P, H, D].  All four tensors are used by the forward pass only: what the backward pass
+ *   needs of them (rotated operands, row sums, and the output before its rounding to bf16, from which it takes
+ *   delta_i = dO_i . O_i) is kept in the handle's buffer. */
 ll_status ll_clip_forward(ll_clip* clip, int64_t ctx_start, int n_ctx, int n_clip, const void* q, const void* k,
                           const void* v, void* out, void* stream);
 /* Introspection (works on index-only handles): the key set of chunk `chunk` (0-based, in clip order) of the handle's
@@ -238,11 +239,10 @@ ll_status ll_clip_forward(ll_clip* clip, int64_t ctx_start, int n_ctx, int n_cli
  * LL_ERR_STATE without a forward pass. */
 ll_status ll_clip_chunk_key_ranges(const ll_clip* clip, int chunk, int64_t* ranges, int cap, int* n);
 
-/* Backward of the handle's last forward.  out: what ll_clip_forward wrote; dout: device bf16 [n_clip * P, H, D];
- * dq, dk, dv: device bf16 [n_clip * P, H, D], gradients for the clip's own frames (context and sink frames outside
- * the clip are constants).  LL_ERR_STATE without a forward pass. */
-ll_status ll_clip_backward(ll_clip* clip, const void* out, const void* dout, void* dq, void* dk, void* dv,
-                           void* stream);
+/* Backward of the handle's last forward.  dout: device bf16 [n_clip * P, H, D]; dq, dk, dv: device bf16
+ * [n_clip * P, H, D], gradients for the clip's own frames (context and sink frames outside the clip are constants).
+ * LL_ERR_STATE without a forward pass. */
+ll_status ll_clip_backward(ll_clip* clip, const void* dout, void* dq, void* dk, void* dv, void* stream);
 
 /* Attention kernel variant: 0 = default for the shape, otherwise a variant id listed by
  * ll_attn_variant_name.  Process-wide tuning knob for benchmarking. */

@@ -44,7 +44,7 @@ SIGNATURES = {
     "ll_clip_create": (_i, [_i] * 9 + [C.c_float, _vp, _sz, C.POINTER(_vp)]),
     "ll_clip_destroy": (_i, [_vp]),
     "ll_clip_forward": (_i, [_vp, _i64, _i, _i, _vp, _vp, _vp, _vp, _vp]),
-    "ll_clip_backward": (_i, [_vp, _vp, _vp, _vp, _vp, _vp, _vp]),
+    "ll_clip_backward": (_i, [_vp, _vp, _vp, _vp, _vp, _vp]),
     "ll_clip_chunk_key_ranges": (_i, [_vp, _i, C.POINTER(_i64), _i, C.POINTER(_i)]),
     "ll_set_attn_variant": (_i, [_i]),
     "ll_attn_variant_name": (C.c_char_p, [_i]),
@@ -318,6 +318,6 @@ class Clip:
         _check(lib().ll_clip_chunk_key_ranges(self._h, chunk, buf, 2, C.byref(n)))
         return [(buf[2 * i], buf[2 * i + 1]) for i in range(n.value)]
 
-    def backward(self, out=None, dout=None, dq=None, dk=None, dv=None):
+    def backward(self, dout=None, dq=None, dk=None, dv=None):
         stream = _stream() if self.buffer is not None else None
-        _check(lib().ll_clip_backward(self._h, _ptr(out), _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), stream))
+        _check(lib().ll_clip_backward(self._h, _ptr(dout), _ptr(dq), _ptr(dk), _ptr(dv), stream))

@@ -14,7 +14,7 @@ struct ll_clip {
     int64_t hs_all, hs_clip;            // elements between heads of a fragment region pair
     int64_t row_stride;                 // floats between heads of lse and delta
     // byte offsets into the workspace
-    size_t o_a, o_b, o_cq, o_cd, o_qrot, o_krot, o_lse, o_delta, o_gq, o_gk, o_zero, o_freq, o_row, o_col;
+    size_t o_a, o_b, o_cq, o_cd, o_qrot, o_krot, o_lse, o_delta, o_gq, o_gk, o_o32, o_zero, o_freq, o_row, o_col;
     RopeTables rope;
     // what the last forward left
     bool have_fwd;
@@ -25,7 +25,7 @@ struct ll_clip {
 namespace {
 struct ClipSizes {
     int64_t kb_all, kb_clip, hs_all, hs_clip, row_stride;
-    size_t o_a, o_b, o_cq, o_cd, o_qrot, o_krot, o_lse, o_delta, o_gq, o_gk, o_zero, o_freq, o_row, o_col, total;
+    size_t o_a, o_b, o_cq, o_cd, o_qrot, o_krot, o_lse, o_delta, o_gq, o_gk, o_o32, o_zero, o_freq, o_row, o_col, total;
 };
 bool clip_shapes_ok(int H, int D, int P, int S, int W, int T, int C) {
     return H >= 1 && H <= 4096 && (D == 64 || D == 128) && P >= 1 && S >= 0 && W >= 0 && T >= 1 && C >= 1 &&
@@ -52,6 +52,7 @@ ClipSizes clip_sizes(int H, int D, int P, int S, int W, int T, int C, int grid_h
     z.o_delta = take(size_t(z.row_stride) * H * 4);
     z.o_gq = take(size_t(n_clip) * H * D * 4);
     z.o_gk = take(size_t(n_clip) * H * D * 4);
+    z.o_o32 = take(size_t(n_clip) * H * D * 4);
     const int d_hw = 2 * (D / 6), n_t = (D - 2 * d_hw) / 2, n_h = d_hw / 2;
     z.o_zero = take(size_t(D / 2) * sizeof(double));
     z.o_freq = take(size_t(n_t) * sizeof(double));
@@ -91,7 +92,7 @@ ll_status ll_clip_create(int heads, int head_dim, int tokens_per_frame, int sink
     c->dev = static_cast<char*>(dev_buffer);
     c->kb_all = z.kb_all; c->kb_clip = z.kb_clip; c->hs_all = z.hs_all; c->hs_clip = z.hs_clip; c->row_stride = z.row_stride;
     c->o_a = z.o_a; c->o_b = z.o_b; c->o_cq = z.o_cq; c->o_cd = z.o_cd; c->o_qrot = z.o_qrot; c->o_krot = z.o_krot;
-    c->o_lse = z.o_lse; c->o_delta = z.o_delta; c->o_gq = z.o_gq; c->o_gk = z.o_gk;
+    c->o_lse = z.o_lse; c->o_delta = z.o_delta; c->o_gq = z.o_gq; c->o_gk = z.o_gk; c->o_o32 = z.o_o32;
     c->o_zero = z.o_zero; c->o_freq = z.o_freq; c->o_row = z.o_row; c->o_col = z.o_col;
     const int d_hw = 2 * (head_dim / 6), n_t = (head_dim - 2 * d_hw) / 2, n_h = d_hw / 2;
     c->rope = RopeTables{nullptr, nullptr, nullptr, n_t, n_h, n_h};
@@ -260,6 +261,7 @@ ll_status ll_clip_forward(ll_clip* clip, int64_t ctx_start, int n_ctx, int n_cli
         p.H = c->H; p.D = c->D; p.kblock = KBLOCK;
         p.scale_log2e = 1.0f;
         p.lse = clip_f32(c, c->o_lse); p.lse_stride = c->row_stride;
+        p.out32 = clip_f32(c, c->o_o32);
         const int m = std::min(MAX_ATTN_CHUNKS, n_chunks - base);
         int tiles = 0;
         for (int i = 0; i < m; ++i) {
@@ -297,14 +299,14 @@ ll_status ll_clip_chunk_key_ranges(const ll_clip* clip, int chunk, int64_t* rang
     return LL_OK;
 }
 
-ll_status ll_clip_backward(ll_clip* clip, const void* out, const void* dout, void* dq, void* dk, void* dv, void* stream) {
+ll_status ll_clip_backward(ll_clip* clip, const void* dout, void* dq, void* dk, void* dv, void* stream) {
     if (!clip) return fail(LL_ERR_INVALID_ARG, "clip is null");
     ll_clip* c = clip;
     if (!c->have_fwd) return fail(LL_ERR_STATE, "no forward pass to differentiate");
-    const bool any_null = !out || !dout || !dq || !dk || !dv;
+    const bool any_null = !dout || !dq || !dk || !dv;
     if (c->dev && any_null) return fail(LL_ERR_INVALID_ARG, "null tensor");
-    if (!c->dev && !(!out && !dout && !dq && !dk && !dv)) return fail(LL_ERR_INVALID_ARG, "index-only handle takes null tensors");
-    if (!aligned16(out, dout, dq, dk) || !aligned16(dv)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+    if (!c->dev && !(!dout && !dq && !dk && !dv)) return fail(LL_ERR_INVALID_ARG, "index-only handle takes null tensors");
+    if (!aligned16(dout, dq, dk, dv)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
     if (!c->dev) return LL_OK;
     hipStream_t s = static_cast<hipStream_t>(stream);
     const int n_clip = c->n_clip;
@@ -313,8 +315,9 @@ ll_status ll_clip_backward(ll_clip* clip, const void* out, const void* dout, voi
     const int64_t col_slot0 = int64_t(c->n_frames - n_clip) * c->P;
     const uint16_t* qrot = clip_u16(c, c->o_qrot);
     const uint16_t* dO = static_cast<const uint16_t*>(dout);
-    // 1. delta_i = dO_i . O_i, and the clip's q' and dO as fragment regions (each both ways round)
-    hipError_t e = launch_bwd_delta(static_cast<const uint16_t*>(out), dO, clip_f32(c, c->o_delta), int(rows), c->H, c->D, c->row_stride, s);
+    // 1. delta_i = dO_i . O_i (O as the forward kept it, not rounded to bf16), and the clip's q' and dO as fragment
+    //    regions (each both ways round)
+    hipError_t e = launch_bwd_delta(clip_f32(c, c->o_o32), dO, clip_f32(c, c->o_delta), int(rows), c->H, c->D, c->row_stride, s);
     if (e == hipSuccess) e = clip_write_pair(c, qrot, dO, rows, clip_u16(c, c->o_cq), c->kb_clip, c->hs_clip, s);   // q' K-style, dO^T
     if (e == hipSuccess) e = clip_write_pair(c, dO, qrot, rows, clip_u16(c, c->o_cd), c->kb_clip, c->hs_clip, s);   // dO K-style, q'^T
     if (e != hipSuccess) return hip_fail(e, "clip backward preparation kernels launch");

@@ -395,9 +395,10 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
 }
 
 // ---------------------------------------------------------------------------------------------------------------
-// delta[head][row] = sum_d dO[row][head][d] * O[row][head][d]; D / 8 lanes per (row, head), 8 features each.
+// delta[head][row] = sum_d dO[row][head][d] * O[row][head][d], O being the forward's output before its rounding to
+// bf16; D / 8 lanes per (row, head), 8 features each.
 template <int D>
-__global__ __launch_bounds__(256) void ll_bwd_delta_kernel(const uint16_t* out, const uint16_t* dout, float* delta,
+__global__ __launch_bounds__(256) void ll_bwd_delta_kernel(const float* out, const uint16_t* dout, float* delta,
                                                            int rows, int H, int64_t row_stride) {
     constexpr int LPR = D / 8;                        // lanes per (row, head)
     const int64_t idx = (int64_t(blockIdx.x) * 256 + threadIdx.x) / LPR;   // (row, head) pair
@@ -405,10 +406,11 @@ __global__ __launch_bounds__(256) void ll_bwd_delta_kernel(const uint16_t* out, 
     const bool on = idx < int64_t(rows) * H;
     float acc = 0.f;
     if (on) {
-        const bf16x8 a = *reinterpret_cast<const bf16x8*>(out + idx * D + part * 8);
+        const f32x4 a0 = *reinterpret_cast<const f32x4*>(out + idx * D + part * 8);
+        const f32x4 a1 = *reinterpret_cast<const f32x4*>(out + idx * D + part * 8 + 4);
         const bf16x8 b = *reinterpret_cast<const bf16x8*>(dout + idx * D + part * 8);
 #pragma unroll
-        for (int e = 0; e < 8; ++e) acc += float(a[e]) * float(b[e]);
+        for (int e = 0; e < 4; ++e) acc += a0[e] * float(b[e]) + a1[e] * float(b[e + 4]);
     }
 #pragma unroll
     for (int m = LPR / 2; m >= 1; m >>= 1) acc += __shfl_xor(acc, m);
@@ -502,7 +504,7 @@ hipError_t launch_bwd_dkv(const BwdParams& p, hipStream_t s) {
     return hipGetLastError();
 }
 
-hipError_t launch_bwd_delta(const uint16_t* out, const uint16_t* dout, float* delta, int rows, int H, int D,
+hipError_t launch_bwd_delta(const float* out, const uint16_t* dout, float* delta, int rows, int H, int D,
                             int64_t row_stride, hipStream_t s) {
     if (rows <= 0) return hipSuccess;
     const int64_t threads = int64_t(rows) * H * (D / 8);

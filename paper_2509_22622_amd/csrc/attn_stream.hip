@@ -558,6 +558,21 @@ __global__ __launch_bounds__(SP_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2
         // v_log_f32 is the base-2 logarithm; callers that want no row sums leave the pointer null
         if (p.lse != nullptr && lane < 32 && q0 + lane < ch.q_end)
             p.lse[int64_t(head) * p.lse_stride + q0 + lane] = st.m + __builtin_amdgcn_logf(l);
+        // and the output once more, not rounded to bf16: the backward pass takes delta = dO . O from it (with the
+        // rounded output the error of delta, about 2^-9 |dO||O|, is what is left of dP - delta when one key holds
+        // nearly all of a row's weight)
+        if (p.out32 != nullptr && q0 + (lane & 31) < ch.q_end) {
+            const float inv = 1.0f / l;
+            float* dst = p.out32 + (int64_t(q0 + (lane & 31)) * p.H + head) * D + (lane >> 5) * 4;
+#pragma unroll
+            for (int db = 0; db < D / 32; ++db)
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    typedef float f32x4 __attribute__((ext_vector_type(4)));
+                    const f32x4 w = {st.o[db][4 * g] * inv, st.o[db][4 * g + 1] * inv, st.o[db][4 * g + 2] * inv, st.o[db][4 * g + 3] * inv};
+                    *reinterpret_cast<f32x4*>(dst + db * 32 + g * 8) = w;
+                }
+        }
     }
 }
 

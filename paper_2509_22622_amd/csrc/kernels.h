@@ -112,6 +112,7 @@ struct AttnParams {
     int n_t;
     float* lse;                  // *_lse kernels: log2 of each row's sum of 2^score, [H][lse_stride] (null otherwise)
     int64_t lse_stride;
+    float* out32;                // *_lse kernels: the output once more in fp32, [rows, H, D] (null: not wanted)
     uint16_t xcd_first[9];
     uint16_t xcd_group[MAX_XCD_GROUPS];
     AttnChunk chunk[MAX_ATTN_CHUNKS];
@@ -159,7 +160,7 @@ struct BwdFinishParams {
 int bwd_tile_cols(int D);     // columns per workgroup of the two kernels below
 hipError_t launch_bwd_dq(const BwdParams& p, hipStream_t s);
 hipError_t launch_bwd_dkv(const BwdParams& p, hipStream_t s);
-hipError_t launch_bwd_delta(const uint16_t* out, const uint16_t* dout, float* delta, int rows, int H, int D,
+hipError_t launch_bwd_delta(const float* out32, const uint16_t* dout, float* delta, int rows, int H, int D,
                             int64_t row_stride, hipStream_t s);
 hipError_t launch_bwd_finish(const BwdFinishParams& p, hipStream_t s);
 

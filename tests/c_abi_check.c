@@ -36,9 +36,9 @@ int main(void) {
         ll_clip* cl = NULL;
         if (ll_clip_bytes(2, 64, 60, 3, 6, 9, 3) == 0 || ll_clip_bytes(2, 96, 60, 3, 6, 9, 3) != 0) return 20;
         if (ll_clip_create(2, 64, 60, 3, 6, 9, 3, 6, 10, 10000.0f, NULL, 0, &cl) != LL_OK) return 21;
-        if (ll_clip_backward(cl, NULL, NULL, NULL, NULL, NULL, NULL) != LL_ERR_STATE) return 22;
+        if (ll_clip_backward(cl, NULL, NULL, NULL, NULL, NULL) != LL_ERR_STATE) return 22;
         if (ll_clip_forward(cl, 9, 6, 9, NULL, NULL, NULL, NULL, NULL) != LL_OK) return 23;
-        if (ll_clip_backward(cl, NULL, NULL, NULL, NULL, NULL, NULL) != LL_OK) return 24;
+        if (ll_clip_backward(cl, NULL, NULL, NULL, NULL, NULL) != LL_OK) return 24;
         if (ll_clip_destroy(cl) != LL_OK) return 25;
     }
     printf("c abi ok\n");

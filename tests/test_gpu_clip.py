@@ -3,8 +3,10 @@
 Tolerances.  Forward: those of the inference path (max-abs 1e-2, relative L2 5e-3).  Gradients: the backward kernels
 rebuild the softmax weights P from bf16 operands, round P and dZ = P (dP - delta) to bf16 for the second products and
 the results to bf16 again; each rounding is 2^-9 relative and they add up over three stages in which errors of
-different keys average out (measured: 3.1e-3 to 3.8e-3).  Relative L2 <= 6e-3 per gradient tensor, and no element further off than 2 % of the
-tensor's largest magnitude.
+different keys average out (delta itself is taken from the forward's unrounded output, so it adds nothing).  Measured:
+3.1e-3 to 3.8e-3 at ordinary shapes, 5.8e-3 at the worst of 300 random geometries (2 queries, 5 keys, one key holding
+most of the weight: nothing averages out).  Relative L2 <= 8e-3 per gradient tensor, and no element further off than
+2 % of the tensor's largest magnitude.
 """
 import numpy as np
 import pytest
@@ -19,7 +21,7 @@ import gpu_harness as H
 
 pytestmark = pytest.mark.gpu
 
-GRAD_REL_L2 = 6e-3
+GRAD_REL_L2 = 8e-3
 GRAD_MAX_FRAC = 2e-2
 
 
@@ -43,7 +45,7 @@ def run_case(heads, head_dim, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip, seed
     clip = B.Clip(heads, head_dim, gh, gw, C, S, W, T)
     out, dq, dk, dv = (torch.empty((n_clip * P, heads, head_dim), dtype=torch.bfloat16, device="cuda") for _ in range(4))
     clip.forward(ctx_start, n_ctx, n_clip, H.to_dev(q), H.to_dev(k), H.to_dev(v), out)
-    clip.backward(out, H.to_dev(dout), dq, dk, dv)
+    clip.backward(H.to_dev(dout), dq, dk, dv)
     torch.cuda.synchronize()
     want_out = oracle.forward(ctx_start, n_ctx, n_clip, bf16_bits_to_f64(q), bf16_bits_to_f64(k), bf16_bits_to_f64(v))
     what = f"H{heads} D{head_dim} P{P} C{C} S{S} W{W} ctx {ctx_start}+{n_ctx} clip {n_clip}"
@@ -100,7 +102,7 @@ def test_second_step_with_a_shorter_clip_reuses_the_handle():
         dout = bits((n_clip * P, heads, head_dim), 30 + step, "q")
         out, dq, dk, dv = (torch.empty((n_clip * P, heads, head_dim), dtype=torch.bfloat16, device="cuda") for _ in range(4))
         clip.forward(ctx_start, n_ctx, n_clip, H.to_dev(q), H.to_dev(k), H.to_dev(v), out)
-        clip.backward(out, H.to_dev(dout), dq, dk, dv)
+        clip.backward(H.to_dev(dout), dq, dk, dv)
         torch.cuda.synchronize()
         H.assert_parity(H.to_bits(out), oracle.forward(ctx_start, n_ctx, n_clip, *(bf16_bits_to_f64(t) for t in (q, k, v))), f"step {step}")
         for name, t, w in zip(("dq", "dk", "dv"), (dq, dk, dv), oracle.backward(bf16_bits_to_f64(dout))):
@@ -128,7 +130,7 @@ def test_graph_replay_of_a_training_step():
 
     def step(c, q, k, v, do, o, dq, dk, dv):
         c.forward(ctx_start, n_ctx, n_clip, q, k, v, o)
-        c.backward(o, do, dq, dk, dv)
+        c.backward(do, dq, dk, dv)
 
     step(graphed, sq, sk, sv, sdo, so, sdq, sdk, sdv)
     torch.cuda.synchronize()
@@ -184,3 +186,10 @@ def test_more_frames_chunks_and_groups_than_one_launch_takes():
     once."""
     run_case(2, 64, 2, 3, 1, 2, 5, 40, 9, 5, 40, seed=9)
     run_case(1, 128, 2, 3, 2, 0, 3, 70, 0, 0, 70, seed=10)       # a first clip without a sink: 35 chunks, 70 frames
+
+
+def test_one_dominant_key():
+    """Two queries over five keys, one key holding most of each row's weight: dP - delta is then a small difference of
+    large numbers, and a delta taken from the bf16-rounded output would be off by about 2^-9 |dO||O|, 2.5 % of dK
+    here.  The handle keeps the forward's output unrounded for this."""
+    run_case(1, 128, 1, 1, 4, 3, 3, 2, 27, 0, 2, seed=238)
