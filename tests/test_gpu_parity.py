@@ -342,3 +342,10 @@ def test_read_frame_one_tensor_at_a_time():
         P = w.tokens_per_frame
         assert np.array_equal(H.to_bits(only_v), v[frame * P:(frame + 1) * P])      # V is stored bit-exact
     cache.close()
+
+
+@pytest.mark.parametrize("ws", [60000, 2 ** 31 + 77])
+def test_prefill_and_streaming_at_very_late_frames(ws):
+    """Frame indices are 64-bit and absolute: the rotary angles of the frame axis are taken in fp64 on the device, so a
+    window hours into a video (or past 2^31 frames) is as exact as one at the start."""
+    _prefill_case(ODD64, True, ws, ODD64.window_frames + ODD64.chunk_frames, pre_chunks=3)
