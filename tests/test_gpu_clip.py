@@ -71,6 +71,7 @@ def run_case(heads, head_dim, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip, seed
     (2, 64, 9, 15, 2, 2, 4, 6, 30, 4, 6),     # P 135: two column tiles per frame, the second ragged
     (1, 128, 4, 8, 1, 0, 2, 5, 0, 2, 5),      # no sink, chunks of one frame, context from frame 0
     (2, 64, 2, 3, 3, 2, 0, 6, 2, 0, 6),       # no window at all: sink and own chunk only
+    (2, 64, 3, 5, 2, 1, 3, 7, 2 ** 31 + 5, 3, 7),   # a clip past 2^31 frames: 64-bit absolute frame positions
 ])
 def test_clip_forward_and_gradients(heads, head_dim, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip):
     run_case(heads, head_dim, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip)
