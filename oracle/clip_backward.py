@@ -34,7 +34,7 @@ import math
 
 import numpy as np
 
-from oracle.longlive_oracle import OracleConfig, key_frames, rope_rotate
+from oracle.longlive_oracle import OracleConfig, key_frames, rope_angles, rope_rotate
 
 
 def _unrotate_grad(cfg: OracleConfig, g: np.ndarray, frame_start: int) -> np.ndarray:
@@ -123,3 +123,51 @@ class ClipOracle:
         dq = _unrotate_grad(cfg, dq_rot, clip_start)
         dk = _unrotate_grad(cfg, dk_rot[first:], clip_start)
         return dq, dk, dv_all[first:]
+
+    def backward_sample(self, dout: np.ndarray, q_rows, key_rows):
+        """The same gradients for a sample only: rows ``q_rows`` of dq and rows ``key_rows`` of dk and dv (indices into
+        the clip's tokens), all heads of the tensors given to ``forward``.  Same formulas; only the chunks that hold a
+        sampled query or see a sampled key are visited.  For shapes at which the full backward would take minutes."""
+        cfg, P = self.cfg, self.cfg.tokens_per_frame
+        ctx_start, n_ctx, n_clip, fr, pos, q_rot, k_rot, v, steps = self._saved
+        clip_start = ctx_start + n_ctx
+        first = pos[clip_start] * P
+        scale = 1.0 / math.sqrt(cfg.head_dim)
+        q_rows, key_rows = np.asarray(q_rows, dtype=np.int64), np.asarray(key_rows, dtype=np.int64)
+        dq_rot = np.zeros((q_rows.size,) + q_rot.shape[1:])
+        dk_rot = np.zeros((key_rows.size,) + q_rot.shape[1:])
+        dv = np.zeros_like(dk_rot)
+        for rows, kidx in steps:
+            in_chunk = np.nonzero((q_rows >= rows.start) & (q_rows < rows.stop))[0]
+            where = {int(t): i for i, t in enumerate(kidx)}
+            seen = [(n, where[first + int(j)]) for n, j in enumerate(key_rows) if first + int(j) in where]
+            if in_chunk.size == 0 and not seen:
+                continue
+            for h in range(cfg.heads):
+                if seen:                                     # every query of the chunk contributes to a key it sees
+                    p = self._softmax(q_rot[rows, h, :], k_rot[kidx, h, :], scale)
+                    do = dout[rows, h, :]
+                    dp = do @ v[kidx, h, :].T
+                    dz = p * (dp - (p * dp).sum(axis=1, keepdims=True))
+                    for n, col in seen:
+                        dv[n, h, :] += p[:, col] @ do
+                        dk_rot[n, h, :] += (dz[:, col] @ q_rot[rows, h, :]) * scale
+                if in_chunk.size:
+                    r = q_rows[in_chunk]
+                    p = self._softmax(q_rot[r, h, :], k_rot[kidx, h, :], scale)
+                    dp = dout[r, h, :] @ v[kidx, h, :].T
+                    dz = p * (dp - (p * dp).sum(axis=1, keepdims=True))
+                    dq_rot[in_chunk, h, :] = (dz @ k_rot[kidx, h, :]) * scale
+        # back through the rotary turn, token by token
+        def unrotate(g, tokens):
+            out = np.empty_like(g)
+            for n, t in enumerate(tokens):
+                f, y, x = clip_start + int(t) // P, (int(t) % P) // cfg.grid_w, (int(t) % P) % cfg.grid_w
+                a = rope_angles(cfg, f, y, x)
+                c, sn = np.cos(a)[None, :], np.sin(a)[None, :]
+                re, im = g[n, :, 0::2], g[n, :, 1::2]
+                out[n, :, 0::2] = re * c + im * sn            # the rotation by -a
+                out[n, :, 1::2] = im * c - re * sn
+            return out
+        return unrotate(dq_rot, q_rows), unrotate(dk_rot, key_rows), dv
+

@@ -194,3 +194,37 @@ def test_one_dominant_key():
     large numbers, and a delta taken from the bf16-rounded output would be off by about 2^-9 |dO||O|, 2.5 % of dK
     here.  The handle keeps the forward's output unrounded for this."""
     run_case(1, 128, 1, 1, 4, 3, 3, 2, 27, 0, 2, seed=238)
+
+
+def test_bench_shape_sampled():
+    """The shape bench.py times (12 heads x 128, 30 x 52 tokens per frame, chunk 3, sink 3, window 9, a clip of 21
+    frames after 9 context frames: 33 resident frames, 7 chunks, 32760 queries) on the GPU; the oracle follows heads
+    0 and 11 only (heads are independent): their whole forward output, dq at sampled rows of every chunk, dk and dv at
+    sampled keys of an early and of the last chunk."""
+    heads, head_dim, gh, gw, C, S, W, T = 12, 128, 30, 52, 3, 3, 9, 21
+    P, ctx_start, n_ctx, n_clip = gh * gw, 60, 9, 21
+    nf = S + n_ctx + n_clip
+    q = bits((n_clip * P, heads, head_dim), 80, "q")
+    k, v = bits((nf * P, heads, head_dim), 80, "k"), bits((nf * P, heads, head_dim), 80, "v")
+    dout = bits((n_clip * P, heads, head_dim), 81, "q")
+    clip = B.Clip(heads, head_dim, gh, gw, C, S, W, T)
+    out, dq, dk, dv = (torch.empty((n_clip * P, heads, head_dim), dtype=torch.bfloat16, device="cuda") for _ in range(4))
+    clip.forward(ctx_start, n_ctx, n_clip, H.to_dev(q), H.to_dev(k), H.to_dev(v), out)
+    clip.backward(H.to_dev(dout), dq, dk, dv)
+    torch.cuda.synchronize()
+    sel = [0, 11]
+    oracle = ClipOracle(OracleConfig(1, len(sel), head_dim, gh, gw, C, S, W))
+    f64 = lambda b: bf16_bits_to_f64(np.ascontiguousarray(b[:, sel, :]))
+    want_out = oracle.forward(ctx_start, n_ctx, n_clip, f64(q), f64(k), f64(v))
+    H.assert_parity(H.to_bits(out)[:, sel, :], want_out, "bench shape forward, heads 0 and 11")
+    rng = np.random.Generator(np.random.Philox(key=4242))
+    q_rows = np.sort(np.concatenate([c * C * P + rng.integers(0, C * P, 6) for c in range(n_clip // C)]))
+    key_rows = np.sort(np.concatenate([3 * C * P + rng.integers(0, C * P, 6), 6 * C * P + rng.integers(0, C * P, 6),
+                                       [6 * C * P, n_clip * P - 1]]))
+    wq, wk, wv = oracle.backward_sample(f64(dout), q_rows, key_rows)
+    for name, t, w, rows in (("dq", dq, wq, q_rows), ("dk", dk, wk, key_rows), ("dv", dv, wv, key_rows)):
+        g = bf16_bits_to_f64(H.to_bits(t)[rows][:, sel, :])
+        assert np.isfinite(g).all()
+        max_abs, rel = error_metrics(g, w)
+        assert rel <= GRAD_REL_L2 and max_abs <= GRAD_MAX_FRAC * np.abs(w).max(), f"{name}: max_abs {max_abs:.3e} of {np.abs(w).max():.3e}, rel_l2 {rel:.3e}"
+    clip.close()

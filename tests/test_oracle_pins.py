@@ -740,3 +740,18 @@ def test_clip_forward_equals_streaming_inference():
         rows = slice(2 * c * P, 2 * (c + 1) * P)
         inf.append(0, 2 * c, qb[rows], kb[rows], vb[rows])
         assert np.abs(got[rows] - inf.attn(0)).max() < 1e-12
+
+
+# P28: the sampled form of the backward oracle returns the same rows as the full one
+def test_clip_backward_sample_equals_full():
+    cfg = OracleConfig(1, 2, 24, 2, 3, 2, 1, 3)
+    P = cfg.tokens_per_frame
+    ctx_start, n_ctx, n_clip = 4, 3, 7
+    o, q, k, v, dout, nf = _clip_case(120, cfg, ctx_start, n_ctx, n_clip)
+    o.forward(ctx_start, n_ctx, n_clip, q, k, v)
+    dq, dk, dv = o.backward(dout)
+    q_rows, key_rows = [0, 5, 17, n_clip * P - 1, 23], [1, 13, 30, n_clip * P - 2]
+    sq, sk, sv = o.backward_sample(dout, q_rows, key_rows)
+    assert np.abs(sq - dq[q_rows]).max() < 1e-12
+    assert np.abs(sk - dk[key_rows]).max() < 1e-12
+    assert np.abs(sv - dv[key_rows]).max() < 1e-12
