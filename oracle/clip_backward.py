@@ -25,8 +25,8 @@ clip of a video (no context yet) contains the sink frames itself and they then r
 
 Pins (tests/test_oracle_pins.py): central finite differences of the forward in random directions, a library's
 reverse-mode differentiation of a masked attention written with library ops, zero gradient to anything outside the
-key set (window eviction inside a long clip), and equality of a first clip's forward with the inference oracle
-streamed from frame 0.
+key set (window eviction inside a long clip), equality of a first clip's forward with the inference oracle
+streamed from frame 0, and the sampled form of the backward against the full one.
 """
 from __future__ import annotations
 
