@@ -124,8 +124,3 @@ class Fp8Oracle(Oracle):
     def attn(self, layer: int, rows=None, order=None) -> np.ndarray:
         K8, V8 = self.gather_keys(layer, order)
         return attention_log2(self.layer[layer].staged[2], K8, V8, rows) * 2.0 ** self.v_exp
-
-    def frame_codes(self, layer: int, frame: int):
-        """(K8 codes, V8 codes) of a stored frame, uint8 [P, H, D]."""
-        k8, v8 = self._store(layer)[frame]
-        return e4m3_encode(k8), e4m3_encode(v8)

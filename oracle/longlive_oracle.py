@@ -32,7 +32,9 @@ form with adjacent-element pairs described at ``rope_pair_split``.
 Pins (tests/test_oracle_pins.py): brute force loops, plain chunk-causal
 attention through a library masked softmax, row sums, closed-form key-set
 probe, eviction poisoning, key-order invariance, streaming == prefill,
-cross-config equality, constant resident size, rotary closed forms.
+cross-config equality, constant resident size, rotary closed forms; the re-prefill's
+outputs (sink kept or rebuilt, short last chunks) against one masked softmax over all
+retained tokens; ``error_metrics`` against hand-computed values.
 """
 from __future__ import annotations
 
@@ -252,15 +254,7 @@ class Oracle:
         """(K' float64, V float64) of a stored frame, each [P, H, D]."""
         return self._store(layer)[frame]
 
-    def reset(self, layer: int) -> None:
-        self.layer[layer] = _Layer()
-
     # -- KV-recache: re-prefill from the retained frames ---------------------
-    def recache_frames(self, include_sink: bool, win_start: int, n_win: int) -> list[int]:
-        S = self.cfg.sink_frames
-        fr = list(range(S)) if include_sink else []
-        return fr + list(range(win_start, win_start + n_win))
-
     def recache_chunks(self, include_sink: bool, win_start: int, n_win: int):
         """[(frame_start, n_frames)] in order: the sink cut into chunks of C, then the window."""
         C, S = self.cfg.chunk_frames, self.cfg.sink_frames

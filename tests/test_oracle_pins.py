@@ -12,7 +12,7 @@ import pytest
 import torch
 
 from oracle import brute
-from oracle.longlive_oracle import (Oracle, OracleConfig, attention, bf16_bits_to_f64, key_frames,
+from oracle.longlive_oracle import (Oracle, OracleConfig, attention, bf16_bits_to_f64, error_metrics, key_frames,
                                     rope_angles, rope_pair_split, rope_rotate)
 from paper_2509_22622_amd import synth
 
@@ -203,6 +203,131 @@ def test_prefill_without_sink_keeps_old_sink():
     for f in range(3):
         assert np.array_equal(o.frame_kv(0, f)[0], sink_before[f])
     assert o.live_frames(0) == [0, 1, 2] + list(range(9, 18))
+
+
+def _prefill_by_one_mask(cfg, include_sink, win_start, n_win, q, k, v, held_sink=None):
+    """The re-prefill written as ONE masked softmax over all retained tokens (Sec. 3.1 "KV Recache", Sec. 3.3 last
+    sentence): the retained frames G = sink + [win_start, win_start + n_win) are cut into chunks of C (the sink
+    from frame 0, the window from win_start; a last piece may be shorter); a query of the chunk [f0, f1) sees key
+    frame g iff g is in G and (g < S or f0 - W <= g) and g < f1 (nothing of a later chunk, sink or not).  Rotation by the brute-force complex multiplication, the softmax by a
+    library's masked attention.  held_sink: (K' float64, V float64) per sink frame when include_sink is false (those
+    keys are not re-rotated: they stay as they were stored)."""
+    P, C, S, W = cfg.tokens_per_frame, cfg.chunk_frames, cfg.sink_frames, cfg.window_frames
+    H, D = cfg.heads, cfg.head_dim
+    in_frames = (list(range(S)) if include_sink else []) + list(range(win_start, win_start + n_win))
+
+    def rot(bits, frames):
+        x = bf16_bits_to_f64(bits)
+        out = np.empty_like(x)
+        for t in range(x.shape[0]):
+            f = frames[t // P]
+            y, xx = divmod(t % P, cfg.grid_w)
+            for h in range(H):
+                out[t, h] = brute.rotate_vec(list(x[t, h]), D, f, y, xx, cfg.theta)
+        return out
+
+    qr, kr, vv = rot(q, in_frames), rot(k, in_frames), bf16_bits_to_f64(v)
+    key_frames_all, K_all, V_all = list(in_frames), kr, vv
+    if not include_sink and S > 0:
+        key_frames_all = list(range(S)) + key_frames_all
+        K_all = np.concatenate([held_sink[f][0] for f in range(S)] + [kr])
+        V_all = np.concatenate([held_sink[f][1] for f in range(S)] + [vv])
+    # first frame and end of the chunk each query frame belongs to
+    span_of = {}
+    if include_sink:
+        for f in range(S):
+            span_of[f] = ((f // C) * C, min(S, (f // C + 1) * C))
+    for f in range(win_start, win_start + n_win):
+        a = win_start + ((f - win_start) // C) * C
+        span_of[f] = (a, min(win_start + n_win, a + C))
+    q_f0 = np.array([span_of[in_frames[t // P]][0] for t in range(qr.shape[0])])[:, None]
+    q_f1 = np.array([span_of[in_frames[t // P]][1] for t in range(qr.shape[0])])[:, None]
+    key_g = np.array([key_frames_all[t // P] for t in range(K_all.shape[0])])[None, :]
+    mask = ((key_g < S) | (key_g >= q_f0 - W)) & (key_g < q_f1)
+    if not include_sink:
+        mask |= key_g < S          # a kept sink is complete from the start
+    ref = torch.nn.functional.scaled_dot_product_attention(
+        torch.from_numpy(qr).permute(1, 0, 2), torch.from_numpy(K_all).permute(1, 0, 2),
+        torch.from_numpy(V_all).permute(1, 0, 2), attn_mask=torch.from_numpy(mask))
+    return ref.permute(1, 0, 2).numpy()
+
+
+@pytest.mark.parametrize("S,W,C,n_win,win_start", [
+    (2, 4, 3, 7, 2),      # sink shorter than a chunk, window not a multiple of the chunk
+    (2, 4, 3, 6, 50),     # the same sink, late window
+    (4, 5, 3, 8, 100),    # sink cut into two chunks (3 + 1): its second chunk must see the first
+    (3, 6, 3, 7, 30),     # S % C == 0, short last chunk
+    (0, 4, 2, 5, 9),      # no sink
+])
+def test_prefill_outputs_equal_one_masked_softmax(S, W, C, n_win, win_start):
+    cfg = OracleConfig(1, 2, 12, 2, 2, C, S, W)
+    P = cfg.tokens_per_frame
+    shape = ((S + n_win) * P, cfg.heads, cfg.head_dim)
+    q, k, v = _bits(shape, 61), _bits(shape, 62), _bits(shape, 63)
+    o = Oracle(cfg)
+    got = o.recache_prefill(0, True, win_start, n_win, q, k, v)
+    want = _prefill_by_one_mask(cfg, True, win_start, n_win, q, k, v)
+    assert got.shape == want.shape
+    assert np.abs(got - want).max() < 1e-12
+    assert sorted(o._store(0)) == list(range(S)) + list(range(win_start, win_start + n_win))
+
+
+@pytest.mark.parametrize("S,W,C,n_win,win_start,history", [
+    (3, 6, 3, 9, 9, 6),     # full ring re-prefilled, sink kept
+    (3, 6, 3, 7, 12, 6),    # short last chunk
+    (2, 4, 3, 5, 14, 5),    # S % C != 0: the kept sink was staged together with a window frame
+    (3, 9, 3, 4, 40, 4),    # fewer frames than the window holds
+])
+def test_prefill_outputs_with_kept_sink_equal_one_masked_softmax(S, W, C, n_win, win_start, history):
+    """include_sink = 0 after a streamed history: the sink's old keys and values stay, everything else goes."""
+    cfg = OracleConfig(1, 2, 12, 2, 2, C, S, W)
+    P = cfg.tokens_per_frame
+    o = Oracle(cfg)
+    for i, (q, k, v) in enumerate(_stream(cfg, history, 300)):
+        o.append(0, C * i, q, k, v)
+    held = {f: tuple(a.copy() for a in o.frame_kv(0, f)) for f in range(S)}
+    shape = (n_win * P, cfg.heads, cfg.head_dim)
+    q, k, v = _bits(shape, 71), _bits(shape, 72), _bits(shape, 73)
+    got = o.recache_prefill(0, False, win_start, n_win, q, k, v)
+    want = _prefill_by_one_mask(cfg, False, win_start, n_win, q, k, v, held)
+    assert np.abs(got - want).max() < 1e-12
+    # nothing of the streamed history but the sink is left
+    assert sorted(o._store(0)) == list(range(S)) + list(range(win_start, win_start + n_win))
+    # and a planted mistake is seen: re-rotating nothing but dropping the sink changes the result
+    o2 = Oracle(cfg)
+    for i, (qq, kk, vv) in enumerate(_stream(cfg, history, 300)):
+        o2.append(0, C * i, qq, kk, vv)
+    for f in range(S):
+        o2.layer[0].committed.pop(f, None)
+        if o2.layer[0].staged is not None:
+            o2.layer[0].staged[3].pop(f, None)
+    with pytest.raises(ValueError):
+        o2.recache_prefill(0, False, win_start, n_win, q, k, v)
+
+
+# ---- the yardstick of every GPU parity test ---------------------------------
+def test_error_metrics_hand_computed():
+    """max |got - want| and ||got - want||_2 / ||want||_2 over the whole tensor."""
+    got = np.array([1.0, 2.0, 2.0])
+    want = np.array([1.0, 2.0, 4.0])
+    max_abs, rel = error_metrics(got, want)
+    assert max_abs == 2.0
+    assert rel == pytest.approx(2.0 / math.sqrt(21.0), rel=1e-15)
+    # normalised by the reference, not by the result: swapping the two changes the figure (2 / 3 here)
+    assert error_metrics(want, got)[1] == pytest.approx(2.0 / 3.0, rel=1e-15)
+    # the whole tensor, whatever its shape: a 2 x 2 x 2 case with known norms (not a norm per row or per matrix)
+    want3 = np.array([[[3.0, 0.0], [0.0, 4.0]], [[0.0, 0.0], [12.0, 0.0]]])
+    got3 = want3.copy()
+    got3[0, 0, 1] = 0.5
+    got3[1, 1, 1] = -1.0
+    max_abs, rel = error_metrics(got3, want3)
+    assert max_abs == 1.0
+    assert rel == pytest.approx(math.sqrt(1.25) / 13.0, rel=1e-15)
+    # a maximum, not a mean or an rms; fp32 and bf16-decoded inputs are taken as they are
+    assert error_metrics(np.array([0.0, 0.0, 0.0, 3.0], np.float32), np.array([1.0, 0.0, 0.0, 0.0]))[0] == 3.0
+    assert error_metrics(np.zeros(4), np.array([1.0, -1.0, 1.0, -1.0])) == (1.0, 1.0)
+    # sign of the difference does not matter, and equal tensors give exactly zero
+    assert error_metrics(want, want) == (0.0, 0.0)
 
 
 # ---- P8: two configurations with identical key sets -----------------------
