@@ -131,9 +131,13 @@ ll_status ll_sink_window_attn(ll_cache* cache, int layer, const void* q_roped, v
  *   for the rotated queries (out must not alias q, k or v).
  *   All non-sink frames held before are dropped.  include_sink == 0 keeps the sink K/V
  *   already held (LL_ERR_STATE if the sink is incomplete).  win_start >= S, 0 <= n_win <=
- *   W + C.  Afterwards the layer is as if those frames had been streamed: the last chunk
+ *   W + C; n_win == 0 (the sink alone, include_sink != 0) requires win_start == S.
+ *   Afterwards the layer is as if those frames had been streamed: the last chunk
  *   is staged and the next ll_chunk_append must start at win_start + n_win (or repeat the
- *   last chunk's start). */
+ *   last chunk's start).  Every check is made before anything is enqueued: a refused call leaves
+ *   the layer untouched.  If a kernel launch itself fails (LL_ERR_HIP) the layer's slots may be
+ *   half rewritten: the layer is then reset (as by ll_cache_reset), later calls on it return
+ *   LL_ERR_STATE until it is filled again from frame 0 or by another re-prefill with the sink. */
 ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64_t win_start,
                              int n_win, const void* q, const void* k, const void* v,
                              void* out, void* stream);
@@ -152,7 +156,7 @@ ll_status ll_cache_slot_of_frame(const ll_cache* cache, int layer, int64_t frame
 ll_status ll_cache_live_ranges(const ll_cache* cache, int layer, int64_t* ranges, int cap,
                                int* n);
 /* Copy one held frame's rotated K and V out of the cache into [P, H, D] bf16 device
- * tensors (either may be NULL).  LL_ERR_STATE if the frame is not held. */
+ * tensors (either may be NULL, not both: LL_ERR_INVALID_ARG).  LL_ERR_STATE if the frame is not held. */
 ll_status ll_cache_read_frame(const ll_cache* cache, int layer, int64_t frame, void* k_out,
                               void* v_out, void* stream);
 
@@ -210,7 +214,10 @@ ll_status ll_cross_attn(const ll_prompt* prompt, int layer, const void* q, int n
  *     P = softmax(q' K'^T / sqrt(D)),  dV = P^T dO,  dZ = P * (dO V^T - rowsum(dO * O)),
  *     dq' = dZ K' / sqrt(D),  dK' = dZ^T q' / sqrt(D),  then back through the rotary turn of each pair.
  * One handle serves one layer at a time: the backward pass differentiates the handle's last forward pass.  All
- * intermediate tensors live in the caller's buffer; nothing is allocated. */
+ * intermediate tensors live in the caller's buffer; nothing is allocated.  The kernels multiply rows of that buffer
+ * which lie outside a step's key set by an exact zero instead of clearing them, so the buffer must hold finite
+ * numbers only: it is zeroed at ll_clip_create, and q, k, v, dout must be finite in every step (a NaN or an infinity
+ * in one step's inputs stays in the buffer and can reach later steps of the same handle). */
 typedef struct ll_clip ll_clip;
 
 /* Bytes of device memory ll_clip_create needs; 0 if the shapes are invalid.  clip_frames is the largest n_clip. */

@@ -261,11 +261,16 @@ static int64_t sink_shift_of(const ll_cache* c, int64_t f0) {
     return std::max<int64_t>(0, f0 - c->g.W - c->g.S);
 }
 
-// Enqueue attention for a list of query chunks (each with its key ranges).
-static ll_status enqueue_attn(ll_cache* c, int layer, const std::vector<ChunkWork>& work, const void* q, void* out,
-                              hipStream_t s) {
+// Turn a list of query chunks (each with its key ranges) into kernel launches: every check that can fail is made
+// here, before anything is enqueued or any bookkeeping changes.
+struct AttnLaunches { int variant = 0; std::vector<AttnParams> params; };
+
+static ll_status build_attn(const ll_cache* c, int layer, const std::vector<ChunkWork>& work, const void* q, void* out,
+                            AttnLaunches& L) {
     const int variant = pick_variant(c);
     const int qt = attn_variant_qtile(variant);
+    L.variant = variant;
+    L.params.clear();
     for (size_t base = 0; base < work.size(); base += MAX_ATTN_CHUNKS) {
         AttnParams p{};
         p.out = static_cast<uint16_t*>(out);
@@ -314,7 +319,14 @@ static ll_status enqueue_attn(ll_cache* c, int layer, const std::vector<ChunkWor
             tiles += (w.q_end - w.q_begin + qt - 1) / qt;
         }
         p.n_chunks = m; p.n_tiles = tiles;
-        hipError_t e = launch_attn(p, variant, s);
+        L.params.push_back(p);
+    }
+    return LL_OK;
+}
+
+static ll_status launch_built_attn(const AttnLaunches& L, hipStream_t s) {
+    for (const AttnParams& p : L.params) {
+        hipError_t e = launch_attn(p, L.variant, s);
         if (e != hipSuccess) return hip_fail(e, "attention kernel launch");
     }
     return LL_OK;
@@ -358,7 +370,10 @@ ll_status ll_sink_window_attn(ll_cache* cache, int layer, const void* q_roped, v
     work[0].q_end = L.staged_n * cache->g.P;
     work[0].ranges = live_ranges(cache->g, L);
     work[0].f0 = L.staged_f0;
-    return enqueue_attn(cache, layer, work, q_roped, out, static_cast<hipStream_t>(stream));
+    AttnLaunches launches;
+    ll_status st = build_attn(cache, layer, work, q_roped, out, launches);
+    if (st != LL_OK) return st;
+    return launch_built_attn(launches, static_cast<hipStream_t>(stream));
 }
 
 ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64_t win_start, int n_win, const void* q,
@@ -369,6 +384,8 @@ ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64
     if (win_start < g.S) return fail(LL_ERR_INVALID_ARG, "win_start %lld overlaps the sink [0, %d)", (long long)win_start, g.S);
     const int n_total = (include_sink ? g.S : 0) + n_win;
     if (n_total == 0) return fail(LL_ERR_INVALID_ARG, "no frames to prefill");
+    if (n_win == 0 && win_start != g.S)
+        return fail(LL_ERR_INVALID_ARG, "n_win 0 (the sink alone) needs win_start == %d: the next chunk follows the sink", g.S);
     const bool any_null = !q || !k || !v || !out;
     if (cache->dev && any_null) return fail(LL_ERR_INVALID_ARG, "null tensor");
     if (!cache->dev && !(!q && !k && !v && !out)) return fail(LL_ERR_INVALID_ARG, "index-only handle takes null tensors");
@@ -376,34 +393,40 @@ ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64
     if (!aligned16(q, k, v, out)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
     LayerIndex& L = cache->layer[layer];
     if (!include_sink && L.sink_have < g.S) return fail(LL_ERR_STATE, "layer %d: sink incomplete (%lld of %d frames)", layer, (long long)L.sink_have, g.S);
-
+    // the bookkeeping is advanced on a copy and the launches are prepared (every check made) before anything is
+    // enqueued: a request that cannot run leaves the layer as it was
     const std::vector<ChunkSpan> chunks = prefill_chunks(g, include_sink != 0, win_start, n_win);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (cache->dev) {
-        std::vector<int64_t> frames;
-        for (const ChunkSpan& c : chunks)
-            for (int i = 0; i < c.n; ++i) frames.push_back(c.f0 + i);
-        // rotated queries are staged in `out`; the attention kernel reads and overwrites them in place (bf16: a
-        // wave reads exactly the rows it writes).  E4M3 queries are half as wide as the output rows, so they are
-        // staged in the cache buffer's own area instead.
-        void* q_stage = cache->fmt ? static_cast<void*>(cache->q8_stage) : out;
-        ll_status st = enqueue_append(cache, layer, frames.data(), int(frames.size()), q, k, v, q_stage, s);
-        if (st != LL_OK) return st;
-    }
-    begin_prefill(g, L, include_sink != 0, win_start);
+    LayerIndex next = L;
+    begin_prefill(g, next, include_sink != 0, win_start);
     std::vector<ChunkWork> work;
     int row = 0;
     for (const ChunkSpan& c : chunks) {
-        prefill_stage(g, L, c.f0, c.n);
+        prefill_stage(g, next, c.f0, c.n);
         ChunkWork w;
         w.q_begin = row; w.q_end = row + c.n * g.P;
-        w.ranges = live_ranges(g, L);
+        w.ranges = live_ranges(g, next);
         w.f0 = c.f0;
         work.push_back(w);
         row = w.q_end;
     }
-    if (cache->dev) return enqueue_attn(cache, layer, work, cache->fmt ? static_cast<void*>(cache->q8_stage) : out, out, s);
-    return LL_OK;
+    if (!cache->dev) { L = next; return LL_OK; }
+    // rotated queries are staged in `out`; the attention kernel reads and overwrites them in place (bf16: a
+    // wave reads exactly the rows it writes).  E4M3 queries are half as wide as the output rows, so they are
+    // staged in the cache buffer's own area instead.
+    void* q_stage = cache->fmt ? static_cast<void*>(cache->q8_stage) : out;
+    AttnLaunches launches;
+    ll_status st = build_attn(cache, layer, work, q_stage, out, launches);
+    if (st != LL_OK) return st;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    std::vector<int64_t> frames;
+    for (const ChunkSpan& c : chunks)
+        for (int i = 0; i < c.n; ++i) frames.push_back(c.f0 + i);
+    st = enqueue_append(cache, layer, frames.data(), int(frames.size()), q, k, v, q_stage, s);
+    if (st == LL_OK) st = launch_built_attn(launches, s);
+    // a launch that failed half way leaves slots overwritten that the old bookkeeping still describes: forget the
+    // layer, so that later calls report LL_ERR_STATE instead of reading a half-written cache
+    L = st == LL_OK ? next : LayerIndex();
+    return st;
 }
 
 ll_status ll_cache_live_frames(const ll_cache* cache, int layer, int64_t* frames, int cap, int* n) {
@@ -436,6 +459,8 @@ ll_status ll_cache_live_ranges(const ll_cache* cache, int layer, int64_t* ranges
 
 ll_status ll_cache_read_frame(const ll_cache* cache, int layer, int64_t frame, void* k_out, void* v_out, void* stream) {
     CHECK_CACHE_LAYER(cache, layer);
+    if (!k_out && !v_out) return fail(LL_ERR_INVALID_ARG, "k_out and v_out are both null");
+    if (!aligned16(k_out, v_out)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
     if (!cache->dev) return fail(LL_ERR_INVALID_ARG, "index-only handle has no device cache");
     if (!frame_held(cache->g, cache->layer[layer], frame)) return fail(LL_ERR_STATE, "layer %d does not hold frame %lld", layer, (long long)frame);
     ReadFrameParams p{};

@@ -129,7 +129,7 @@ hipError_t launch_append(const AppendParams& p, hipStream_t s) {
 
 // Copy one frame's K (already rotated) and V out of the cache layout into [P, H, D].
 __global__ __launch_bounds__(256) void ll_read_frame_kernel(const ReadFrameParams p) {
-    if (p.v_out == nullptr) {                   // keys only: 8 features of a row are 16 contiguous bytes on both sides
+    if (p.k_out != nullptr && p.v_out == nullptr) {   // keys only: 8 features of a row are 16 contiguous bytes on both sides
         const int64_t units = int64_t(p.P) * p.H * (p.D / 8);
         for (int64_t u = blockIdx.x * 256LL + threadIdx.x; u < units; u += int64_t(gridDim.x) * 256) {
             const int c = int(u % (p.D / 8));

@@ -164,6 +164,25 @@ def test_error_paths():
     c.reset(0)
     c.chunk_append(0, 0, 3)
     assert L.ll_status_string(2) == b"LL_ERR_STATE"
+    # ll_cache_read_frame: nothing to write to is an error of the arguments, whatever the handle (a keys-only copy
+    # with no key tensor would otherwise store through a null pointer); a misaligned tensor likewise
+    assert L.ll_cache_read_frame(c._h, 0, 0, None, None, None) == B.LL_ERR_INVALID_ARG
+    assert b"both null" in L.ll_last_error()
+    assert L.ll_cache_read_frame(c._h, 0, 0, C.c_void_p(0x1008), None, None) == B.LL_ERR_INVALID_ARG
+    assert b"aligned" in L.ll_last_error()
+    # a re-prefill of the sink alone: the next chunk can only follow the sink, so any other win_start is refused
+    with pytest.raises(B.LongLiveError) as e:
+        c.recache_prefill(0, True, 9, 0)
+    assert e.value.status == B.LL_ERR_INVALID_ARG
+    before = c.live_frames(0)
+    c.recache_prefill(0, True, 3, 0)
+    assert c.live_frames(0) == [0, 1, 2]
+    c.chunk_append(0, 3, 3)
+    assert c.live_frames(0) == [0, 1, 2, 3, 4, 5] and before == [0, 1, 2]
+    # a refused re-prefill leaves the layer as it was
+    with pytest.raises(B.LongLiveError):
+        c.recache_prefill(0, True, 3, 10)
+    assert c.live_frames(0) == [0, 1, 2, 3, 4, 5]
     c.close()
 
 
