@@ -68,6 +68,35 @@ def test_wan_layer_streaming():
     cache.close()
 
 
+def test_wan_layer_sink_relative():
+    """Config 2's shape with the sink at a fixed rotary distance (the configuration bench.py times as
+    cfg2_sink_relative): the sink is a key range of its own once f0 > W + S (chunks 5 and 6 here, shifts 3 and 6),
+    and the kblock it shares with the ring is visited once per range."""
+    from oracle.sink_relative import SinkRelativeOracle
+    w = synth.WAN_LAYER
+    cache, oracle = H.make_cache(w), SinkRelativeOracle(H.oracle_cfg(w))
+    cache.set_sink_relative(True)
+    shifts = []
+    for i in range(7):
+        f0 = 3 * i
+        q, k, v = synth.chunk_qkv(w, 0, i)
+        qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+        qr, out = torch.empty_like(qd), torch.empty_like(qd)
+        cache.chunk_append(0, f0, 3, qd, kd, vd, qr)
+        cache.sink_window_attn(0, qr, out)
+        torch.cuda.synchronize()
+        oracle.append(0, f0, q, k, v)
+        assert cache.live_frames(0) == oracle.live_frames(0)
+        shifts.append(oracle.delta(f0))
+        if i >= 3:
+            _check_sampled(out, oracle, 0, _sample_rows(w.chunk_tokens, 400 + i), f"cfg2 sink-relative chunk {i}")
+        if i == 6:                                                 # every element once, with a shift in force
+            H.assert_parity(H.to_bits(out), oracle.attn(0), "cfg2 sink-relative chunk 6 full tensor")
+        _trim(oracle, 0, f0 - w.window_frames, w.sink_frames)
+    assert shifts == [0, 0, 0, 0, 0, 3, 6]
+    cache.close()
+
+
 def test_long_window():
     """Config 4: no sink, window 21 frames (37440 keys in steady state)."""
     w = synth.LONG_WINDOW
