@@ -142,6 +142,22 @@ ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64
                              int n_win, const void* q, const void* k, const void* v,
                              void* out, void* stream);
 
+/* ll_recache_prefill for callers that must not allocate or hand over scratch memory (code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc): same arguments, same result, and no device memory beyond
+ * the inputs, the outputs and the cache itself is taken from the caller.  The one scratch buffer the re-prefill
+ * needs - the E4M3 queries of an 8-bit cache, which ll_recache_prefill stages in an area of the cache buffer -
+ * lives in an array inside the library instead: 36 MiB per GPU the library is used on, held until the process
+ * ends (a re-prefill of 15 frames at 1560 tokens x 12 heads x 128 needs 34.3 MiB).
+ *   LL_ERR_BUFFER_TOO_SMALL if (frames to prefill) * P * H * D exceeds 36 MiB (nothing is enqueued).
+ *   Every call on one GPU shares that GPU's array: two such calls must not overlap in time on one GPU, whatever
+ *   their handles or layers (enqueue them on one stream, or order the streams); the array keeps the last call's
+ *   queries, nothing in it needs clearing (every byte a call reads it has written before).
+ *   A bf16 cache stages its queries in `out` and needs no scratch: for such a handle the call is
+ *   ll_recache_prefill.  Neither call allocates, frees or synchronises. */
+ll_status ll_recache_prefill_static(ll_cache* cache, int layer, int include_sink, int64_t win_start,
+                                    int n_win, const void* q, const void* k, const void* v,
+                                    void* out, void* stream);
+
 /* ---- introspection (exact integer answers; used for the bit-exact indexing checks) ---- */
 
 /* Frames the staged chunk attends to, ascending.  frames: host, capacity `cap`; *n = count. */

@@ -29,6 +29,7 @@ SIGNATURES = {
     "ll_chunk_append": (_i, [_vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]),
     "ll_sink_window_attn": (_i, [_vp, _i, _vp, _vp, _vp]),
     "ll_recache_prefill": (_i, [_vp, _i, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]),
+    "ll_recache_prefill_static": (_i, [_vp, _i, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]),
     "ll_cache_live_frames": (_i, [_vp, _i, C.POINTER(_i64), _i, C.POINTER(_i)]),
     "ll_cache_slot_of_frame": (_i, [_vp, _i, _i64, C.POINTER(_i64)]),
     "ll_cache_live_ranges": (_i, [_vp, _i, C.POINTER(_i64), _i, C.POINTER(_i)]),
@@ -201,6 +202,11 @@ class Cache:
         stream = _stream() if q is not None else None
         _check(lib().ll_recache_prefill(self._h, layer, int(include_sink), win_start, n_win, _ptr(q), _ptr(k), _ptr(v),
                                         _ptr(out), stream))
+
+    def recache_prefill_static(self, layer, include_sink, win_start, n_win, q=None, k=None, v=None, out=None):
+        stream = _stream() if q is not None else None
+        _check(lib().ll_recache_prefill_static(self._h, layer, int(include_sink), win_start, n_win, _ptr(q), _ptr(k),
+                                               _ptr(v), _ptr(out), stream))
 
     def live_frames(self, layer):
         cap = self.S + self.W + self.C + 1

@@ -80,6 +80,29 @@ Sizes sizes(int fmt, int layers, int H, int D, int P, int S, int W, int C, int g
     z.total = (off + 255) & ~size_t(255);
     return z;
 }
+// Staging area of ll_recache_prefill_static: the E4M3 queries of one re-prefill of an 8-bit cache.  One copy per GPU
+// the library runs on, held until the process ends.  In host code the array's name is only a stand-in: its device
+// address comes from hipGetSymbolAddress, once per device (each GPU has its own copy at its own address).
+constexpr size_t STATIC_STAGE_BYTES = size_t(36) << 20;
+constexpr int MAX_DEVICES = 64;
+static __device__ __align__(256) unsigned char scratch[STATIC_STAGE_BYTES];
+static void* g_scratch_ptr[MAX_DEVICES] = {};
+
+// Device address of `scratch` on the current device (looked up on the first call per device).
+ll_status static_stage(void** ptr) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= MAX_DEVICES) return fail(LL_ERR_UNSUPPORTED, "device %d beyond the %d the library keeps a staging area for", dev, MAX_DEVICES);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return LL_OK;
+}
 // upper bound of the table area when the grid is not known yet (ll_cache_bytes)
 size_t table_bound(int D, int P) { return 3 * 256 + 64 * sizeof(double) + 2 * size_t(P) * (D / 2) * sizeof(float2); }
 }  // namespace
@@ -152,7 +175,7 @@ static ll_status cache_create(int fmt, int k_exp, int v_exp, int layers, int hea
                 const double a = double(x) * std::pow(double(rope_theta), -2.0 * i / (2.0 * z.n_w));
                 col[size_t(x) * z.n_w + i] = make_float2(float(std::cos(a)), float(std::sin(a)));
             }
-        hipError_t e = hipMemset(c->dev, 0, z.table_off);
+        hipError_t e = hipMemset(c->dev, 0, need);      // all of it: the padding behind the tables too
         if (e == hipSuccess) e = hipMemcpy(c->dev + z.table_off, inv_t.data(), inv_t.size() * sizeof(double), hipMemcpyHostToDevice);
         if (e == hipSuccess && !row.empty()) e = hipMemcpy(c->dev + z.row_off, row.data(), row.size() * sizeof(float2), hipMemcpyHostToDevice);
         if (e == hipSuccess && !col.empty()) e = hipMemcpy(c->dev + z.col_off, col.data(), col.size() * sizeof(float2), hipMemcpyHostToDevice);
@@ -376,8 +399,10 @@ ll_status ll_sink_window_attn(ll_cache* cache, int layer, const void* q_roped, v
     return launch_built_attn(launches, static_cast<hipStream_t>(stream));
 }
 
-ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64_t win_start, int n_win, const void* q,
-                             const void* k, const void* v, void* out, void* stream) {
+// use_static_stage: an 8-bit cache stages its E4M3 queries in the library's own static array instead of the area
+// of the caller's cache buffer
+static ll_status recache_prefill(ll_cache* cache, int layer, int include_sink, int64_t win_start, int n_win, const void* q,
+                                 const void* k, const void* v, void* out, void* stream, bool use_static_stage) {
     CHECK_CACHE_LAYER(cache, layer);
     const Geometry& g = cache->g;
     if (n_win < 0 || n_win > g.ring()) return fail(LL_ERR_INVALID_ARG, "n_win %d outside [0, %d]", n_win, g.ring());
@@ -414,8 +439,16 @@ ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64
     // wave reads exactly the rows it writes).  E4M3 queries are half as wide as the output rows, so they are
     // staged in the cache buffer's own area instead.
     void* q_stage = cache->fmt ? static_cast<void*>(cache->q8_stage) : out;
+    ll_status st = LL_OK;
+    if (cache->fmt && use_static_stage) {
+        const size_t need = size_t(n_total) * g.P * cache->H * cache->D;      // one byte per element
+        if (need > STATIC_STAGE_BYTES)
+            return fail(LL_ERR_BUFFER_TOO_SMALL, "the re-prefill stages %zu bytes of queries, the static area holds %zu", need, STATIC_STAGE_BYTES);
+        st = static_stage(&q_stage);
+        if (st != LL_OK) return st;
+    }
     AttnLaunches launches;
-    ll_status st = build_attn(cache, layer, work, q_stage, out, launches);
+    st = build_attn(cache, layer, work, q_stage, out, launches);
     if (st != LL_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     std::vector<int64_t> frames;
@@ -427,6 +460,16 @@ ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64
     // layer, so that later calls report LL_ERR_STATE instead of reading a half-written cache
     L = st == LL_OK ? next : LayerIndex();
     return st;
+}
+
+ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64_t win_start, int n_win, const void* q,
+                             const void* k, const void* v, void* out, void* stream) {
+    return recache_prefill(cache, layer, include_sink, win_start, n_win, q, k, v, out, stream, false);
+}
+
+ll_status ll_recache_prefill_static(ll_cache* cache, int layer, int include_sink, int64_t win_start, int n_win,
+                                    const void* q, const void* k, const void* v, void* out, void* stream) {
+    return recache_prefill(cache, layer, include_sink, win_start, n_win, q, k, v, out, stream, true);
 }
 
 ll_status ll_cache_live_frames(const ll_cache* cache, int layer, int64_t* frames, int cap, int* n) {
