@@ -275,16 +275,20 @@ constexpr int kNumSimple = sizeof(kSimpleVariants) / sizeof(kSimpleVariants[0]);
 static_assert(kNumSimple == 10, "attn_variant_short_keys names table positions 8 and 10");
 
 // variant ids: 1..kNumSimple are the kernels of this file, then the software-pipelined kernels, then the
-// kernels of the 8-bit cache
+// kernels of the 8-bit cache, then the software-pipelined kernels on 16x16x32 MFMAs
 static const AttnVariant* variant(int v) {
     if (v >= 1 && v <= kNumSimple) return &kSimpleVariants[v - 1];
     v -= kNumSimple;
     if (v >= 1 && v <= kNumStreamVariants) return &kStreamVariants[v - 1];
     v -= kNumStreamVariants;
     if (v >= 1 && v <= kNumFp8Variants) return &kFp8Variants[v - 1];
+    v -= kNumFp8Variants;
+    if (v >= 1 && v <= kNumStream16Variants) return &kStream16Variants[v - 1];
     return nullptr;
 }
-int attn_variant_count() { return kNumSimple + kNumStreamVariants + kNumFp8Variants; }
+static int first_stream16() { return kNumSimple + kNumStreamVariants + kNumFp8Variants + 1; }
+static bool is_stream16(int v) { return v >= first_stream16() && v < first_stream16() + kNumStream16Variants; }
+int attn_variant_count() { return kNumSimple + kNumStreamVariants + kNumFp8Variants + kNumStream16Variants; }
 const char* attn_variant_name(int v) { return variant(v) ? variant(v)->name : nullptr; }
 // the software-pipelined kernels are the default
 int attn_variant_default(int D, int kblock) {
@@ -294,13 +298,15 @@ int attn_variant_default(int D, int kblock) {
 int attn_variant_qtile(int v) { return variant(v)->qtile; }
 bool attn_variant_supports(int v, int D, int kblock) { return variant(v) && variant(v)->D == D && variant(v)->kblock == kblock; }
 // only the software-pipelined bf16 kernels take queries turned back for the sink range (AttnChunk::sink_shift)
-bool attn_variant_sink_shift(int v) { return v > kNumSimple && v <= kNumSimple + 2; }
+bool attn_variant_sink_shift(int v) { return (v > kNumSimple && v <= kNumSimple + 2) || (is_stream16(v) && v < first_stream16() + 2); }
 // the software-pipelined kernel that multiplies the queries by AttnParams::scale_log2e itself
 int attn_variant_qscale(int D) { return kNumSimple + (D == 128 ? 3 : 4); }
 int attn_variant_lse(int D) { return kNumSimple + (D == 128 ? 5 : 6); }
 // the 128-query kernel that leaves room for three workgroups per CU (short key sets, many query tiles)
 int attn_variant_short_keys(int D) { return D == 128 ? 8 : 10; }
-bool attn_variant_applies_scale(int v) { return (v >= 1 && v <= kNumSimple) || v == kNumSimple + 3 || v == kNumSimple + 4; }
+bool attn_variant_applies_scale(int v) {
+    return (v >= 1 && v <= kNumSimple) || v == kNumSimple + 3 || v == kNumSimple + 4 || v == first_stream16() + 2 || v == first_stream16() + 3;
+}
 
 hipError_t launch_attn(const AttnParams& p_in, int variant, hipStream_t s) {
     if (!attn_variant_supports(variant, p_in.D, p_in.kblock)) return hipErrorInvalidValue;
@@ -318,7 +324,7 @@ hipError_t launch_attn(const AttnParams& p_in, int variant, hipStream_t s) {
     int grid = ((total + 7) / 8) * 8;           // the kernels spread their workgroups over the 8 XCDs
     p.n_groups = 0;
     const int groups = p.H * p.n_chunks;
-    if (variant > kNumSimple && p.n_chunks > 1 && groups >= 16 && groups <= MAX_XCD_GROUPS) {
+    if (variant > kNumSimple && p.n_chunks > 1 && groups >= 16 && groups <= MAX_XCD_GROUPS) {   // every kernel but the simple ones reads the placement
         // Tiles of different chunks differ in length, and the hardware binds workgroup b to XCD b % 8: hand each
         // XCD whole (head, chunk) groups so that all carry the same number of kblock steps (longest group to the
         // least loaded XCD), and let each start with its longest tiles.
@@ -354,7 +360,8 @@ hipError_t launch_attn(const AttnParams& p_in, int variant, hipStream_t s) {
         p.n_groups = n;
         grid = 8 * most_tiles;
     }
-    static bool attr_set[32] = {};
+    static bool attr_set[64] = {};
+    if (variant > 64) return hipErrorInvalidValue;
     if (!attr_set[variant - 1]) {
         hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(v.kernel),
                                            hipFuncAttributeMaxDynamicSharedMemorySize, v.lds_bytes);

@@ -176,6 +176,8 @@ extern const AttnVariant kStreamVariants[];
 extern const int kNumStreamVariants;
 extern const AttnVariant kFp8Variants[];
 extern const int kNumFp8Variants;
+extern const AttnVariant kStream16Variants[];   // the software-pipelined kernels on 16x16x32 MFMAs (attn_stream16.hip)
+extern const int kNumStream16Variants;
 
 // Attention variants (query rows per workgroup differ).
 int attn_variant_count();

@@ -36,6 +36,37 @@ struct LdsPlan {
     }
 };
 
+// The plan of the same kernel built on 16x16x32 MFMAs (attn_stream16.hip).  A step has the same KS + NV slots, each
+// now opened by the two MFMAs that share a fragment: slot k < KS takes K fragment k; the O^T slots run over the
+// V^T fragments twice, slot KS + j taking fragments 2 j and 2 j + 1 for the first query block (j < NV / 2) and slot
+// KS + NV / 2 + j the same two for the second.  Reads are issued as above (V^T fragment f in slot f / 2, K fragment
+// f of the next kblock in slot KS + f / 2, after the slot's MFMAs, V^T before K, in fragment order).  A fragment is
+// waited for at its first use only; the younger of a slot's two V^T fragments carries the wait for both.
+template <int D>
+struct LdsPlan16 {
+    static constexpr int KS = D / 16;
+    static constexpr int NV = D / 16;
+    static constexpr int vslot(int f) { return f / 2; }
+    static constexpr int kslot(int f) { return KS + f / 2; }
+    static constexpr int first_use_v(int f) { return KS + f / 2; }            // slot of the first query block
+    static constexpr int last_use_v(int f) { return KS + NV / 2 + f / 2; }    // slot of the second query block
+    // Reads issued after V^T fragment 2 j + 1 when slot KS + j starts.
+    static constexpr int wait_v(int j) {
+        const int g = 2 * j + 1;
+        int c = 0;
+        for (int f = 0; f < NV; ++f) c += vslot(f) > vslot(g) || (vslot(f) == vslot(g) && f > g);
+        for (int f = 0; f < KS; ++f) c += kslot(f) < KS + j;
+        return c;
+    }
+    // Reads issued after K fragment k (read in the step before) when slot k starts.
+    static constexpr int wait_k(int k) {
+        int c = 0;
+        for (int f = 0; f < KS; ++f) c += kslot(f) > kslot(k) || (kslot(f) == kslot(k) && f > k);
+        for (int f = 0; f < NV; ++f) c += vslot(f) < k;
+        return c;
+    }
+};
+
 // The same for the kernel of the 8-bit cache.  A step has NK = 2 * D/64 slots of S^T MFMAs (for the next kblock)
 // and DB = D/32 slots of O^T MFMAs (for this one); every MFMA consumes one operand fragment, read with two 16-byte
 // LDS reads.  Slot k issues its MFMA first and then the two reads of the fragment that slot k + AHEAD_SLOTS needs

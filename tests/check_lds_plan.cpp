@@ -55,8 +55,63 @@ int check() {
     return 0;
 }
 
+// The same replay for the plan of the 16x16x32 form (LdsPlan16): slot k < KS consumes K fragment k; slot KS + j
+// (j < NV / 2) consumes V^T fragments 2 j and 2 j + 1 under ONE wait placed on the younger of the two; slot
+// KS + NV / 2 + j uses the same two again without a wait.
+template <int D>
+int check16() {
+    using P = ll::LdsPlan16<D>;
+    constexpr int KS = P::KS, NV = P::NV, NSLOT = KS + NV, HV = NV / 2;
+    std::deque<int> issued;
+    auto position_from_youngest = [&](int id) {
+        for (int i = int(issued.size()) - 1, n = 0; i >= 0; --i, ++n)
+            if (issued[i] == id) return n;
+        return -1;
+    };
+    for (int step = 0; step < 6; ++step) {
+        for (int k = 0; k < NSLOT; ++k) {
+            if (step > 0 && (k < KS || k < KS + HV)) {
+                int need_old, need_young, count;
+                if (k < KS) { need_old = need_young = (step - 1) * 100 + 50 + k; count = P::wait_k(k); }
+                else        { need_old = step * 100 + 2 * (k - KS); need_young = need_old + 1; count = P::wait_v(k - KS); }
+                const int pos_young = position_from_youngest(need_young), pos_old = position_from_youngest(need_old);
+                if (pos_young < 0 || pos_old < 0) { std::printf("16: D=%d step %d slot %d: a fragment was never read\n", D, step, k); return 1; }
+                if (count > 15) { std::printf("16: D=%d slot %d: count %d does not fit the counter\n", D, k, count); return 1; }
+                if (pos_young < count || pos_old < count) { std::printf("16: D=%d step %d slot %d: wait %d too weak\n", D, step, k, count); return 1; }
+                if (pos_young != count) { std::printf("16: D=%d step %d slot %d: wait %d stricter than needed (%d)\n", D, step, k, count, pos_young); return 1; }
+            }
+            if (k >= KS + HV) {   // second use: the fragments must be the ones of this step, untouched since
+                for (int e = 0; e < 2; ++e) {
+                    const int f = 2 * (k - KS - HV) + e;
+                    if (P::last_use_v(f) != k || P::first_use_v(f) != k - HV) { std::printf("16: D=%d: use slots of V^T fragment %d\n", D, f); return 1; }
+                }
+            }
+            for (int f = 0; f < NV; ++f)
+                if (P::vslot(f) == k) {
+                    // the register was last used in slot last_use_v(f) of the step before, and is first needed in first_use_v(f)
+                    if (!(k < P::first_use_v(f))) { std::printf("16: D=%d: V^T fragment %d read in slot %d, after its use\n", D, f, k); return 1; }
+                    if (!(P::last_use_v(f) < NSLOT)) return 1;
+                    issued.push_back(step * 100 + f);
+                }
+            for (int f = 0; f < KS; ++f)
+                if (P::kslot(f) == k) {
+                    if (!(k > f)) { std::printf("16: D=%d: K fragment %d read in slot %d, before its register is free\n", D, f, k); return 1; }
+                    issued.push_back(step * 100 + 50 + f);
+                }
+        }
+    }
+    int nv = 0, nk = 0;
+    for (int k = 0; k < NSLOT; ++k) {
+        for (int f = 0; f < NV; ++f) nv += P::vslot(f) == k;
+        for (int f = 0; f < KS; ++f) nk += P::kslot(f) == k;
+    }
+    if (nv != NV || nk != KS) { std::printf("16: D=%d: %d V^T and %d K reads per step\n", D, nv, nk); return 1; }
+    return 0;
+}
+
 int main() {
     if (check<64>() || check<128>()) return 1;
+    if (check16<64>() || check16<128>()) return 1;
     std::printf("lds plan ok\n");
     return 0;
 }
