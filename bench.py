@@ -464,7 +464,7 @@ def main():
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "attn_ms_per_layer": round(attn_ms, 4), "append_ms_per_layer": round(append_ms, 4),
         "append_GBps": round(append_bytes / (append_ms * 1e-3) / 1e9, 1),
-        "roofline": {"bound": "mfma", "kernel": "ll_attn_stream_kernel<128, false, false>", "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "ll_attn_stream16_kernel<128, false, false>", "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": ATTN_HBM_TRAFFIC_BYTES,
                      "flops_per_launch": fl_layer, "avg_launch_ms": round(attn_ms, 4),
                      "algorithmic_bytes": (2 * nq + 2 * nk) * Hh * D * 2},

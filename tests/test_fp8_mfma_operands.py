@@ -10,6 +10,8 @@ import re
 import subprocess
 import tempfile
 
+import pytest
+
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 SRC = os.path.join(ROOT, "paper_2509_22622_amd", "csrc", "attn_fp8.hip")
 PAT = re.compile(r"v_mfma_scale_f32_32x32x64_f8f6f4\s+v\[(\d+):(\d+)\],\s*v\[(\d+):(\d+)\],\s*v\[(\d+):(\d+)\],\s*(\S+?),")
@@ -37,15 +39,17 @@ def test_no_result_over_operand():
     assert len(piped) == 4 and all(v == 0 for v in piped.values()), f"spills in the pipelined kernels: {piped}"
 
 
-def test_bf16_stream_kernels_do_not_spill():
-    """The bf16 software-pipelined kernels use the same pending LDS reads: they must not spill either."""
+@pytest.mark.parametrize("source, kernel", [("attn_stream.hip", "ll_attn_stream_kernel"),
+                                            ("attn_stream16.hip", "ll_attn_stream16_kernel")])
+def test_bf16_stream_kernels_do_not_spill(source, kernel):
+    """The bf16 software-pipelined kernels (both MFMA shapes) use the same pending LDS reads: they must not spill."""
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    src = os.path.join(ROOT, "paper_2509_22622_amd", "csrc", "attn_stream.hip")
+    src = os.path.join(ROOT, "paper_2509_22622_amd", "csrc", source)
     with tempfile.TemporaryDirectory() as tmp:
         out = os.path.join(tmp, "attn_stream.s")
         subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
                         "-packed-fp32-ops", "-S", "--cuda-device-only", src, "-o", out], check=True, capture_output=True)
         text = open(out).read()
     spills = dict(re.findall(r"\.name:\s+(\S+)[\s\S]*?\.vgpr_spill_count:\s+(\d+)", text))
-    stream = {k: int(v) for k, v in spills.items() if "ll_attn_stream_kernel" in k}
+    stream = {k: int(v) for k, v in spills.items() if kernel + "I" in k}
     assert len(stream) == 6 and all(v == 0 for v in stream.values()), f"spills: {stream}"
