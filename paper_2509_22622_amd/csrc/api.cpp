@@ -27,6 +27,7 @@ struct ll_cache {
     int64_t head_stride;    // elements between heads (K region + V region); bytes for the 8-bit cache
     int64_t layer_stride;   // elements between layers
     RopeTables rope;
+    std::vector<double> inv_freq_t;   // host copy of the frame-axis frequencies (the device copy is rope.inv_freq_t)
     std::vector<LayerIndex> layer;
 };
 
@@ -139,8 +140,8 @@ static ll_status cache_create(int fmt, int k_exp, int v_exp, int layers, int hea
     if (grid_h < 1 || grid_w < 1 || int64_t(grid_h) * grid_w != tokens_per_frame)
         return fail(LL_ERR_INVALID_ARG, "grid %dx%d does not give %d tokens per frame", grid_h, grid_w, tokens_per_frame);
     if (!(rope_theta > 1.0f)) return fail(LL_ERR_INVALID_ARG, "rope_theta must exceed 1");
-    if (chunk_frames > MAX_APPEND_FRAMES)
-        return fail(LL_ERR_UNSUPPORTED, "chunk_frames above %d", MAX_APPEND_FRAMES);
+    if (chunk_frames > MAX_CHUNK_FRAMES)
+        return fail(LL_ERR_UNSUPPORTED, "chunk_frames above %d", MAX_CHUNK_FRAMES);
     const bool index_only = dev_buffer == nullptr && dev_bytes == 0;
     const size_t need = cache_bytes(fmt, layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames);
     if (!index_only) {
@@ -160,10 +161,12 @@ static ll_status cache_create(int fmt, int k_exp, int v_exp, int layers, int hea
     c->kblocks = z.kblocks; c->head_stride = z.head_stride; c->layer_stride = z.layer_stride;
     c->layer.assign(layers, LayerIndex());
     c->rope = RopeTables{nullptr, nullptr, nullptr, z.n_t, z.n_h, z.n_w};
+    if (z.n_t > MAX_T_PAIRS) { delete c; return fail(LL_ERR_UNSUPPORTED, "%d frame-axis rotary pairs, at most %d", z.n_t, MAX_T_PAIRS); }
+    c->inv_freq_t.resize(z.n_t);
+    for (int i = 0; i < z.n_t; ++i) c->inv_freq_t[i] = std::pow(double(rope_theta), -2.0 * i / (2.0 * z.n_t));
     if (!index_only) {
         // Rotary tables: angles in double, stored as float (cos, sin); frame frequencies stay double.
-        std::vector<double> inv_t(z.n_t);
-        for (int i = 0; i < z.n_t; ++i) inv_t[i] = std::pow(double(rope_theta), -2.0 * i / (2.0 * z.n_t));
+        const std::vector<double>& inv_t = c->inv_freq_t;
         std::vector<float2> row(size_t(grid_h) * z.n_h), col(size_t(grid_w) * z.n_w);
         for (int y = 0; y < grid_h; ++y)
             for (int i = 0; i < z.n_h; ++i) {
@@ -265,6 +268,7 @@ static ll_status enqueue_append(ll_cache* c, int layer, const int64_t* frames, i
             const int nseg = int((p.slot[i] % c->kb + c->g.P + c->kb - 1) / c->kb);
             p.seg_begin[i + 1] = p.seg_begin[i] + nseg;
         }
+        set_frame_rotation(p, c->inv_freq_t.data());
         hipError_t e = c->fmt ? launch_append8(p, s) : launch_append(p, s);
         if (e != hipSuccess) return hip_fail(e, "append kernel launch");
     }
@@ -372,7 +376,7 @@ ll_status ll_chunk_append(ll_cache* cache, int layer, int64_t frame_start, int n
         return fail(LL_ERR_STATE, "layer %d: frame_start %lld neither repeats (%lld) nor follows (%lld) the staged chunk",
                     layer, (long long)frame_start, (long long)L.staged_f0, (long long)(L.staged_f0 + L.staged_n));
     if (cache->dev) {
-        int64_t frames[MAX_APPEND_FRAMES];
+        int64_t frames[MAX_CHUNK_FRAMES];
         for (int i = 0; i < n_frames; ++i) frames[i] = frame_start + i;
         ll_status st = enqueue_append(cache, layer, frames, n_frames, q, k, v, q_out, static_cast<hipStream_t>(stream));
         if (st != LL_OK) return st;

@@ -16,6 +16,7 @@ struct ll_clip {
     // byte offsets into the workspace
     size_t o_a, o_b, o_cq, o_cd, o_qrot, o_krot, o_lse, o_delta, o_gq, o_gk, o_o32, o_zero, o_freq, o_row, o_col;
     RopeTables rope;
+    std::vector<double> inv_freq_t;     // host copy of the frame-axis frequencies
     // what the last forward left
     bool have_fwd;
     int64_t ctx_start;
@@ -96,13 +97,14 @@ ll_status ll_clip_create(int heads, int head_dim, int tokens_per_frame, int sink
     c->o_zero = z.o_zero; c->o_freq = z.o_freq; c->o_row = z.o_row; c->o_col = z.o_col;
     const int d_hw = 2 * (head_dim / 6), n_t = (head_dim - 2 * d_hw) / 2, n_h = d_hw / 2;
     c->rope = RopeTables{nullptr, nullptr, nullptr, n_t, n_h, n_h};
+    c->inv_freq_t.resize(n_t);
+    for (int i = 0; i < n_t; ++i) c->inv_freq_t[i] = std::pow(double(rope_theta), -2.0 * i / (2.0 * n_t));
     c->have_fwd = false;
     if (!index_only) {
         if (!dev_buffer) { delete c; return fail(LL_ERR_INVALID_ARG, "dev_buffer is null"); }
         if (reinterpret_cast<uintptr_t>(dev_buffer) & 255) { delete c; return fail(LL_ERR_INVALID_ARG, "dev_buffer is not 256-byte aligned"); }
         if (dev_bytes < need) { delete c; return fail(LL_ERR_BUFFER_TOO_SMALL, "dev_buffer has %zu bytes, %zu needed", dev_bytes, need); }
-        std::vector<double> inv_t(n_t);
-        for (int i = 0; i < n_t; ++i) inv_t[i] = std::pow(double(rope_theta), -2.0 * i / (2.0 * n_t));
+        const std::vector<double>& inv_t = c->inv_freq_t;
         std::vector<float2> row(size_t(grid_h) * n_h), col(size_t(grid_w) * n_h);
         for (int y = 0; y < grid_h; ++y)
             for (int i = 0; i < n_h; ++i) {
@@ -171,6 +173,7 @@ hipError_t clip_write_pair(const ll_clip* c, const uint16_t* k, const uint16_t* 
     p.k_cache = region; p.v_cache = region + kblocks * KBLOCK * c->D;
     p.head_stride = head_stride;
     p.rope = clip_identity_rope(c);
+    p.identity = 1;
     p.H = c->H; p.D = c->D; p.P = int(rows); p.grid_w = int(rows);
     p.n_frames = 1;
     p.frame[0] = 0; p.slot[0] = 0;
@@ -232,6 +235,7 @@ ll_status ll_clip_forward(ll_clip* clip, int64_t ctx_start, int n_ctx, int n_cli
                 p.slot[i] = int64_t(pos) * c->P;
                 p.seg_begin[i + 1] = p.seg_begin[i] + int((p.slot[i] % KBLOCK + c->P + KBLOCK - 1) / KBLOCK);
             }
+            set_frame_rotation(p, c->inv_freq_t.data());
             hipError_t e = launch_append(p, s);
             if (e != hipSuccess) return hip_fail(e, "clip cache-write kernel launch");
         }

@@ -91,14 +91,14 @@ ll_status ll_prompt_recache(ll_prompt* prompt, int layer, const void* k, const v
     if (!prompt->dev && (k || v)) return fail(LL_ERR_INVALID_ARG, "index-only handle takes null tensors");
     if (!aligned16(k, v)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
     if (prompt->dev) {
-        // The cache-write kernel of ll_chunk_append with one "frame" of n_tokens tokens at slot 0, no queries, and a
-        // rotary step whose every pair is on the frame axis at frequency zero: (cos, sin) = (1, 0), the keys pass
-        // unchanged bit for bit.
+        // The cache-write kernel of ll_chunk_append with one "frame" of n_tokens tokens at slot 0, no queries, and
+        // its rotary step switched off: the keys pass unchanged bit for bit.
         AppendParams p{};
         p.k = static_cast<const uint16_t*>(k); p.v = static_cast<const uint16_t*>(v);
         p.k_cache = prompt_k(prompt, layer); p.v_cache = prompt_v(prompt, layer);
         p.head_stride = prompt->head_stride;
         p.rope = RopeTables{prompt->zero_freq, nullptr, nullptr, prompt->D / 2, 0, 0};
+        p.identity = 1;
         p.H = prompt->H; p.D = prompt->D; p.P = n_tokens; p.grid_w = n_tokens;
         p.n_frames = 1;
         p.frame[0] = 0; p.slot[0] = 0;

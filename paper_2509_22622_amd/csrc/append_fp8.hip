@@ -50,11 +50,7 @@ __global__ __launch_bounds__(256) void ll_append8_kernel(const AppendParams p) {
     const int ntok = k_hi - k_lo;
     const int tok0 = int(s_begin - slot0);                         // token inside the frame
 
-    if (tid < p.rope.n_t) {
-        double sn, cs;
-        sincos(double(p.frame[fi]) * p.rope.inv_freq_t[tid], &sn, &cs);
-        t_cs[tid] = make_float2(float(cs), float(sn));
-    }
+    if (tid < p.rope.n_t) t_cs[tid] = p.t_cs[fi][tid];           // frame-axis (cos, sin), made on the host in double
     __syncthreads();
 
     const int64_t row0 = int64_t(fi) * p.P + tok0;                 // first input row
@@ -138,6 +134,7 @@ __global__ __launch_bounds__(256) void ll_append8_kernel(const AppendParams p) {
 hipError_t launch_append8(const AppendParams& p, hipStream_t s) {
     const int nseg = p.seg_begin[p.n_frames];
     if (nseg <= 0) return hipSuccess;
+    if (p.n_frames > MAX_APPEND_FRAMES || p.rope.n_t > MAX_T_PAIRS) return hipErrorInvalidValue;
     dim3 grid(nseg, p.H), block(256);
     if (p.D == 128) hipLaunchKernelGGL(ll_append8_kernel<128>, grid, block, 0, s, p);
     else if (p.D == 64) hipLaunchKernelGGL(ll_append8_kernel<64>, grid, block, 0, s, p);

@@ -14,6 +14,7 @@
 // A head's K region is `kblocks_alloc` kblocks long, followed by its V region.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <cmath>
 #include <cstdint>
 
 namespace ll {
@@ -22,7 +23,9 @@ constexpr int KBLOCK = 32;          // key slots per kblock
 constexpr int PAD_KBLOCKS = 8;      // readable padding after the last kblock of a head
 constexpr int MAX_RANGES = 3;
 constexpr int MAX_ATTN_CHUNKS = 16; // query chunks per attention launch
-constexpr int MAX_APPEND_FRAMES = 32;
+constexpr int MAX_APPEND_FRAMES = 8;  // frames per cache-write launch (its argument block carries a rotary table per frame)
+constexpr int MAX_CHUNK_FRAMES = 32;  // largest chunk (ll_chunk_append splits longer runs of frames into several launches)
+constexpr int MAX_T_PAIRS = 24;       // frame-axis rotary pairs: 22 at head_dim 128, 12 at 64
 constexpr int MAX_XCD_GROUPS = 256; // (head, chunk) groups an attention launch can place on the XCDs one by one
 __host__ __device__ inline int swap23(int i) {
     return (i & ~12) | ((i & 4) << 1) | ((i & 8) >> 1);
@@ -72,13 +75,27 @@ struct AppendParams {
     RopeTables rope;
     int H, D, P, grid_w;
     int n_frames;
-    int64_t frame[MAX_APPEND_FRAMES];                           // absolute frame index
+    int64_t frame[MAX_APPEND_FRAMES];                           // absolute frame index (host side: input of set_frame_rotation)
+    // (cos, sin) of frame * frequency for every frame-axis pair of every frame, computed on the host in double
+    // (set_frame_rotation): the kernels run no trigonometry.  identity != 0: no rotary step at all (every pair
+    // passes unchanged; q, where given, only takes q_scale) - the tables are not read then.
+    float2 t_cs[MAX_APPEND_FRAMES][MAX_T_PAIRS];
+    int identity;
     int64_t slot[MAX_APPEND_FRAMES];                            // first token slot
     int seg_begin[MAX_APPEND_FRAMES + 1];                       // prefix sum of kblock segments (32 or 64 slots)
     // 8-bit cache (all null / unused for the bf16 cache): byte pointers, head_stride in bytes
     uint8_t* q8_out; uint8_t* k8_cache; uint8_t* v8_cache;
     float k_mul, v_mul;                                         // 2^-k_exp, 2^-v_exp (q_scale carries 2^k_exp)
 };
+
+// Fill p.t_cs from p.frame[0 .. n_frames) and the host copy of the frame-axis frequencies (p.rope.n_t of them).
+inline void set_frame_rotation(AppendParams& p, const double* inv_freq_t_host) {
+    for (int i = 0; i < p.n_frames; ++i)
+        for (int j = 0; j < p.rope.n_t && j < MAX_T_PAIRS; ++j) {
+            const double a = double(p.frame[i]) * inv_freq_t_host[j];
+            p.t_cs[i][j] = make_float2(float(std::cos(a)), float(std::sin(a)));
+        }
+}
 
 struct AttnChunk {
     int q_begin, q_end;          // query rows [q_begin, q_end) of the q tensor
