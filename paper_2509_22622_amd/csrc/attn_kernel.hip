@@ -299,7 +299,9 @@ int attn_variant_default(int D, int kblock) {
 int attn_variant_qtile(int v) { return variant(v)->qtile; }
 bool attn_variant_supports(int v, int D, int kblock) { return variant(v) && variant(v)->D == D && variant(v)->kblock == kblock; }
 // only the software-pipelined bf16 kernels take queries turned back for the sink range (AttnChunk::sink_shift)
-bool attn_variant_sink_shift(int v) { return (v > kNumSimple && v <= kNumSimple + 2) || (is_stream16(v) && v < first_stream16() + 2); }
+bool attn_variant_sink_shift(int v) {
+    return (v > kNumSimple && v <= kNumSimple + 2) || (is_stream16(v) && (v < first_stream16() + 2 || v >= first_stream16() + 6));
+}
 // the software-pipelined kernel that multiplies the queries by AttnParams::scale_log2e itself
 int attn_variant_qscale(int D) { return first_stream16() + (D == 128 ? 2 : 3); }
 int attn_variant_lse(int D) { return first_stream16() + (D == 128 ? 4 : 5); }

@@ -41,6 +41,9 @@ typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float S16_RESCALE_SLACK = 6.0f;        // log2 units: p stays below 2^6 between rescales
 constexpr int S16_THREADS = 512;
+// Fixed-reference pass: a row sum above this (weights of 2^(score - reference), reference = largest score of the first
+// kblock) sends the tile to the pass that follows the maximum.  Far below what fp32 sums and bf16 weights can hold.
+constexpr float S16_FIXED_REF_LIMIT = 0x1p48f;
 
 __device__ __forceinline__ unsigned s16_pack_bf16(float a, float b) {
     f32x2 v = {a, b};
@@ -120,10 +123,17 @@ __device__ __forceinline__ unsigned s16_k_load_offset(int lane) {
 }
 
 // Virtual kblocks [vb, ve) of chunk `ch` for the 32 queries starting at row q0 of head `head`.
-template <int D, bool QSCALE>
+// SCHED selects where a step's vector and LDS work sits (bit 0: exponentials of the second query block moved behind
+// the S^T slots; bit 1: one LDS fragment read per slot instead of two in half of the slots; bit 2: no issue priority)
+// and, bit 3, whether the reference is fixed: the scores' running maximum is then not followed at all (no max3, no
+// vote, no rescaling), the reference stays at the first kblock's maximum, and the caller must look at the row sums
+// afterwards: a sum beyond S16_FIXED_REF_LIMIT (or not a number) means some score rose far above the reference, and
+// the tile has to be computed again with the reference followed.
+template <int D, bool QSCALE, int SCHED>
 __device__ __forceinline__ void s16_segment(const AttnParams& p, const AttnChunk& ch, int head, int q0, int vb, int ve,
                                             char* lds, S16State<D>& st, const float2* shift_cs) {
-    using Plan = LdsPlan16<D>;
+    using Plan = LdsPlan16<D, (SCHED & 2) != 0>;
+    constexpr bool TRACK = !(SCHED & 8);
     constexpr int KS = Plan::KS;                // K fragments per kblock = S^T slots (two MFMAs each)
     constexpr int NV = Plan::NV;                // V^T fragments per kblock = O^T slots (two MFMAs each)
     constexpr int NQ = D / 32;                  // contraction steps of S^T
@@ -309,15 +319,17 @@ __device__ __forceinline__ void s16_segment(const AttnParams& p, const AttnChunk
             if (edge) {                                                                                             \
                 next_edge = s16_next_edge((I), n0, n01, T);                                                         \
                 mask_s(S_CUR, S16_LIVE(I));                                                                         \
-                mx[0] = max_s(S_CUR, 0);                                                                            \
-                mx[1] = max_s(S_CUR, 1);                                                                            \
+                if (TRACK) {                                                                                        \
+                    mx[0] = max_s(S_CUR, 0);                                                                        \
+                    mx[1] = max_s(S_CUR, 1);                                                                        \
+                }                                                                                                   \
                 if (sink_shift != 0 && (I) == n0 - 1) {     /* the sink ends here: back to the unturned queries */  \
                     _Pragma("unroll") for (int qb = 0; qb < 2; ++qb)                                                \
                         _Pragma("unroll") for (int s = 0; s < NQ; ++s)                                              \
                             qf[qb][s] = *reinterpret_cast<const bf16x8*>(q_src[qb] + s * 32);                       \
                 }                                                                                                   \
             }                                                                                                       \
-            _Pragma("unroll") for (int qb = 0; qb < 2; ++qb) {                                                      \
+            if (TRACK) _Pragma("unroll") for (int qb = 0; qb < 2; ++qb) {                                           \
                 const float delta = fmaxf(col_max(mx[qb]), 0.f);                                                    \
                 const float alpha = __builtin_amdgcn_exp2f(-delta);                                                 \
                 mref[qb] += delta;                                                                                  \
@@ -335,8 +347,8 @@ __device__ __forceinline__ void s16_segment(const AttnParams& p, const AttnChunk
         unsigned pb[2][4];                                                                                          \
         float m_run[2] = {-INFINITY, -INFINITY};                                                                    \
         _Pragma("unroll") for (int k = 0; k < NSLOT; ++k) {                                                         \
-            if (k == 0) __builtin_amdgcn_s_setprio(1);                                                              \
-            if (k == KS) __builtin_amdgcn_s_setprio(0);                                                             \
+            if (k == 0 && !(SCHED & 4)) __builtin_amdgcn_s_setprio(1);                                              \
+            if (k == KS && !(SCHED & 4)) __builtin_amdgcn_s_setprio(0);                                             \
             if (k < KS) {                                                                                           \
                 const int m = k & 1, s = k >> 1;                                                                    \
                 s16_lds_wait_n(kfr[k], Plan::wait_k(k));                                                            \
@@ -361,7 +373,9 @@ __device__ __forceinline__ void s16_segment(const AttnParams& p, const AttnChunk
                 issue_load(S16_PHYS_KB(v), ((I) + PF) & (NS - 1), (k - DMA_FIRST) / DMA_STEP);                      \
             }                                                                                                       \
             _Pragma("unroll") for (int j = 0; j < NPAIR; ++j) {                                                     \
-                const int qb = j / 4, w = j % 4, e = (j * SPAN) / NPAIR;                                            \
+                const int qb = j / 4, w = j % 4;                                                                    \
+                const int e = !(SCHED & 1) ? (j * SPAN) / NPAIR                                                     \
+                              : (qb == 0 ? (w * (KS - 1)) / 4 : KS - 1 + (w * (HV - 1)) / 3);                       \
                 if (k == e) {                                                                                       \
                     d0[j] = __builtin_amdgcn_exp2f(S_CUR[w >> 1][qb][2 * (w & 1)]);                                 \
                     d1[j] = __builtin_amdgcn_exp2f(S_CUR[w >> 1][qb][2 * (w & 1) + 1]);                             \
@@ -377,7 +391,7 @@ __device__ __forceinline__ void s16_segment(const AttnParams& p, const AttnChunk
                     S16_PIN(lsum[qb][1]);                                                                           \
                 }                                                                                                   \
             }                                                                                                       \
-            if (k >= MAX_FIRST) {                                                                                   \
+            if (TRACK && k >= MAX_FIRST) {                                                                          \
                 const int qb = (k - MAX_FIRST) >> 1, m = (k - MAX_FIRST) & 1;                                       \
                 m_run[qb] = fmaxf(fmaxf(m_run[qb], S_NEXT[m][qb][0]), S_NEXT[m][qb][1]);                            \
                 m_run[qb] = fmaxf(fmaxf(m_run[qb], S_NEXT[m][qb][2]), S_NEXT[m][qb][3]);                            \
@@ -392,9 +406,11 @@ __device__ __forceinline__ void s16_segment(const AttnParams& p, const AttnChunk
                 mask_v(vfr, S16_LIVE(I));                                                                           \
             }                                                                                                       \
         }                                                                                                           \
-        mx[0] = m_run[0];                                                                                           \
-        mx[1] = m_run[1];                                                                                           \
-        vote = __any(fmaxf(mx[0], mx[1]) > S16_RESCALE_SLACK);                                                      \
+        if (TRACK) {                                                                                                \
+            mx[0] = m_run[0];                                                                                       \
+            mx[1] = m_run[1];                                                                                       \
+            vote = __any(fmaxf(mx[0], mx[1]) > S16_RESCALE_SLACK);                                                  \
+        }                                                                                                           \
         if (BAR == 1 || (BAR == 2 && RingPlan::barrier_after((I) - vb))) {                                          \
             s16_wait_vmcnt<(PF - LAND) * LPW>();                                                                    \
             __builtin_amdgcn_s_barrier();                                                                           \
@@ -479,7 +495,7 @@ __device__ __forceinline__ void s16_segment_loads_only(const AttnParams& p, cons
 }
 
 // ---- one workgroup per (head, query tile): placement on the XCDs as in attn_stream.hip
-template <int D, bool QSCALE, bool LSE>
+template <int D, bool QSCALE, bool LSE, int SCHED = 0>
 __global__ __launch_bounds__(S16_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2))) void ll_attn_stream16_kernel(const AttnParams p) {
     extern __shared__ __attribute__((aligned(16))) char lds[];
     __shared__ float2 shift_cs[64];
@@ -519,12 +535,22 @@ __global__ __launch_bounds__(S16_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     }
     const int row_block = ((wave & 3) << 1) | (wave >> 2);      // waves w and w + 4 (one SIMD) take neighbouring blocks
     const int q0 = ch.q_begin + (tile - ch.tile_begin) * 256 + row_block * 32;
-    if (q0 >= ch.q_end) {                        // wave-uniform: this wave has no rows in the chunk's last tile
-        s16_segment_loads_only<D>(p, ch, head, 0, ch.n_kblocks, lds);
-        return;
-    }
+    // wave-uniform: a wave without rows in the chunk's last tile only takes its share of the loads and barriers
+    const bool has_rows = q0 < ch.q_end;
     S16State<D> st;
-    s16_segment<D, QSCALE>(p, ch, head, q0, 0, ch.n_kblocks, lds, st, shift_cs);
+    if (has_rows) s16_segment<D, QSCALE, SCHED>(p, ch, head, q0, 0, ch.n_kblocks, lds, st, shift_cs);
+    else s16_segment_loads_only<D>(p, ch, head, 0, ch.n_kblocks, lds);
+    if constexpr ((SCHED & 8) != 0) {
+        // the pass above kept its first reference: fine unless some row's sum ran away (a score far above the first
+        // kblock's maximum); then the whole workgroup (the waves share the ring and its barriers) takes the tile again
+        // with the reference followed.  The barrier inside the vote also ends every wave's reads of the first pass.
+        const bool ran_away = has_rows && !(st.l[0] < S16_FIXED_REF_LIMIT && st.l[1] < S16_FIXED_REF_LIMIT);
+        if (__syncthreads_or(ran_away)) {
+            if (has_rows) s16_segment<D, QSCALE, SCHED & ~8>(p, ch, head, q0, 0, ch.n_kblocks, lds, st, shift_cs);
+            else s16_segment_loads_only<D>(p, ch, head, 0, ch.n_kblocks, lds);
+        }
+    }
+    if (!has_rows) return;
 
     // out[row][head][16 dq + 4 g + j] = O^T block (dq, qb) register j, divided by the row sum
     const int lane = threadIdx.x & 63, n = lane & 15, g = lane >> 4;
@@ -556,14 +582,22 @@ __global__ __launch_bounds__(S16_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
     }
 }
 
+// Default schedule: exponentials of the second query block behind the S^T slots, and the reference kept fixed with
+// the second, maximum-following pass as the fallback (SCHED 9).  The *_tracked variants follow the maximum throughout.
+constexpr int S16_DEFAULT = 9, S16_TRACKED = 1;
+#define S16_ENTRY(name, D, QS, LSE, SCHED) \
+    {name, D, 256, 8 * 2 * KBLOCK * D * 2, ll_attn_stream16_kernel<D, QS, LSE, SCHED>, S16_THREADS, KBLOCK}
 const AttnVariant kStream16Variants[] = {
-    {"d128_stream16", 128, 256, 8 * 2 * KBLOCK * 128 * 2, ll_attn_stream16_kernel<128, false, false>, S16_THREADS, KBLOCK},
-    {"d64_stream16", 64, 256, 8 * 2 * KBLOCK * 64 * 2, ll_attn_stream16_kernel<64, false, false>, S16_THREADS, KBLOCK},
-    {"d128_stream16_qscale", 128, 256, 8 * 2 * KBLOCK * 128 * 2, ll_attn_stream16_kernel<128, true, false>, S16_THREADS, KBLOCK},
-    {"d64_stream16_qscale", 64, 256, 8 * 2 * KBLOCK * 64 * 2, ll_attn_stream16_kernel<64, true, false>, S16_THREADS, KBLOCK},
-    {"d128_stream16_lse", 128, 256, 8 * 2 * KBLOCK * 128 * 2, ll_attn_stream16_kernel<128, false, true>, S16_THREADS, KBLOCK},
-    {"d64_stream16_lse", 64, 256, 8 * 2 * KBLOCK * 64 * 2, ll_attn_stream16_kernel<64, false, true>, S16_THREADS, KBLOCK},
+    S16_ENTRY("d128_stream16", 128, false, false, S16_DEFAULT),
+    S16_ENTRY("d64_stream16", 64, false, false, S16_DEFAULT),
+    S16_ENTRY("d128_stream16_qscale", 128, true, false, S16_DEFAULT),
+    S16_ENTRY("d64_stream16_qscale", 64, true, false, S16_DEFAULT),
+    S16_ENTRY("d128_stream16_lse", 128, false, true, S16_DEFAULT),
+    S16_ENTRY("d64_stream16_lse", 64, false, true, S16_DEFAULT),
+    S16_ENTRY("d128_stream16_tracked", 128, false, false, S16_TRACKED),
+    S16_ENTRY("d64_stream16_tracked", 64, false, false, S16_TRACKED),
 };
+#undef S16_ENTRY
 const int kNumStream16Variants = sizeof(kStream16Variants) / sizeof(kStream16Variants[0]);
 
 }  // namespace ll

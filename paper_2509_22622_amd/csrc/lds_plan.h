@@ -42,12 +42,13 @@ struct LdsPlan {
 // KS + NV / 2 + j the same two for the second.  Reads are issued as above (V^T fragment f in slot f / 2, K fragment
 // f of the next kblock in slot KS + f / 2, after the slot's MFMAs, V^T before K, in fragment order).  A fragment is
 // waited for at its first use only; the younger of a slot's two V^T fragments carries the wait for both.
-template <int D>
+// SPREAD: one read per slot instead (V^T fragment f in slot f, K fragment f in slot KS + f).
+template <int D, bool SPREAD = false>
 struct LdsPlan16 {
     static constexpr int KS = D / 16;
     static constexpr int NV = D / 16;
-    static constexpr int vslot(int f) { return f / 2; }
-    static constexpr int kslot(int f) { return KS + f / 2; }
+    static constexpr int vslot(int f) { return SPREAD ? f : f / 2; }
+    static constexpr int kslot(int f) { return SPREAD ? KS + f : KS + f / 2; }
     static constexpr int first_use_v(int f) { return KS + f / 2; }            // slot of the first query block
     static constexpr int last_use_v(int f) { return KS + NV / 2 + f / 2; }    // slot of the second query block
     // Reads issued after V^T fragment 2 j + 1 when slot KS + j starts.

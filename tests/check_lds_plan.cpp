@@ -58,9 +58,9 @@ int check() {
 // The same replay for the plan of the 16x16x32 form (LdsPlan16): slot k < KS consumes K fragment k; slot KS + j
 // (j < NV / 2) consumes V^T fragments 2 j and 2 j + 1 under ONE wait placed on the younger of the two; slot
 // KS + NV / 2 + j uses the same two again without a wait.
-template <int D>
+template <int D, bool SPREAD>
 int check16() {
-    using P = ll::LdsPlan16<D>;
+    using P = ll::LdsPlan16<D, SPREAD>;
     constexpr int KS = P::KS, NV = P::NV, NSLOT = KS + NV, HV = NV / 2;
     std::deque<int> issued;
     auto position_from_youngest = [&](int id) {
@@ -111,7 +111,7 @@ int check16() {
 
 int main() {
     if (check<64>() || check<128>()) return 1;
-    if (check16<64>() || check16<128>()) return 1;
+    if (check16<64, false>() || check16<128, false>() || check16<64, true>() || check16<128, true>()) return 1;
     std::printf("lds plan ok\n");
     return 0;
 }

@@ -52,4 +52,4 @@ def test_bf16_stream_kernels_do_not_spill(source, kernel):
         text = open(out).read()
     spills = dict(re.findall(r"\.name:\s+(\S+)[\s\S]*?\.vgpr_spill_count:\s+(\d+)", text))
     stream = {k: int(v) for k, v in spills.items() if kernel + "I" in k}
-    assert len(stream) == 6 and all(v == 0 for v in stream.values()), f"spills: {stream}"
+    assert len(stream) >= 6 and all(v == 0 for v in stream.values()), f"spills: {stream}"

@@ -113,6 +113,57 @@ def test_peaky_softmax():
     _stream_and_check(ODD64, 6, q_scale=6.0, check_cache=False)
 
 
+@pytest.mark.parametrize("jump", [30.0, 200.0, 3000.0])
+def test_a_late_key_far_above_the_first_kblocks_scores(jump):
+    """The default kernel keeps the first kblock's maximum as its reference and only looks at the row sums at the end
+    of a tile; a score far above that reference must send the tile through the pass that follows the maximum.  Keys:
+    N(0,1) everywhere but one key in the fourth kblock of the second chunk that is `jump` times the query of row 5,
+    normalised: that row's logit for it exceeds every other by about jump * |q| / sqrt(D) (2^200 and more as a
+    weight), the other rows see it as one more random key."""
+    w = MID128
+    cache, oracle, marked = H.make_cache(w), Oracle(H.oracle_cfg(w)), Oracle(H.oracle_cfg(w))
+    tok, v_absmax = 100, 0.0
+    for i in range(3):
+        q, k, v = synth.chunk_qkv(w, 0, i)
+        v_marked = v
+        if i == 1:
+            # un-rotated key = a multiple of the un-rotated query at the same token position: the rotary step keeps them aligned
+            qf = synth.bf16_bits_to_f32(q[tok, :, :])
+            k[tok, :, :] = synth.f32_to_bf16_bits(qf * np.float32(jump / 8.0))
+            v_marked = v.copy()
+            v_marked[tok, :, :] = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(v[tok]) + np.float32(1000.0))
+        qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+        qr, out = torch.empty_like(qd), torch.empty_like(qd)
+        cache.chunk_append(0, 3 * i, 3, qd, kd, vd, qr)
+        cache.sink_window_attn(0, qr, out)
+        torch.cuda.synchronize()
+        oracle.append(0, 3 * i, q, k, v)
+        marked.append(0, 3 * i, q, k, v_marked)
+        want = oracle.attn(0)
+        got = bf16_bits_to_f64(H.to_bits(out))
+        assert np.isfinite(got).all()
+        if i == 1:
+            # row `tok` of chunk 1 puts (nearly) all its weight on its own key: the output is that key's value row
+            vrow = bf16_bits_to_f64(v[tok])
+            if jump >= 200:
+                assert np.abs(want[tok] - vrow).max() < 1e-6
+                assert np.abs(got[tok] - vrow).max() <= 2.0 ** -8 * np.abs(vrow).max()
+        # (row, head) pairs that give the large key no weight (the oracle's output does not move when that key's value
+        # row does) are ordinary rows and must meet the graded tolerances; the others depend on a logit whose bf16
+        # storage error alone exceeds them
+        calm = np.abs(marked.attn(0) - want).max(axis=2) < 1e-4          # weight below 1e-7
+        if i == 0:
+            assert calm.all()
+        if jump >= 200:
+            assert calm.sum() > calm.size // 8
+        if calm.any():
+            H.assert_parity(H.to_bits(out)[calm], want[calm], f"late dominant key x{jump}, chunk {i}")
+        # and every output, calm or not, is a convex combination of value rows
+        v_absmax = max(v_absmax, np.abs(bf16_bits_to_f64(v)).max())
+        assert np.abs(got).max() <= v_absmax * (1 + 2.0 ** -7)
+    cache.close()
+
+
 @pytest.mark.parametrize("q_scale", [16.0, 64.0, 256.0])
 def test_extreme_logits_stay_finite_and_convex(q_scale):
     """Logits of std 16 to 256 (softmax close to one-hot, the reference maximum jumps by far more than the slack in
