@@ -17,9 +17,11 @@ if ROOT not in sys.path:
 
 PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk x 2.4 GHz
 PEAK_HBM_GBS = 8000.0
-# HBM bytes per attention launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (profiles/attn_wan_layer_pmc.txt):
-# fetch 100814 KiB x 2.0 (scale from a 1 GiB device copy) + write 14170 KiB x 1.0
+# HBM bytes per attention launch: a constant recorded from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
+# workload (profiles/attn_wan_layer_pmc.txt), not measured by the run that prints it:
+# fetch 100814 KiB x 2.0 (scale from a device copy of known size in the same run) + write 14170 KiB x 1.0
 ATTN_HBM_TRAFFIC_BYTES = int(100814 * 1024 * 2.0 + 14170 * 1024 * 1.0)
+ATTN_HBM_TRAFFIC_SOURCE = "profiles/attn_wan_layer_pmc.txt (recorded constant: 1.28 x the algorithmic bytes, 16 (head, XCD) K/V streams for 12 heads)"
 
 
 def attn_flops(nq, nk, d, h):
@@ -63,6 +65,30 @@ def cpu_baseline(w, chunks=3):
 
 
 PEAK_FP8_TFLOPS = 2 * PEAK_BF16_TFLOPS      # dense fp8 MFMA peak (published: 5.0 PFLOP/s)
+
+
+def copy_reference(nbytes, pool=10, reps=3):
+    """Median time of a plain device-to-device copy of `nbytes` (read) + `nbytes` (written), each copy from and to
+    buffers not touched since more than 256 MB of other traffic (HIP events around every copy, as around the appends)."""
+    import torch
+    src = [torch.full((nbytes,), i, dtype=torch.uint8, device="cuda") for i in range(pool)]
+    dst = [torch.empty(nbytes, dtype=torch.uint8, device="cuda") for _ in range(pool)]
+    t = []
+    for rep in range(reps + 1):
+        ev = []
+        for i in range(pool):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            dst[i].copy_(src[i])
+            b.record()
+            ev.append((a, b))
+        torch.cuda.synchronize()
+        if rep:
+            t += [a.elapsed_time(b) * 1e3 for a, b in ev]
+    t.sort()
+    med = t[len(t) // 2]
+    return {"bytes_read": nbytes, "bytes_written": nbytes, "us_median": round(med, 2),
+            "GBps": round(2 * nbytes / (med * 1e-6) / 1e9, 1), "copies": len(t)}
 
 
 def single_layer_stats(w, gen, warmup=10, iters=50, kv_format="bf16", sink_relative=False):
@@ -334,8 +360,6 @@ def main():
     ap.add_argument("--no-fp8", action="store_true", help="leave out the figures of the 8-bit cache variant")
     ap.add_argument("--fp8-only", action="store_true",
                     help="only the 30-layer step over the 8-bit cache (for profiler runs: one launch shape)")
-    ap.add_argument("--probe-issue", action="store_true",
-                    help="only run the library's MFMA probe with each kind of companion instruction and print a table")
     ap.add_argument("--prompt-only", action="store_true",
                     help="only the prompt side (cross-attention over the prompt, prompt switch), for profiler runs")
     ap.add_argument("--clip-only", action="store_true",
@@ -344,8 +368,6 @@ def main():
                     help="skip the graph replay, the single-layer statistics and the MFMA probe (for profiler runs)")
     ap.add_argument("--full-loop", action="store_true",
                     help="also run 60 consecutive chunks from an empty cache (30 layers), with a time per chunk")
-    ap.add_argument("--probe-copy", action="store_true",
-                    help="also run a plain 1 GiB device copy (reference for scaling rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (--gpus 1); heads are independent, so the path would shard by head")
@@ -358,30 +380,6 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     binding.set_attn_variant(args.variant)
-    if args.probe_issue:
-        for random_ops in (False, True):
-            print(f"operands: {'random bf16 mantissas and signs' if random_ops else 'constant 1.0'}")
-            binding.probe_mfma_mix(0, 1, random_operands=random_ops)          # let the clock settle
-            base, base_clk = binding.probe_mfma_mix(0, 1, random_operands=random_ops)
-            print(f"  {'companion':32s} per MFMA   TFLOP/s   clock GHz   vs none   matrix cycles lost per companion")
-            print(f"  {'none':32s}    -      {base:8.1f}   {base_clk:8.3f}")
-            for kind, name in binding.PROBE_COMPANIONS.items():
-                if kind == 0:
-                    continue
-                for per in ((1,) if kind == 7 else (1, 2)):
-                    t, c = binding.probe_mfma_mix(kind, per, random_operands=random_ops)
-                    # a 32x32x16 MFMA holds the pipe 32 cycles: time per MFMA grows by 32 * (base / t - 1) cycles
-                    lost = "" if kind == 7 else f"{32.0 * (base / t - 1.0) / per:8.2f}"
-                    print(f"  {name:32s}    {per}      {t:8.1f}   {c:8.3f}   {t / base:7.3f}   {lost}")
-            print(f"  fp8 MFMAs (32x32x64, 64 cycles each), {'random E4M3 mantissas and signs' if random_ops else 'constant 1.0'}")
-            binding.probe_mfma_mix(8, 1, random_operands=random_ops)
-            base8 = None
-            for kind, name in binding.PROBE_FP8_KINDS.items():
-                t, c = binding.probe_mfma_mix(kind, 1, random_operands=random_ops)
-                base8 = base8 or t
-                print(f"  {name:58s} {t:8.1f}   {c:8.3f}   {t / base8:7.3f}")
-        return
-
     w = synth.WAN_LOOP
     L, Hh, D, P, Cf = w.layers, w.heads, w.head_dim, w.tokens_per_frame, w.chunk_frames
     nq = w.chunk_tokens
@@ -466,18 +464,17 @@ def main():
         "append_GBps": round(append_bytes / (append_ms * 1e-3) / 1e9, 1),
         "roofline": {"bound": "mfma", "kernel": "ll_attn_stream16_kernel<128, false, false>", "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": ATTN_HBM_TRAFFIC_BYTES,
+                     "traffic_source": ATTN_HBM_TRAFFIC_SOURCE,
                      "flops_per_launch": fl_layer, "avg_launch_ms": round(attn_ms, 4),
                      "algorithmic_bytes": (2 * nq + 2 * nk) * Hh * D * 2},
     }
 
+    # What a plain device copy of the append's bytes achieves from buffers that are in no cache: the practical bound
+    # of the memory-bound append (and, under rocprofv3 --pmc, the dispatch of known size that scales the counters).
+    res["append_copy_reference"] = copy_reference(append_bytes // 2)
+    res["append_vs_copy_reference"] = round(res["append_copy_reference"]["us_median"] / (append_ms * 1e3), 3)
+
     if args.no_extras:
-        if args.probe_copy:
-            src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(3)
-            dst = torch.empty_like(src)
-            for _ in range(3):
-                dst.copy_(src)
-            torch.cuda.synchronize()
-            res["probe_copy_bytes"] = int(src.numel())
         print(json.dumps(res))
         return
 
@@ -569,14 +566,6 @@ def main():
 
     if not args.no_fp8:
         res["fp8_cache"] = fp8_cache_stats(w, gen, q, k, v, args.steps, variant=args.variant)
-
-    if args.probe_copy:
-        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(3)
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        res["probe_copy_bytes"] = int(src.numel())
 
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(synth.WAN_LAYER)
