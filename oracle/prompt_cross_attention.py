@@ -15,9 +15,17 @@ Readings (the paper gives no formulas for this layer): scale 1/sqrt(D); the prom
 prompt to the next and tokens of an earlier, longer prompt must leave no trace; the projections that produce q, k and
 v belong to the model and are inputs here.
 
+The layer's output path (Fig. 2, right: the cross-attention block's result goes back into the video tokens' stream)
+is the plain output projection of a multi-head attention: the heads' outputs of a token are concatenated and
+multiplied by the layer's output weight, y = concat_heads(o) W^T with W [H*D, H*D] stored as a linear layer stores it
+([output feature][input feature]).  No bias here (a bias is an addition the caller can make); the weight belongs to
+the model and is an input.
+
 Pins (tests/test_oracle_pins.py): loops on tiny inputs, a library's scaled-dot-product attention, closed forms (one
 token; equal keys give the mean of the values; a dominant key), invariance under a permutation of the prompt's
-tokens, and independence from the replaced prompt.
+tokens, and independence from the replaced prompt; for the output projection: scalar loops, a library's linear
+layer, the identity weight (returns the concatenated heads), a permutation weight (moves features, bit for bit),
+linearity, and a weight that reads one head only.
 """
 from __future__ import annotations
 
@@ -39,6 +47,19 @@ def cross_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray) -> np.ndarray:
         w /= w.sum(axis=1, keepdims=True)
         out[:, h, :] = w @ v[:, h, :]
     return out
+
+
+def out_projection(o: np.ndarray, w: np.ndarray) -> np.ndarray:
+    """y[t, n] = sum over (h, d) of o[t, h, d] * w[n, h * D + d].  o [Nq, H, D]; w [H*D, H*D]; returns [Nq, H*D]."""
+    o, w = np.asarray(o, dtype=np.float64), np.asarray(w, dtype=np.float64)
+    nq, heads, d = o.shape
+    assert w.shape == (heads * d, heads * d)
+    return o.reshape(nq, heads * d) @ w.T
+
+
+def cross_attention_out(q, k, v, w) -> np.ndarray:
+    """The cross-attention block's output: attention over the prompt, then the output projection."""
+    return out_projection(cross_attention(q, k, v), w)
 
 
 class PromptOracle:

@@ -742,6 +742,51 @@ def test_cross_attention_ignores_token_order():
 
 
 # P23: after a switch nothing of the former prompt is left, also when the new prompt is shorter
+def test_out_projection_loops_library_and_closed_forms():
+    """y = concat_heads(o) W^T (Sec. 3.1, Fig. 2 right: the cross-attention block's output path)."""
+    from oracle.prompt_cross_attention import cross_attention_out, out_projection
+    rng = np.random.default_rng(77)
+    nq, H, D = 5, 3, 4
+    o = rng.standard_normal((nq, H, D))
+    w = rng.standard_normal((H * D, H * D))
+    got = out_projection(o, w)
+    # scalar loops: output feature n of token t sums o[t, h, d] * w[n, h * D + d]
+    for t in range(nq):
+        for n in range(H * D):
+            acc = 0.0
+            for h in range(H):
+                for d in range(D):
+                    acc += o[t, h, d] * w[n, h * D + d]
+            assert abs(got[t, n] - acc) < 1e-13
+    # a library's linear layer (weight stored [out, in])
+    ref = torch.nn.functional.linear(torch.from_numpy(o.reshape(nq, H * D)), torch.from_numpy(w)).numpy()
+    assert np.abs(got - ref).max() < 1e-13
+    # identity weight: the heads side by side, bit for bit; a permutation weight moves features, bit for bit
+    assert np.array_equal(out_projection(o, np.eye(H * D)), o.reshape(nq, H * D))
+    perm = rng.permutation(H * D)
+    pw = np.zeros((H * D, H * D))
+    pw[np.arange(H * D), perm] = 1.0                    # y[n] = x[perm[n]]
+    assert np.array_equal(out_projection(o, pw), o.reshape(nq, H * D)[:, perm])
+    # a transposed weight is a different map (guards the [out][in] convention)
+    assert np.abs(out_projection(o, w.T) - got).max() > 0.1
+    # linear in o and in w
+    o2 = rng.standard_normal((nq, H, D))
+    assert np.abs(out_projection(2.0 * o + o2, w) - (2.0 * got + out_projection(o2, w))).max() < 1e-12
+    # a weight whose columns outside head 1 are zero reads head 1 only
+    w1 = w.copy()
+    w1[:, :D] = 0.0
+    w1[:, 2 * D:] = 0.0
+    o_other = o.copy()
+    o_other[:, 0] += 5.0
+    o_other[:, 2] -= 3.0
+    assert np.abs(out_projection(o, w1) - out_projection(o_other, w1)).max() < 1e-12
+    # the whole block: attention over the prompt, then the projection
+    q, k, v = rng.standard_normal((nq, H, D)), rng.standard_normal((7, H, D)), rng.standard_normal((7, H, D))
+    att = torch.nn.functional.scaled_dot_product_attention(*(torch.from_numpy(a).permute(1, 0, 2) for a in (q, k, v)))
+    ref = torch.nn.functional.linear(att.permute(1, 0, 2).reshape(nq, H * D), torch.from_numpy(w)).numpy()
+    assert np.abs(cross_attention_out(q, k, v, w) - ref).max() < 1e-12
+
+
 def test_prompt_recache_replaces_everything():
     L, H, D = 2, 2, 8
     q = _randn((5, H, D), 64)
