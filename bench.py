@@ -174,6 +174,24 @@ def prompt_side_stats(w, gen, n_text=512, reps=10):
                      "TFLOP/s": round(fl / (ms * 1e-3) / 1e12, 1),
                      "pct_of_bf16_mfma_peak": round(100 * fl / (ms * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
                      "algorithmic_GBps": round(by / (ms * 1e-3) / 1e9, 1)}
+        # the block's whole output path: attention, then y = concat_heads(out) w^T with one weight per layer
+        n = Hh * D
+        if name == "chunk":
+            w_out = (torch.randn((L, n, n), generator=gen, device="cuda", dtype=torch.float32) / n ** 0.5).to(torch.bfloat16)
+        y = torch.empty((nq, n), dtype=torch.bfloat16, device="cuda")
+
+        def run_out():
+            for l in range(L):
+                prompt.cross_attn_out(l, q, w_out[l], out, y)
+
+        ms_out = timed(run_out)
+        fl_proj = 2.0 * nq * n * n * L
+        res[name]["with_out_projection"] = {
+            "ms_30_layers": round(ms_out, 4), "us_per_layer": round(ms_out * 1e3 / L, 2),
+            "projection_us_per_layer": round((ms_out - ms) * 1e3 / L, 2),
+            "projection_TFLOP/s": round(fl_proj / ((ms_out - ms) * 1e-3) / 1e12, 1),
+            "projection_pct_of_bf16_mfma_peak": round(100 * fl_proj / ((ms_out - ms) * 1e-3) / 1e12 / PEAK_BF16_TFLOPS, 2),
+            "block_TFLOP/s": round((fl + fl_proj) / (ms_out * 1e-3) / 1e12, 1)}
     prompt.close()
     return res
 

@@ -219,6 +219,15 @@ ll_status ll_prompt_tokens(const ll_prompt* prompt, int layer, int* n_tokens);
  * out: device, bf16 [n_q, H, D]; out may be q itself (a wave reads exactly the rows it writes), any other overlap is
  * an error the library cannot detect.  1 <= n_q <= 2^24.  LL_ERR_STATE if the layer has no prompt yet. */
 ll_status ll_cross_attn(const ll_prompt* prompt, int layer, const void* q, int n_q, void* out, void* stream);
+/* The cross-attention block's whole output path (Sec. 3.1, Fig. 2 right): ll_cross_attn followed by the layer's
+ * output projection, y = concat_heads(attn_out) w_out^T, on the same stream.
+ *   w_out: device, bf16 [H*D, H*D] as a linear layer stores its weight ([output feature][input feature]); the weight
+ *   belongs to the model and is borrowed like every tensor.  No bias (an addition the caller can fuse elsewhere).
+ *   attn_out: device, bf16 [n_q, H, D]: receives the attention output (what ll_cross_attn returns in `out`; may be q
+ *   itself) and is read again by the projection.  y: device, bf16 [n_q, H*D], fp32 accumulation, one rounding.
+ *   y and w_out must not overlap any other tensor.  Other arguments and errors as for ll_cross_attn. */
+ll_status ll_cross_attn_out(const ll_prompt* prompt, int layer, const void* q, int n_q, const void* w_out,
+                            void* attn_out, void* y, void* stream);
 
 /* ---- The train-time rule and its backward pass (Sec. 3.2 streaming long tuning; Sec. 3.3 "Consistency between
  * Training and Inference").  One training step supervises a clip of n_clip frames that follows the frames generated

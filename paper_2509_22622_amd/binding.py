@@ -41,6 +41,7 @@ SIGNATURES = {
     "ll_prompt_recache": (_i, [_vp, _i, _vp, _vp, _i, _vp]),
     "ll_prompt_tokens": (_i, [_vp, _i, C.POINTER(_i)]),
     "ll_cross_attn": (_i, [_vp, _i, _vp, _i, _vp, _vp]),
+    "ll_cross_attn_out": (_i, [_vp, _i, _vp, _i, _vp, _vp, _vp, _vp]),
     "ll_clip_bytes": (_sz, [_i] * 7),
     "ll_clip_create": (_i, [_i] * 9 + [C.c_float, _vp, _sz, C.POINTER(_vp)]),
     "ll_clip_destroy": (_i, [_vp]),
@@ -280,6 +281,14 @@ class Prompt:
             _check(lib().ll_cross_attn(self._h, layer, _ptr(q), n_q, _ptr(out), _stream()))
         else:
             _check(lib().ll_cross_attn(self._h, layer, None, n_q, None, None))
+
+    def cross_attn_out(self, layer, q=None, w_out=None, attn_out=None, y=None, n_q=None):
+        """Cross-attention followed by the output projection y = concat_heads(attn_out) w_out^T."""
+        if q is not None:
+            n_q = q.shape[0]
+            _check(lib().ll_cross_attn_out(self._h, layer, _ptr(q), n_q, _ptr(w_out), _ptr(attn_out), _ptr(y), _stream()))
+        else:
+            _check(lib().ll_cross_attn_out(self._h, layer, None, n_q, None, None, None, None))
 
 
 class Clip:

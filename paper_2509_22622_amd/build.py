@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "liblonglive.so")
-SOURCES = ["api.cpp", "api_prompt.cpp", "api_clip.cpp", "api_diag.cpp", "cache_index.cpp", "append_kernel.hip", "attn_kernel.hip", "attn_stream.hip", "attn_stream16.hip", "probe_kernels.hip",
+SOURCES = ["api.cpp", "api_prompt.cpp", "api_clip.cpp", "api_diag.cpp", "cache_index.cpp", "append_kernel.hip", "out_proj.hip", "attn_kernel.hip", "attn_stream.hip", "attn_stream16.hip", "probe_kernels.hip",
            "append_fp8.hip", "attn_fp8.hip", "attn_bwd.hip"]
 # Packed-fp32 VALU forms are switched off for every device translation unit.
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

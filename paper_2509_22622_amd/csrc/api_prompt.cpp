@@ -117,7 +117,35 @@ ll_status ll_prompt_tokens(const ll_prompt* prompt, int layer, int* n_tokens) {
     return LL_OK;
 }
 
+static ll_status cross_attn(const ll_prompt* prompt, int layer, const void* q, int n_q, void* out, void* stream);
+
 ll_status ll_cross_attn(const ll_prompt* prompt, int layer, const void* q, int n_q, void* out, void* stream) {
+    return cross_attn(prompt, layer, q, n_q, out, stream);
+}
+
+ll_status ll_cross_attn_out(const ll_prompt* prompt, int layer, const void* q, int n_q, const void* w_out, void* attn_out,
+                            void* y, void* stream) {
+    CHECK_PROMPT_LAYER(prompt, layer);
+    if (prompt->dev) {
+        if (!w_out || !y) return fail(LL_ERR_INVALID_ARG, "null tensor");
+        if (!aligned16(w_out, y)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+        if (y == attn_out || y == q || w_out == attn_out || w_out == y)
+            return fail(LL_ERR_INVALID_ARG, "y and w_out must not overlap the other tensors");
+    } else if (w_out || y) {
+        return fail(LL_ERR_INVALID_ARG, "index-only handle takes null tensors");
+    }
+    ll_status st = cross_attn(prompt, layer, q, n_q, attn_out, stream);      // every other check, and the attention
+    if (st != LL_OK || !prompt->dev) return st;
+    OutProjParams p{};
+    p.x = static_cast<const uint16_t*>(attn_out); p.w = static_cast<const uint16_t*>(w_out);
+    p.y = static_cast<uint16_t*>(y);
+    p.M = n_q; p.N = p.K = prompt->H * prompt->D;
+    hipError_t e = launch_out_proj(p, static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "output projection kernel launch");
+    return LL_OK;
+}
+
+static ll_status cross_attn(const ll_prompt* prompt, int layer, const void* q, int n_q, void* out, void* stream) {
     CHECK_PROMPT_LAYER(prompt, layer);
     if (n_q < 1 || n_q > (1 << 24)) return fail(LL_ERR_INVALID_ARG, "n_q %d outside [1, 2^24]", n_q);
     if (prompt->tokens[layer] == 0) return fail(LL_ERR_STATE, "layer %d: no prompt", layer);

@@ -208,6 +208,11 @@ int attn_variant_qscale(int D);                // the variant for queries not ye
 int attn_variant_short_keys(int D);            // small workgroups, three per CU: for short key sets
 bool attn_variant_applies_scale(int v);        // the variant multiplies the scores (or queries) by scale_log2e itself
 
+// Output projection y = x w^T (out_proj.hip): x [M, K], w [N, K], y [M, N], all bf16 row-major; K a multiple of 32,
+// N a multiple of 4.
+struct OutProjParams { const uint16_t* x; const uint16_t* w; uint16_t* y; int M, N, K; };
+hipError_t launch_out_proj(const OutProjParams& p, hipStream_t s);
+
 hipError_t launch_append(const AppendParams& p, hipStream_t s);
 hipError_t launch_append8(const AppendParams& p, hipStream_t s);
 hipError_t launch_read_frame8(const ReadFrameParams& p, hipStream_t s);

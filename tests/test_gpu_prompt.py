@@ -232,3 +232,95 @@ def test_graph_replay_of_a_prompt_switch():
         assert_parity_prompt(H.to_bits(sout), want, v, f"replay {rep}")
     eager.close()
     graphed.close()
+
+
+# ---- the block's output path: attention over the prompt, then the layer's output projection (ll_cross_attn_out)
+
+def _weight(heads, head_dim, stream):
+    """bf16 weight [H*D, H*D], N(0, 1 / (H*D)): the projection keeps the size of its input."""
+    n = heads * head_dim
+    return synth.normal_bf16((n, n), CFG, 0, stream, "k", scale=1.0 / np.sqrt(n))
+
+
+def assert_parity_projection(y_bits, want, v_bits, what):
+    """Relative L2 as everywhere (5e-3): y inherits the attention output's error (its bf16 rounding included: the
+    projection reads the rounded tensor, the oracle the exact one), adds fp32 summation noise and one more bf16
+    rounding (2^-9 relative, about 1.1e-3 in relative L2).  Absolute bound scaled like the attention output's."""
+    got = bf16_bits_to_f64(y_bits)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    max_abs, rel = error_metrics(got, want)
+    bound = H.MAX_ABS_TOL * max(1.0, float(np.abs(bf16_bits_to_f64(v_bits)).max()))
+    assert max_abs <= bound and rel <= H.REL_L2_TOL, f"{what}: max_abs {max_abs:.3e} (bound {bound:.3e}) rel_l2 {rel:.3e}"
+
+
+@pytest.mark.parametrize("heads,head_dim,n_q,n_t", [
+    (4, 64, 300, 33), (3, 64, 1, 5), (3, 64, 129, 77),          # N = 256, 192 (one and a half weight blocks), ragged rows
+    (3, 128, 1000, 512), (2, 128, 513, 100), (12, 128, 700, 226), (5, 128, 257, 40),
+])
+def test_cross_attn_out_parity(heads, head_dim, n_q, n_t):
+    from oracle.prompt_cross_attention import cross_attention_out
+    p = B.Prompt(1, heads, head_dim, 512)
+    k, v = bits((n_t, heads, head_dim), 11, "k"), bits((n_t, heads, head_dim), 11, "v")
+    q = bits((n_q, heads, head_dim), 12, "q")
+    w = _weight(heads, head_dim, 13)
+    p.recache(0, H.to_dev(k), H.to_dev(v))
+    attn = torch.empty((n_q, heads, head_dim), dtype=torch.bfloat16, device="cuda")
+    y = torch.full((n_q, heads * head_dim), 9.0, dtype=torch.bfloat16, device="cuda")
+    p.cross_attn_out(0, H.to_dev(q), H.to_dev(w), attn, y)
+    torch.cuda.synchronize()
+    want = cross_attention_out(bf16_bits_to_f64(q), bf16_bits_to_f64(k), bf16_bits_to_f64(v), bf16_bits_to_f64(w))
+    assert_parity_projection(H.to_bits(y), want, v, f"H{heads} D{head_dim} n_q {n_q} n_t {n_t}")
+    # the attention output the call leaves behind is ll_cross_attn's, bit for bit
+    ref = torch.empty_like(attn)
+    p.cross_attn(0, H.to_dev(q), ref)
+    torch.cuda.synchronize()
+    assert torch.equal(attn.view(torch.int16), ref.view(torch.int16))
+    p.close()
+
+
+def test_out_projection_exact_cases():
+    """Weights the projection must pass through bit for bit: the identity returns the attention output itself, a
+    permutation moves its features, and a weight that reads one head ignores the others."""
+    heads, head_dim, n_q, n_t = 3, 128, 300, 50
+    n = heads * head_dim
+    p = B.Prompt(1, heads, head_dim, 64)
+    k, v, q = bits((n_t, heads, head_dim), 21, "k"), bits((n_t, heads, head_dim), 21, "v"), bits((n_q, heads, head_dim), 22, "q")
+    p.recache(0, H.to_dev(k), H.to_dev(v))
+    attn = torch.empty((n_q, heads, head_dim), dtype=torch.bfloat16, device="cuda")
+    y = torch.empty((n_q, n), dtype=torch.bfloat16, device="cuda")
+    eye = torch.eye(n, dtype=torch.bfloat16, device="cuda")
+    p.cross_attn_out(0, H.to_dev(q), eye, attn, y)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), attn.reshape(n_q, n).view(torch.int16))
+    perm = torch.from_numpy(np.random.default_rng(5).permutation(n)).cuda()
+    pw = torch.zeros((n, n), dtype=torch.bfloat16, device="cuda")
+    pw[torch.arange(n, device="cuda"), perm] = 1.0                      # y[:, j] = x[:, perm[j]]
+    p.cross_attn_out(0, H.to_dev(q), pw, attn, y)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), attn.reshape(n_q, n)[:, perm].contiguous().view(torch.int16))
+    # attention written over the queries (attn_out = q), projection from there
+    qd = H.to_dev(q)
+    p.cross_attn_out(0, qd, eye, qd, y)
+    torch.cuda.synchronize()
+    assert torch.equal(y.view(torch.int16), attn.reshape(n_q, n).view(torch.int16))
+    with pytest.raises(B.LongLiveError) as e:
+        p.cross_attn_out(0, qd, eye, y.view(n_q, heads, head_dim), y)   # y on top of the attention output
+    assert e.value.status == B.LL_ERR_INVALID_ARG
+    p.close()
+
+
+def test_cross_attn_out_benchmark_shape():
+    """12 heads x 128, 512 prompt tokens, a chunk's 4680 queries: every element of the projected output."""
+    from oracle.prompt_cross_attention import cross_attention_out
+    heads, head_dim, n_q, n_t = 12, 128, 4680, 512
+    p = B.Prompt(1, heads, head_dim, 512)
+    k, v = bits((n_t, heads, head_dim), 31, "k"), bits((n_t, heads, head_dim), 31, "v")
+    q, w = bits((n_q, heads, head_dim), 32, "q"), _weight(heads, head_dim, 33)
+    p.recache(0, H.to_dev(k), H.to_dev(v))
+    attn = torch.empty((n_q, heads, head_dim), dtype=torch.bfloat16, device="cuda")
+    y = torch.empty((n_q, heads * head_dim), dtype=torch.bfloat16, device="cuda")
+    p.cross_attn_out(0, H.to_dev(q), H.to_dev(w), attn, y)
+    torch.cuda.synchronize()
+    want = cross_attention_out(bf16_bits_to_f64(q), bf16_bits_to_f64(k), bf16_bits_to_f64(v), bf16_bits_to_f64(w))
+    assert_parity_projection(H.to_bits(y), want, v, "benchmark shape")
+    p.close()

@@ -287,6 +287,17 @@ def test_prompt_handle_bookkeeping_and_errors():
     with pytest.raises(B.LongLiveError) as e:
         B._check(L.ll_prompt_recache(p._h, 0, C.cast(C.pointer(one), C.c_void_p), None, 5, None))
     assert e.value.status == 1
+    # the call with the output projection keeps the same books and makes the same checks
+    p.cross_attn_out(1, n_q=3000)
+    with pytest.raises(B.LongLiveError) as e:
+        p.cross_attn_out(1, n_q=0)
+    assert e.value.status == B.LL_ERR_INVALID_ARG
+    with pytest.raises(B.LongLiveError) as e:
+        p.cross_attn_out(0, n_q=10)                                             # no prompt in layer 0
+    assert e.value.status == B.LL_ERR_STATE
+    with pytest.raises(B.LongLiveError) as e:                                   # an index-only handle takes no tensors
+        B._check(L.ll_cross_attn_out(p._h, 1, None, 10, C.cast(C.pointer(one), C.c_void_p), None, None, None))
+    assert e.value.status == B.LL_ERR_INVALID_ARG
     p.close()
 
 
