@@ -373,3 +373,33 @@ def test_clip_key_sets_match_oracle(seed):
         with pytest.raises(B.LongLiveError):
             clip.chunk_key_ranges(len(o.clip_chunks(clip_start, n_clip)))
         clip.close()
+
+
+HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+ROCM_CLANG = "/opt/rocm/llvm/bin/clang"
+
+
+@pytest.mark.skipif(not (os.path.exists(HIPCC) and os.path.exists(ROCM_CLANG)), reason="no ROCm toolchain")
+def test_host_code_under_address_and_ub_sanitizers(tmp_path):
+    """The library's host code (every api*.cpp and the cache index) built with AddressSanitizer and
+    UndefinedBehaviorSanitizer on the host pass only, the kernel launchers replaced by stand-ins
+    (tests/host_stubs.cpp), driven from C over index-only handles (tests/host_sanitize_driver.c): random streams of
+    appends, re-prefills, resets and introspection calls, the prompt and the train-time handles.  Any report of
+    either sanitizer ends the driver with a non-zero status."""
+    csrc = os.path.join(ROOT, "paper_2509_22622_amd", "csrc")
+    here = os.path.join(ROOT, "tests")
+    lib = tmp_path / "libll_san.so"
+    san = ["-Xarch_host", "-fsanitize=address", "-Xarch_host", "-fsanitize=undefined", "-Xarch_host",
+           "-fno-sanitize-recover=undefined"]
+    srcs = [os.path.join(csrc, f) for f in ("api.cpp", "api_prompt.cpp", "api_clip.cpp", "api_diag.cpp", "cache_index.cpp")]
+    build = subprocess.run([HIPCC, "--offload-arch=gfx950", "-O1", "-g", "-std=c++17", "-fPIC", "-shared", *san,
+                            "-Wno-unused-command-line-argument", *srcs, os.path.join(here, "host_stubs.cpp"), "-o", str(lib)],
+                           capture_output=True, text=True)
+    assert build.returncode == 0, build.stderr[-3000:]
+    exe = tmp_path / "host_walk"
+    link = subprocess.run([ROCM_CLANG, "-std=c99", "-pedantic", "-Wall", "-Werror", "-g", "-fsanitize=address,undefined",
+                           "-fno-sanitize-recover=undefined", "-o", str(exe), os.path.join(here, "host_sanitize_driver.c"),
+                           "-L", str(tmp_path), "-l:libll_san.so", "-Wl,-rpath," + str(tmp_path)], capture_output=True, text=True)
+    assert link.returncode == 0, link.stderr[-3000:]
+    run = subprocess.run([str(exe)], capture_output=True, text=True, env={**os.environ, "ASAN_OPTIONS": "detect_leaks=1"})
+    assert run.returncode == 0 and "host walk ok" in run.stdout, f"exit {run.returncode}\n{run.stdout[-2000:]}\n{run.stderr[-4000:]}"
