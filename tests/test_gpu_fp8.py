@@ -10,7 +10,8 @@ What is compared, and how tightly:
     the kernel rounds them to E4M3 (relative error at most 2^-4, about 2.6 % rms, independent from key to key).
     For one output element the error is sum_j w_j e_j V_j / sum_j w_j: at most 2^-4 * max|V| in magnitude (the
     max-abs tolerance, plus the bf16 rounding of the output), and for values that are independent from key to
-    key about 2.6 % of the output's own rms, so that the relative L2 error of a tensor is gated at 6 %.  A wrong
+    key about 2.6 % of the output's own rms; measured 2.5-3.6 % over all cases of this file, gated at 4.5 % (a kblock
+    dropped at the benchmark shape adds 3.7 % in quadrature and fails the gate).  A wrong
     key order, a wrong slot or a transposed operand gives a relative L2 error above 1.
 """
 import numpy as np
@@ -27,7 +28,7 @@ from test_gpu_parity import HEADS6, MID128, NOSINK, ODD128, ODD64, WIDE, _random
 
 pytestmark = pytest.mark.gpu
 
-REL_L2_TOL_FP8 = 6e-2
+REL_L2_TOL_FP8 = 4.5e-2
 CODE_FLIP_FRACTION = 2e-3     # fp32 rotation noise ~1e-7 relative against code boundaries 2^-4 apart: ~1e-5 expected
 TABLE = e4m3_table()
 
@@ -134,7 +135,7 @@ def test_loglin_fp8_variants(w):
     """The form of the kernel that takes the E4M3 code of a weight as round(8 log2(weight) + 56) instead of
     computing the exponential: a weight is off by a factor between 0.96 and 1.02 (after normalisation) on top of a
     rounding to an eighth of an octave (+-4.4 %), so a single weight may be off by up to 2^-3 (the max-abs gate
-    below); the relative L2 error of a tensor (3.1-3.6 % expected) stays inside the tier's 6 %.  Row sums come
+    below); the relative L2 error of a tensor (3.1-3.6 % expected) stays inside the tier's 4.5 %.  Row sums come
     from the same 8-bit weights, so every output lies in the hull of the V8 rows."""
     ids = {n: v for v, n in B.attn_variant_names().items()}
     B.set_attn_variant(ids["d%d_fp8_loglin" % w.head_dim])
