@@ -97,6 +97,47 @@ def test_wan_layer_sink_relative():
     cache.close()
 
 
+def test_wan_layer_second_pass_at_full_size():
+    """Config 2's shape with one key far above everything else in the ring's last frames (200 times a query of the
+    staged chunk): the default kernel's fixed-reference pass sees a row sum run away in that query's tile and the
+    workgroup takes the tile again with the maximum followed; every other tile stays on the first pass.  Sampled rows
+    against the oracle; rows that give the large key weight are left to the closed form (the dominated row returns
+    that key's value row) because the bf16 storage of so large a key moves their logits by more than the tolerance."""
+    w = synth.WAN_LAYER
+    P = w.tokens_per_frame
+    cache, oracle, marked = H.make_cache(w), Oracle(H.oracle_cfg(w)), Oracle(H.oracle_cfg(w))
+    tok = 2 * P + 777                                              # a token of the staged chunk's last frame
+    for i in range(6):
+        f0 = 3 * i
+        q, k, v = synth.chunk_qkv(w, 0, i)
+        v_marked = v
+        if i == 5:
+            k[tok] = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(q[tok]) * np.float32(200.0 / 8.0))
+            v_marked = v.copy()
+            v_marked[tok] = synth.f32_to_bf16_bits(synth.bf16_bits_to_f32(v[tok]) + np.float32(1000.0))
+        qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+        qr, out = torch.empty_like(qd), torch.empty_like(qd)
+        cache.chunk_append(0, f0, 3, qd, kd, vd, qr)
+        cache.sink_window_attn(0, qr, out)
+        torch.cuda.synchronize()
+        oracle.append(0, f0, q, k, v)
+        marked.append(0, f0, q, k, v_marked)
+        _trim(oracle, 0, f0 - w.window_frames, w.sink_frames)
+        _trim(marked, 0, f0 - w.window_frames, w.sink_frames)
+    rows = np.unique(np.concatenate([_sample_rows(w.chunk_tokens, 555), np.arange(tok - 40, tok + 40)]))   # the tile of `tok` too
+    want = oracle.attn(0, rows=rows)
+    got = bf16_bits_to_f64(H.to_bits(out[torch.from_numpy(rows).cuda()]))
+    assert np.isfinite(got).all()
+    at = int(np.searchsorted(rows, tok))
+    vrow = bf16_bits_to_f64(v[tok])
+    assert np.abs(want[at] - vrow).max() < 1e-6 and np.abs(got[at] - vrow).max() <= 2.0 ** -8 * np.abs(vrow).max()
+    calm = np.abs(marked.attn(0, rows=rows) - want).max(axis=2) < 1e-4
+    assert calm.sum() > calm.size // 8
+    max_abs, rel = error_metrics(got[calm], want[calm])
+    assert max_abs <= H.MAX_ABS_TOL and rel <= H.REL_L2_TOL, f"second pass at full size: max_abs {max_abs:.3e} rel_l2 {rel:.3e}"
+    cache.close()
+
+
 def test_long_window():
     """Config 4: no sink, window 21 frames (37440 keys in steady state)."""
     w = synth.LONG_WINDOW
