@@ -177,12 +177,17 @@ def prompt_side_stats(w, gen, n_text=512, reps=10):
         # the block's whole output path: attention, then y = concat_heads(out) w^T with one weight per layer
         n = Hh * D
         if name == "chunk":
-            w_out = (torch.randn((L, n, n), generator=gen, device="cuda", dtype=torch.float32) / n ** 0.5).to(torch.bfloat16)
+            w_row = (torch.randn((L, n, n), generator=gen, device="cuda", dtype=torch.float32) / n ** 0.5).to(torch.bfloat16)
+            w_out = torch.empty_like(w_row)                  # packed once, as at model load
+            for l in range(L):
+                prompt.pack_out_weight(w_row[l], w_out[l])
+            del w_row
         y = torch.empty((nq, n), dtype=torch.bfloat16, device="cuda")
+        work = torch.empty(prompt.cross_attn_out_workspace_bytes(nq), dtype=torch.uint8, device="cuda")
 
         def run_out():
             for l in range(L):
-                prompt.cross_attn_out(l, q, w_out[l], out, y)
+                prompt.cross_attn_out(l, q, w_out[l], work, y)
 
         ms_out = timed(run_out)
         fl_proj = 2.0 * nq * n * n * L

@@ -219,15 +219,27 @@ ll_status ll_prompt_tokens(const ll_prompt* prompt, int layer, int* n_tokens);
  * out: device, bf16 [n_q, H, D]; out may be q itself (a wave reads exactly the rows it writes), any other overlap is
  * an error the library cannot detect.  1 <= n_q <= 2^24.  LL_ERR_STATE if the layer has no prompt yet. */
 ll_status ll_cross_attn(const ll_prompt* prompt, int layer, const void* q, int n_q, void* out, void* stream);
-/* The cross-attention block's whole output path (Sec. 3.1, Fig. 2 right): ll_cross_attn followed by the layer's
- * output projection, y = concat_heads(attn_out) w_out^T, on the same stream.
- *   w_out: device, bf16 [H*D, H*D] as a linear layer stores its weight ([output feature][input feature]); the weight
- *   belongs to the model and is borrowed like every tensor.  No bias (an addition the caller can fuse elsewhere).
- *   attn_out: device, bf16 [n_q, H, D]: receives the attention output (what ll_cross_attn returns in `out`; may be q
- *   itself) and is read again by the projection.  y: device, bf16 [n_q, H*D], fp32 accumulation, one rounding.
- *   y and w_out must not overlap any other tensor.  Other arguments and errors as for ll_cross_attn. */
-ll_status ll_cross_attn_out(const ll_prompt* prompt, int layer, const void* q, int n_q, const void* w_out,
-                            void* attn_out, void* y, void* stream);
+/* The cross-attention block's whole output path (Sec. 3.1, Fig. 2 right): the attention of ll_cross_attn followed by
+ * the layer's output projection, y = concat_heads(attn_out) w_out^T, on the same stream.  The two kernels hand the
+ * attention output over in the order the matrix instructions of the projection read it (blocks of 16 rows x 32
+ * features), not as a row-major tensor; the weight is brought into the same order once, by ll_out_proj_pack_weight.
+ *
+ * ll_out_proj_pack_weight: w_out: device, bf16 [H*D, H*D] as a linear layer stores its weight ([output feature][input
+ *   feature]); w_packed: device, the same number of bytes, 16-byte aligned, must not overlap w_out.  One kernel; done
+ *   once per layer when the model is loaded.  head_dim 64 or 128, heads >= 1.  No bias anywhere (an addition the
+ *   caller can fuse elsewhere).
+ * ll_cross_attn_out_workspace_bytes: bytes of `workspace` for n_q rows (n_q rounded up to 16, x H*D x 2); 0 if a
+ *   size is invalid.
+ * ll_cross_attn_out: w_packed as written by ll_out_proj_pack_weight for this handle's heads and head_dim (borrowed);
+ *   workspace: device, 16-byte aligned, at least ll_cross_attn_out_workspace_bytes(...) bytes, owned by the caller:
+ *   receives the attention output in the projection's order and is read again by the projection (its contents
+ *   afterwards are that intermediate, of no use to the caller; callers that want the attention output itself use
+ *   ll_cross_attn).  y: device, bf16 [n_q, H*D], fp32 accumulation, one rounding.  y, w_packed and workspace must not
+ *   overlap one another or q.  Other arguments and errors as for ll_cross_attn. */
+ll_status ll_out_proj_pack_weight(int heads, int head_dim, const void* w_out, void* w_packed, void* stream);
+size_t ll_cross_attn_out_workspace_bytes(int heads, int head_dim, int n_q);
+ll_status ll_cross_attn_out(const ll_prompt* prompt, int layer, const void* q, int n_q, const void* w_packed,
+                            void* workspace, void* y, void* stream);
 
 /* ---- The train-time rule and its backward pass (Sec. 3.2 streaming long tuning; Sec. 3.3 "Consistency between
  * Training and Inference").  One training step supervises a clip of n_clip frames that follows the frames generated

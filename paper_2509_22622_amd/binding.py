@@ -42,6 +42,8 @@ SIGNATURES = {
     "ll_prompt_tokens": (_i, [_vp, _i, C.POINTER(_i)]),
     "ll_cross_attn": (_i, [_vp, _i, _vp, _i, _vp, _vp]),
     "ll_cross_attn_out": (_i, [_vp, _i, _vp, _i, _vp, _vp, _vp, _vp]),
+    "ll_out_proj_pack_weight": (_i, [_i, _i, _vp, _vp, _vp]),
+    "ll_cross_attn_out_workspace_bytes": (C.c_size_t, [_i, _i, _i]),
     "ll_clip_bytes": (_sz, [_i] * 7),
     "ll_clip_create": (_i, [_i] * 9 + [C.c_float, _vp, _sz, C.POINTER(_vp)]),
     "ll_clip_destroy": (_i, [_vp]),
@@ -282,11 +284,19 @@ class Prompt:
         else:
             _check(lib().ll_cross_attn(self._h, layer, None, n_q, None, None))
 
-    def cross_attn_out(self, layer, q=None, w_out=None, attn_out=None, y=None, n_q=None):
-        """Cross-attention followed by the output projection y = concat_heads(attn_out) w_out^T."""
+    def pack_out_weight(self, w_out, w_packed):
+        """The layer's output weight (bf16 [H*D, H*D], [output feature][input feature]) in the projection's order."""
+        _check(lib().ll_out_proj_pack_weight(self.heads, self.head_dim, _ptr(w_out), _ptr(w_packed), _stream()))
+
+    def cross_attn_out_workspace_bytes(self, n_q) -> int:
+        return lib().ll_cross_attn_out_workspace_bytes(self.heads, self.head_dim, n_q)
+
+    def cross_attn_out(self, layer, q=None, w_packed=None, workspace=None, y=None, n_q=None):
+        """Cross-attention followed by the output projection y = concat_heads(attention output) w_out^T; w_packed from
+        pack_out_weight, workspace of cross_attn_out_workspace_bytes(n_q) bytes."""
         if q is not None:
             n_q = q.shape[0]
-            _check(lib().ll_cross_attn_out(self._h, layer, _ptr(q), n_q, _ptr(w_out), _ptr(attn_out), _ptr(y), _stream()))
+            _check(lib().ll_cross_attn_out(self._h, layer, _ptr(q), n_q, _ptr(w_packed), _ptr(workspace), _ptr(y), _stream()))
         else:
             _check(lib().ll_cross_attn_out(self._h, layer, None, n_q, None, None, None, None))
 

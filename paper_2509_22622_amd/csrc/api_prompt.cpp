@@ -117,27 +117,46 @@ ll_status ll_prompt_tokens(const ll_prompt* prompt, int layer, int* n_tokens) {
     return LL_OK;
 }
 
-static ll_status cross_attn(const ll_prompt* prompt, int layer, const void* q, int n_q, void* out, void* stream);
+// out_frag: the output goes to `out` in the output projection's fragment order instead of row-major
+static ll_status cross_attn(const ll_prompt* prompt, int layer, const void* q, int n_q, void* out, bool out_frag, void* stream);
 
 ll_status ll_cross_attn(const ll_prompt* prompt, int layer, const void* q, int n_q, void* out, void* stream) {
-    return cross_attn(prompt, layer, q, n_q, out, stream);
+    return cross_attn(prompt, layer, q, n_q, out, false, stream);
 }
 
-ll_status ll_cross_attn_out(const ll_prompt* prompt, int layer, const void* q, int n_q, const void* w_out, void* attn_out,
-                            void* y, void* stream) {
+ll_status ll_out_proj_pack_weight(int heads, int head_dim, const void* w_out, void* w_packed, void* stream) {
+    if (heads < 1 || heads > 1024 || (head_dim != 64 && head_dim != 128))
+        return fail(LL_ERR_INVALID_ARG, "heads %d (1..1024) or head_dim %d (64 or 128)", heads, head_dim);
+    if (!w_out || !w_packed) return fail(LL_ERR_INVALID_ARG, "null tensor");
+    if (!aligned16(w_out, w_packed)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+    if (w_out == w_packed) return fail(LL_ERR_INVALID_ARG, "w_packed must not be w_out");
+    const int n = heads * head_dim;
+    hipError_t e = launch_pack_out_weight(static_cast<const uint16_t*>(w_out), static_cast<uint16_t*>(w_packed), n, n,
+                                          static_cast<hipStream_t>(stream));
+    if (e != hipSuccess) return hip_fail(e, "weight packing kernel launch");
+    return LL_OK;
+}
+
+size_t ll_cross_attn_out_workspace_bytes(int heads, int head_dim, int n_q) {
+    if (heads < 1 || heads > 1024 || (head_dim != 64 && head_dim != 128) || n_q < 1 || n_q > (1 << 24)) return 0;
+    return (size_t(n_q) + 15) / 16 * 16 * size_t(heads) * size_t(head_dim) * 2;
+}
+
+ll_status ll_cross_attn_out(const ll_prompt* prompt, int layer, const void* q, int n_q, const void* w_packed,
+                            void* workspace, void* y, void* stream) {
     CHECK_PROMPT_LAYER(prompt, layer);
     if (prompt->dev) {
-        if (!w_out || !y) return fail(LL_ERR_INVALID_ARG, "null tensor");
-        if (!aligned16(w_out, y)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
-        if (y == attn_out || y == q || w_out == attn_out || w_out == y)
-            return fail(LL_ERR_INVALID_ARG, "y and w_out must not overlap the other tensors");
-    } else if (w_out || y) {
+        if (!w_packed || !y) return fail(LL_ERR_INVALID_ARG, "null tensor");
+        if (!aligned16(w_packed, y)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+        if (y == workspace || y == q || w_packed == workspace || w_packed == y || workspace == q)
+            return fail(LL_ERR_INVALID_ARG, "y, w_packed and workspace must not overlap the other tensors");
+    } else if (w_packed || y) {
         return fail(LL_ERR_INVALID_ARG, "index-only handle takes null tensors");
     }
-    ll_status st = cross_attn(prompt, layer, q, n_q, attn_out, stream);      // every other check, and the attention
+    ll_status st = cross_attn(prompt, layer, q, n_q, workspace, true, stream);   // every other check, and the attention
     if (st != LL_OK || !prompt->dev) return st;
     OutProjParams p{};
-    p.x = static_cast<const uint16_t*>(attn_out); p.w = static_cast<const uint16_t*>(w_out);
+    p.x_frag = static_cast<const uint16_t*>(workspace); p.w_frag = static_cast<const uint16_t*>(w_packed);
     p.y = static_cast<uint16_t*>(y);
     p.M = n_q; p.N = p.K = prompt->H * prompt->D;
     hipError_t e = launch_out_proj(p, static_cast<hipStream_t>(stream));
@@ -145,7 +164,7 @@ ll_status ll_cross_attn_out(const ll_prompt* prompt, int layer, const void* q, i
     return LL_OK;
 }
 
-static ll_status cross_attn(const ll_prompt* prompt, int layer, const void* q, int n_q, void* out, void* stream) {
+static ll_status cross_attn(const ll_prompt* prompt, int layer, const void* q, int n_q, void* out, bool out_frag, void* stream) {
     CHECK_PROMPT_LAYER(prompt, layer);
     if (n_q < 1 || n_q > (1 << 24)) return fail(LL_ERR_INVALID_ARG, "n_q %d outside [1, 2^24]", n_q);
     if (prompt->tokens[layer] == 0) return fail(LL_ERR_STATE, "layer %d: no prompt", layer);
@@ -161,10 +180,13 @@ static ll_status cross_attn(const ll_prompt* prompt, int layer, const void* q, i
     // with several rounds (a re-prefill's queries) small workgroups, three to a CU in different phases, are.
     int variant = attn_variant_qscale(prompt->D);
     if ((int64_t(n_q) + 255) / 256 * prompt->H > 512) variant = attn_variant_short_keys(prompt->D);
-    if (g_variant != 0 && attn_variant_supports(g_variant, prompt->D, KBLOCK) && attn_variant_applies_scale(g_variant))
+    if (g_variant != 0 && attn_variant_supports(g_variant, prompt->D, KBLOCK) && attn_variant_applies_scale(g_variant) &&
+        (!out_frag || attn_variant_out_frag(g_variant)))
         variant = g_variant;
     AttnParams p{};
-    p.q = static_cast<const uint16_t*>(q); p.out = static_cast<uint16_t*>(out);
+    p.q = static_cast<const uint16_t*>(q);
+    if (out_frag) p.out_frag = static_cast<uint16_t*>(out);
+    else p.out = static_cast<uint16_t*>(out);
     p.k_cache = prompt_k(prompt, layer); p.v_cache = prompt_v(prompt, layer);
     p.head_stride = prompt->head_stride;
     p.H = prompt->H; p.D = prompt->D;

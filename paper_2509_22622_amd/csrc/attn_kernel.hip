@@ -240,6 +240,23 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(OCC, 8)
         const float inv = 1.0f / l;
         const int row = q0 + n * 32 + col;
         if (row < ch.q_end) {
+            if (p.out_frag != nullptr) {         // uniform: the output projection's operand (kernels.h)
+                // features 32 db + 4 G + e and 32 db + 16 + 4 G + e of lane group G are registers 4 g + e of this
+                // lane half for g = 0, 2 (G = half) and g = 1, 3 (G = half + 2)
+                const int n_ksteps = p.H * DB;
+#pragma unroll
+                for (int db = 0; db < DB; ++db)
+#pragma unroll
+                    for (int hi = 0; hi < 2; ++hi) {
+                        const int g0 = hi, g1 = hi + 2;
+                        const u32x4 w = {pack_bf16(o[n][db][4 * g0] * inv, o[n][db][4 * g0 + 1] * inv),
+                                         pack_bf16(o[n][db][4 * g0 + 2] * inv, o[n][db][4 * g0 + 3] * inv),
+                                         pack_bf16(o[n][db][4 * g1] * inv, o[n][db][4 * g1 + 1] * inv),
+                                         pack_bf16(o[n][db][4 * g1 + 2] * inv, o[n][db][4 * g1 + 3] * inv)};
+                        *reinterpret_cast<u32x4*>(p.out_frag + op_frag_offset(row, head * DB + db, half + 2 * hi, n_ksteps)) = w;
+                    }
+                continue;
+            }
             uint16_t* dst = p.out + (int64_t(row) * p.H + head) * D + half * 4;
 #pragma unroll
             for (int db = 0; db < DB; ++db)
@@ -307,6 +324,7 @@ int attn_variant_qscale(int D) { return first_stream16() + (D == 128 ? 2 : 3); }
 int attn_variant_lse(int D) { return first_stream16() + (D == 128 ? 4 : 5); }
 // the 128-query kernel that leaves room for three workgroups per CU (short key sets, many query tiles)
 int attn_variant_short_keys(int D) { return D == 128 ? 8 : 10; }
+bool attn_variant_out_frag(int v) { return (v >= 1 && v <= kNumSimple) || is_stream16(v); }
 bool attn_variant_applies_scale(int v) {
     return (v >= 1 && v <= kNumSimple) || v == kNumSimple + 3 || v == kNumSimple + 4 || v == first_stream16() + 2 || v == first_stream16() + 3;
 }

@@ -562,6 +562,17 @@ __global__ __launch_bounds__(S16_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
         const float inv = 1.0f / l;
         const int row = q0 + 16 * qb + n;
         if (row < ch.q_end) {
+            if (p.out_frag != nullptr) {         // uniform: the output projection's operand, 1 KB per store instruction
+                const int n_ksteps = p.H * (D / 32);
+#pragma unroll
+                for (int t = 0; t < D / 32; ++t) {
+                    const f32x4 a = st.o[2 * t][qb], b = st.o[2 * t + 1][qb];
+                    const u32x4 w = {s16_pack_bf16(a[0] * inv, a[1] * inv), s16_pack_bf16(a[2] * inv, a[3] * inv),
+                                     s16_pack_bf16(b[0] * inv, b[1] * inv), s16_pack_bf16(b[2] * inv, b[3] * inv)};
+                    *reinterpret_cast<u32x4*>(p.out_frag + op_frag_offset(row, head * (D / 32) + t, g, n_ksteps)) = w;
+                }
+                continue;
+            }
             uint16_t* dst = p.out + (int64_t(row) * p.H + head) * D + g * 4;
 #pragma unroll
             for (int dq = 0; dq < D / 16; ++dq) {

@@ -110,6 +110,10 @@ struct AttnChunk {
 
 struct AttnParams {
     const uint16_t* q; uint16_t* out;     // [rows, H, D]
+    // When set, the output goes here instead, in the fragment order of the output projection (op_frag_offset with
+    // H * D / 32 k-steps, the heads side by side); honoured by the kernels attn_variant_out_frag names.  Chunk 0 must
+    // start at row 0.
+    uint16_t* out_frag;
     const uint16_t* k_cache; const uint16_t* v_cache;   // layer base (head 0)
     int64_t head_stride;
     int H, D;
@@ -207,11 +211,21 @@ int attn_variant_lse(int D);                   // the variant that also writes A
 int attn_variant_qscale(int D);                // the variant for queries not yet scaled (honours scale_log2e)
 int attn_variant_short_keys(int D);            // small workgroups, three per CU: for short key sets
 bool attn_variant_applies_scale(int v);        // the variant multiplies the scores (or queries) by scale_log2e itself
+bool attn_variant_out_frag(int v);             // the variant honours AttnParams::out_frag
 
-// Output projection y = x w^T (out_proj.hip): x [M, K], w [N, K], y [M, N], all bf16 row-major; K a multiple of 32,
-// N a multiple of 4.
-struct OutProjParams { const uint16_t* x; const uint16_t* w; uint16_t* y; int M, N, K; };
+// Output projection y = x w^T (out_proj.hip): x [M, K] and w [N, K] in fragment order, y [M, N] bf16 row-major.
+// Fragment order: 16 rows x 32 contraction indices form one 1 KB fragment, ready to be an operand of a 16x16x32 MFMA:
+// lane 16 g + r holds, for row 16 b + r, the indices 32 ks + 4 g + 0..3 and 32 ks + 16 + 4 g + 0..3 (the pairing the
+// attention kernels' accumulators give for free); the fragments of a row block b lie side by side in ks.  The
+// offset, in elements, of the 8 values of (row, k-step ks, lane group g) in a tensor of n_ksteps = K / 32 k-steps:
+__host__ __device__ inline int64_t op_frag_offset(int row, int ks, int g, int n_ksteps) {
+    return ((int64_t(row >> 4) * n_ksteps + ks) * 64 + 16 * g + (row & 15)) * 8;
+}
+// x_frag holds ceil(M / 16) row blocks (rows past M in the last one may hold anything); N a multiple of 16, K of 64.
+struct OutProjParams { const uint16_t* x_frag; const uint16_t* w_frag; uint16_t* y; int M, N, K; };
 hipError_t launch_out_proj(const OutProjParams& p, hipStream_t s);
+// w [N, K] bf16 row-major ([output feature][input feature]) -> fragment order, same size
+hipError_t launch_pack_out_weight(const uint16_t* w, uint16_t* w_frag, int N, int K, hipStream_t s);
 
 hipError_t launch_append(const AppendParams& p, hipStream_t s);
 hipError_t launch_append8(const AppendParams& p, hipStream_t s);

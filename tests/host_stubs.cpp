@@ -14,6 +14,7 @@ int attn_variant_lse(int D) { return D == 128 ? 1 : 2; }
 int attn_variant_qscale(int D) { return D == 128 ? 1 : 2; }
 int attn_variant_short_keys(int D) { return D == 128 ? 1 : 2; }
 bool attn_variant_applies_scale(int) { return true; }
+bool attn_variant_out_frag(int) { return true; }
 int bwd_tile_cols(int) { return 256; }
 hipError_t launch_append(const AppendParams&, hipStream_t) { return hipSuccess; }
 hipError_t launch_append8(const AppendParams&, hipStream_t) { return hipSuccess; }
@@ -21,6 +22,7 @@ hipError_t launch_read_frame(const ReadFrameParams&, hipStream_t) { return hipSu
 hipError_t launch_read_frame8(const ReadFrameParams&, hipStream_t) { return hipSuccess; }
 hipError_t launch_attn(const AttnParams&, int, hipStream_t) { return hipSuccess; }
 hipError_t launch_out_proj(const OutProjParams&, hipStream_t) { return hipSuccess; }
+hipError_t launch_pack_out_weight(const uint16_t*, uint16_t*, int, int, hipStream_t) { return hipSuccess; }
 hipError_t launch_bwd_dq(const BwdParams&, hipStream_t) { return hipSuccess; }
 hipError_t launch_bwd_dkv(const BwdParams&, hipStream_t) { return hipSuccess; }
 hipError_t launch_bwd_delta(const float*, const uint16_t*, float*, int, int, int, int64_t, hipStream_t) { return hipSuccess; }

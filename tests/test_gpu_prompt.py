@@ -253,6 +253,20 @@ def assert_parity_projection(y_bits, want, v_bits, what):
     assert max_abs <= bound and rel <= H.REL_L2_TOL, f"{what}: max_abs {max_abs:.3e} (bound {bound:.3e}) rel_l2 {rel:.3e}"
 
 
+def _project(p, q_dev, w_dev, y=None):
+    """ll_cross_attn_out with a freshly packed weight and a workspace of exactly the size the library asks for."""
+    n_q, n = q_dev.shape[0], p.heads * p.head_dim
+    w_packed = torch.empty_like(w_dev)
+    p.pack_out_weight(w_dev, w_packed)
+    nbytes = p.cross_attn_out_workspace_bytes(n_q)
+    assert nbytes == (n_q + 15) // 16 * 16 * n * 2
+    work = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+    if y is None:
+        y = torch.full((n_q, n), 9.0, dtype=torch.bfloat16, device="cuda")
+    p.cross_attn_out(0, q_dev, w_packed, work, y)
+    return y
+
+
 @pytest.mark.parametrize("heads,head_dim,n_q,n_t", [
     (4, 64, 300, 33), (3, 64, 1, 5), (3, 64, 129, 77),          # N = 256, 192 (one and a half weight blocks), ragged rows
     (3, 128, 1000, 512), (2, 128, 513, 100), (12, 128, 700, 226), (5, 128, 257, 40),
@@ -264,47 +278,58 @@ def test_cross_attn_out_parity(heads, head_dim, n_q, n_t):
     q = bits((n_q, heads, head_dim), 12, "q")
     w = _weight(heads, head_dim, 13)
     p.recache(0, H.to_dev(k), H.to_dev(v))
-    attn = torch.empty((n_q, heads, head_dim), dtype=torch.bfloat16, device="cuda")
-    y = torch.full((n_q, heads * head_dim), 9.0, dtype=torch.bfloat16, device="cuda")
-    p.cross_attn_out(0, H.to_dev(q), H.to_dev(w), attn, y)
+    y = _project(p, H.to_dev(q), H.to_dev(w))
     torch.cuda.synchronize()
     want = cross_attention_out(bf16_bits_to_f64(q), bf16_bits_to_f64(k), bf16_bits_to_f64(v), bf16_bits_to_f64(w))
     assert_parity_projection(H.to_bits(y), want, v, f"H{heads} D{head_dim} n_q {n_q} n_t {n_t}")
-    # the attention output the call leaves behind is ll_cross_attn's, bit for bit
-    ref = torch.empty_like(attn)
-    p.cross_attn(0, H.to_dev(q), ref)
-    torch.cuda.synchronize()
-    assert torch.equal(attn.view(torch.int16), ref.view(torch.int16))
     p.close()
 
 
-def test_out_projection_exact_cases():
-    """Weights the projection must pass through bit for bit: the identity returns the attention output itself, a
-    permutation moves its features, and a weight that reads one head ignores the others."""
-    heads, head_dim, n_q, n_t = 3, 128, 300, 50
+@pytest.mark.parametrize("heads,head_dim,n_q", [(3, 128, 300), (5, 64, 77),
+                                                (12, 128, 11000), (12, 64, 11000)])   # the last two: the kernel for many query tiles
+def test_out_projection_exact_cases(heads, head_dim, n_q):
+    """Weights the projection must pass through bit for bit: the identity returns the attention output itself (what
+    ll_cross_attn writes: so the hand-over between the two kernels loses and moves nothing), a permutation moves its
+    features."""
+    n_t = 50
     n = heads * head_dim
     p = B.Prompt(1, heads, head_dim, 64)
     k, v, q = bits((n_t, heads, head_dim), 21, "k"), bits((n_t, heads, head_dim), 21, "v"), bits((n_q, heads, head_dim), 22, "q")
     p.recache(0, H.to_dev(k), H.to_dev(v))
+    qd = H.to_dev(q)
     attn = torch.empty((n_q, heads, head_dim), dtype=torch.bfloat16, device="cuda")
-    y = torch.empty((n_q, n), dtype=torch.bfloat16, device="cuda")
+    p.cross_attn(0, qd, attn)
     eye = torch.eye(n, dtype=torch.bfloat16, device="cuda")
-    p.cross_attn_out(0, H.to_dev(q), eye, attn, y)
+    y = _project(p, qd, eye)
     torch.cuda.synchronize()
     assert torch.equal(y.view(torch.int16), attn.reshape(n_q, n).view(torch.int16))
     perm = torch.from_numpy(np.random.default_rng(5).permutation(n)).cuda()
     pw = torch.zeros((n, n), dtype=torch.bfloat16, device="cuda")
     pw[torch.arange(n, device="cuda"), perm] = 1.0                      # y[:, j] = x[:, perm[j]]
-    p.cross_attn_out(0, H.to_dev(q), pw, attn, y)
+    y = _project(p, qd, pw)
     torch.cuda.synchronize()
     assert torch.equal(y.view(torch.int16), attn.reshape(n_q, n)[:, perm].contiguous().view(torch.int16))
-    # attention written over the queries (attn_out = q), projection from there
-    qd = H.to_dev(q)
-    p.cross_attn_out(0, qd, eye, qd, y)
-    torch.cuda.synchronize()
-    assert torch.equal(y.view(torch.int16), attn.reshape(n_q, n).view(torch.int16))
+    p.close()
+
+
+def test_cross_attn_out_refuses_overlapping_tensors():
+    heads, head_dim, n_q = 2, 64, 40
+    n = heads * head_dim
+    p = B.Prompt(1, heads, head_dim, 64)
+    kv = H.to_dev(bits((9, heads, head_dim), 21, "k"))
+    p.recache(0, kv, kv)
+    qd = H.to_dev(bits((n_q, heads, head_dim), 22, "q"))
+    w = torch.eye(n, dtype=torch.bfloat16, device="cuda")
+    wp = torch.empty_like(w)
+    p.pack_out_weight(w, wp)
+    work = torch.empty(p.cross_attn_out_workspace_bytes(n_q), dtype=torch.uint8, device="cuda")
+    y = torch.empty((n_q, n), dtype=torch.bfloat16, device="cuda")
+    for args in ((qd, wp, y, y), (qd, wp, qd, y), (qd, wp, work, qd), (qd, wp, wp, y)):
+        with pytest.raises(B.LongLiveError) as e:
+            p.cross_attn_out(0, *args)
+        assert e.value.status == B.LL_ERR_INVALID_ARG
     with pytest.raises(B.LongLiveError) as e:
-        p.cross_attn_out(0, qd, eye, y.view(n_q, heads, head_dim), y)   # y on top of the attention output
+        p.pack_out_weight(w, w)
     assert e.value.status == B.LL_ERR_INVALID_ARG
     p.close()
 
@@ -317,9 +342,7 @@ def test_cross_attn_out_benchmark_shape():
     k, v = bits((n_t, heads, head_dim), 31, "k"), bits((n_t, heads, head_dim), 31, "v")
     q, w = bits((n_q, heads, head_dim), 32, "q"), _weight(heads, head_dim, 33)
     p.recache(0, H.to_dev(k), H.to_dev(v))
-    attn = torch.empty((n_q, heads, head_dim), dtype=torch.bfloat16, device="cuda")
-    y = torch.empty((n_q, heads * head_dim), dtype=torch.bfloat16, device="cuda")
-    p.cross_attn_out(0, H.to_dev(q), H.to_dev(w), attn, y)
+    y = _project(p, H.to_dev(q), H.to_dev(w))
     torch.cuda.synchronize()
     want = cross_attention_out(bf16_bits_to_f64(q), bf16_bits_to_f64(k), bf16_bits_to_f64(v), bf16_bits_to_f64(w))
     assert_parity_projection(H.to_bits(y), want, v, "benchmark shape")

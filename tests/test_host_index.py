@@ -298,6 +298,13 @@ def test_prompt_handle_bookkeeping_and_errors():
     with pytest.raises(B.LongLiveError) as e:                                   # an index-only handle takes no tensors
         B._check(L.ll_cross_attn_out(p._h, 1, None, 10, C.cast(C.pointer(one), C.c_void_p), None, None, None))
     assert e.value.status == B.LL_ERR_INVALID_ARG
+    # the workspace of the hand-over between the two kernels: rows rounded up to 16, all heads, bf16
+    assert p.cross_attn_out_workspace_bytes(1) == 16 * p.heads * p.head_dim * 2
+    assert p.cross_attn_out_workspace_bytes(4680) == 4688 * p.heads * p.head_dim * 2
+    assert p.cross_attn_out_workspace_bytes(0) == 0 and L.ll_cross_attn_out_workspace_bytes(3, 96, 100) == 0
+    for heads, head_dim, w, wp in ((0, 128, one, one), (3, 96, one, one), (3, 128, None, one), (3, 128, one, None)):
+        ptr = lambda x: C.cast(C.pointer(x), C.c_void_p) if x is not None else None
+        assert L.ll_out_proj_pack_weight(heads, head_dim, ptr(w), ptr(wp), None) == B.LL_ERR_INVALID_ARG
     p.close()
 
 
