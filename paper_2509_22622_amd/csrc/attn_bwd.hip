@@ -57,6 +57,40 @@ __device__ __forceinline__ void bw_wait_vmcnt() {
 // included); the "memory" clobber keeps the compiler from moving LDS reads across it.
 __device__ __forceinline__ void bw_barrier() { asm volatile("s_barrier" ::: "memory"); }
 
+// Direct-to-LDS loads of the streamed fragments through a buffer descriptor: the region's base and the fragment's
+// offset stay in scalar registers and a lane contributes only its 16 * lane (the flat form keeps a 64-bit address per
+// region in vector registers, which these kernels do not have to spare).  A region of one head is far below 4 GB; the
+// descriptor's range covers everything (offsets are in bounds by construction, as with the flat form).
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t bw_region(const char* base) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(base), 0, 0x7FFFFFFF, 0x00020000);   // raw buffer of dwords
+}
+__device__ __forceinline__ void bw_load_lds16(__amdgpu_buffer_rsrc_t r, char* to, int lane_off, int uniform_off) {
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, (__attribute__((address_space(3))) void*)(to), 16, lane_off, uniform_off, 0, 0);
+}
+
+// LDS reads the compiler does not see (it would place each right before its use): the read leaves `dst` pending until
+// bw_lds_wait<N>(dst) has run with N = LDS reads issued after it by then (the LDS returns data in issue order; further
+// outstanding operations only make the wait longer).  A kernel that uses them must not spill (a spill would store a
+// pending register): tests/test_fp8_mfma_operands.py checks the generated code.
+__device__ __forceinline__ void bw_lds_read(u32x4& dst, unsigned addr, int offset) {
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(dst) : "v"(addr), "n"(offset));
+}
+template <int N>
+__device__ __forceinline__ void bw_lds_wait(u32x4& x) {
+    asm volatile("s_waitcnt lgkmcnt(%1)" : "+v"(x) : "n"(N));
+}
+__device__ __forceinline__ void bw_lds_wait_n(u32x4& x, int n) {
+    switch (n) {
+        case 0: bw_lds_wait<0>(x); break;
+        case 1: bw_lds_wait<1>(x); break;
+        case 2: bw_lds_wait<2>(x); break;
+        case 3: bw_lds_wait<3>(x); break;
+        case 4: bw_lds_wait<4>(x); break;
+        case 5: bw_lds_wait<5>(x); break;
+        default: bw_lds_wait<0>(x); break;
+    }
+}
+
 // Walks the 32-row blocks of a group's streamed ranges in order; past the end it stays on the last block.  The ranges
 // are copied into registers once (no kernel-argument loads inside the loop).
 struct BwRanges { int n, rs0, re0, rs1, re1; };
@@ -81,12 +115,17 @@ __device__ inline void bw_iter_advance(const BwRanges& g, BwIter& it) {
     }
 }
 
-// The streamed blocks go from memory straight into a ring of LDS stages (global_load_lds, one 1 KB fragment per wave
-// and load), PF blocks ahead of the block being worked on.  Per block: issue the loads of block it + PF, wait until
-// this wave's loads of block it have landed (all but the PF * LPW youngest), barrier (every wave's have), compute.
-// A wave can be one block ahead of the slowest one, so the stage it writes, (it + 1 + PF) mod NS, must differ from the
-// one still being read, it mod NS: NS = PF + 2.
-constexpr int BW_PF = 2, BW_NS = 4;
+// The streamed blocks go from memory straight into a ring of LDS stages (direct-to-LDS loads, one 1 KB fragment per
+// wave and load), several blocks ahead of the block being worked on; a stage is overwritten only behind a barrier that
+// every wave reaches after its last read of it.
+//   dK/dV kernel (a stage is 4 kblock regions + the rows' lse and delta, 32 KB at head_dim 128; 4 stages): per block,
+//   wait until this wave's loads of block it have landed, barrier, issue the loads of block it + 3 over the stage of
+//   block it - 1, compute.
+//   dQ kernel (3 regions, 24 KB; 6 stages): a block reads its own stage and, for the scores of the block after it,
+//   the next one.  One barrier per two blocks: wait for everything issued so far (blocks up to it + 2), barrier, issue
+//   blocks it + 3 and it + 4 (over the stages of blocks it - 3 and it - 2), compute blocks it and it + 1.
+constexpr int BW_DQ_NS = 6;
+constexpr int BW_DKV_NS = 4, BW_DKV_PF = BW_DKV_NS - 1;
 
 // Workgroup -> (head, column tile): contiguous runs of items per XCD, as in the forward kernels.
 __device__ inline bool bw_item(int n_tiles, int H, int& head, int& tile) {
@@ -114,7 +153,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     constexpr int KS = D / 16, DB = D / 32;
     constexpr int KB_BYTES = KBLOCK * D * 2;
     constexpr int NREG = 3;                           // streamed regions per block
-    extern __shared__ __attribute__((aligned(16))) char lds[];   // [BW_NS][NREG][KB_BYTES]
+    extern __shared__ __attribute__((aligned(16))) char lds[];   // [BW_DQ_NS][NREG][KB_BYTES]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -155,22 +194,23 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     constexpr int LPW = NREG * FPR / NW;              // loads per wave and block
     static_assert((NREG * FPR) % NW == 0, "fragments must split over the waves");
     const int wave_u = __builtin_amdgcn_readfirstlane(wave);
+    const __amdgpu_buffer_rsrc_t rsrc[NREG] = {bw_region(src[0]), bw_region(src[1]), bw_region(src[2])};
     auto issue = [&](int kblk, int stage) {
 #pragma unroll
         for (int l = 0; l < LPW; ++l) {
-            const int f = wave_u + NW * l, region = f / FPR, fr = f % FPR;      // wave-uniform
-            const char* from = src[region] + int64_t(kblk) * KB_BYTES + fr * 1024 + lane * 16;
+            static_assert(FPR == NW && LPW == NREG, "wave w loads fragment w of every region");
+            const int region = l, fr = wave_u;
             char* to = lds + (stage * NREG + region) * KB_BYTES + fr * 1024;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(from),
-                                             (__attribute__((address_space(3))) void*)(to), 16, 0, 0);
+            bw_load_lds16(rsrc[region], to, lane * 16, kblk * KB_BYTES + fr * 1024);
         }
     };
     const BwRanges gr = bw_ranges(g);
     BwIter li, ci;
     bw_iter_init(gr, li);
     bw_iter_init(gr, ci);
+    constexpr int NS = BW_DQ_NS, PF = 3;              // blocks loaded before the first barrier
 #pragma unroll
-    for (int j = 0; j < BW_PF; ++j) {
+    for (int j = 0; j < PF; ++j) {
         issue(li.kb, j);
         bw_iter_advance(gr, li);
     }
@@ -187,53 +227,84 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
             dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, dof[ks], dp, 0, 0, 0);
         }
     };
-    // One block: the vector work and the row-contracting product of block `it` from its scores (s, dp), and the scores
-    // of block it + 1 (past the end: the last block again, unused) into (s_next, dp_next).
-    auto block = [&](int it, f32x16& s, f32x16& dp, f32x16& s_next, f32x16& dp_next) {
-        issue(li.kb, (it + BW_PF) & (BW_NS - 1));
-        bw_iter_advance(gr, li);
-        bw_wait_vmcnt<(BW_PF - 1) * LPW>();          // this wave's loads of block it + 1 have landed
-        bw_barrier();
+    // One block: the vector work and the row-contracting product of block `it` (stage `st`) from its scores (s, dp),
+    // and the scores of block it + 1 (stage `st_next`; past the end: the last block again, unused) into (s_next, dp_next).
+    // Software pipeline: the score MFMAs of block it + 1 do not depend on the vector work of block it and run under it.
+    int st = 0;                                       // it mod NS
+    u32x4 fr[4];
+    const unsigned lds_lane = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds + lane * 16;
+    auto block = [&](f32x16& s, f32x16& dp, f32x16& s_next, f32x16& dp_next) {
+        const int st_next = st + 1 == NS ? 0 : st + 1;
 
-        const char* blk = lds + (it & (BW_NS - 1)) * NREG * KB_BYTES;
         const int key0 = ci.kb * KBLOCK, cur_rs = ci.rng ? gr.rs1 : gr.rs0, cur_re = ci.rng ? gr.re1 : gr.re0;
         bw_iter_advance(gr, ci);
         if (key0 < cur_rs || key0 + KBLOCK > cur_re)  // uniform: only the blocks at the ends of a range
             bw_kill_dead_rows(s, dp, key0, cur_rs, cur_re, half);
 
-        scores(lds + ((it + 1) & (BW_NS - 1)) * NREG * KB_BYTES, s_next, dp_next);
-
+        // The block's 3 KS operand fragments as one sequence, one MFMA each: 2 KS for the scores of block it + 1 (K'
+        // and V fragments of stage st_next alternating over ks), then KS for the dQ product of block it (K'^T
+        // fragments of stage st).  The reads are issued by hand AHEAD fragments before their MFMA into a ring of RING
+        // register buffers (fragment j in buffer j % RING) with counted waits; the compiler's own order put every read
+        // right before its MFMA and left the LDS latency exposed.  The vector work of block it (exp2, dZ, packing;
+        // independent of the score MFMAs) is dealt out behind them, one register pair per two MFMAs (per MFMA at head_dim 64).
+        constexpr int RING = 4, AHEAD = 3, NSC = 2 * KS, NFR = NSC + 2 * DB;
+        constexpr int PER = NSC / 8;                  // score MFMAs per (t, e) register pair of the vector work
+        static_assert(NSC % 8 == 0, "the vector work's eight register pairs split over the score MFMAs");
+        const unsigned next_a = lds_lane + st_next * NREG * KB_BYTES, cur_a = lds_lane + st * NREG * KB_BYTES;
+        auto read_frag = [&](int j) {
+            if (j < NSC) bw_lds_read(fr[j % RING], next_a, (j & 1) * KB_BYTES + (j >> 1) * 1024);
+            else bw_lds_read(fr[j % RING], cur_a, 2 * KB_BYTES + (((j - NSC) % DB) * 2 + (j - NSC) / DB) * 1024);
+        };
+#pragma unroll
+        for (int j = 0; j < AHEAD; ++j) read_frag(j);
+#pragma unroll
+        for (int r = 0; r < 16; ++r) s_next[r] = dp_next[r] = 0.f;
         unsigned dz[2][4];
 #pragma unroll
-        for (int t = 0; t < 2; ++t)
+        for (int j = 0; j < NFR; ++j) {
+            if (j + AHEAD < NFR) read_frag(j + AHEAD);
+            bw_lds_wait_n(fr[j % RING], NFR - 1 - j < AHEAD ? NFR - 1 - j : AHEAD);
+            const bf16x8 a = __builtin_bit_cast(bf16x8, fr[j % RING]);
+            if (j < NSC) {
+                if (j & 1) dp_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, dof[j >> 1], dp_next, 0, 0, 0);
+                else s_next = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, qf[j >> 1], s_next, 0, 0, 0);
+                if (j % PER == PER - 1) {
+                    const int t = (j / PER) / 4, e = (j / PER) % 4;
+                    float z[2];
 #pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float z[2];
-#pragma unroll
-                for (int k = 0; k < 2; ++k) {
-                    const int r = 8 * t + 2 * e + k;
-                    const float pr = __builtin_amdgcn_exp2f(s[r] - lse);
-                    z[k] = pr * (dp[r] - delta);
+                    for (int k = 0; k < 2; ++k) {
+                        const int r = 8 * t + 2 * e + k;
+                        const float pr = __builtin_amdgcn_exp2f(s[r] - lse);
+                        z[k] = pr * (dp[r] - delta);
+                    }
+                    dz[t][e] = bw_pack_bf16(z[0], z[1]);
                 }
-                dz[t][e] = bw_pack_bf16(z[0], z[1]);
-            }
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const u32x4 bv = {dz[t][0], dz[t][1], dz[t][2], dz[t][3]};
-#pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const bf16x8 a = *reinterpret_cast<const bf16x8*>(blk + 2 * KB_BYTES + (db * 2 + t) * 1024 + lane * 16);
+            } else {
+                const int t = (j - NSC) / DB, db = (j - NSC) % DB;
+                const u32x4 bv = {dz[t][0], dz[t][1], dz[t][2], dz[t][3]};
                 acc[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, bv), acc[db], 0, 0, 0);
             }
         }
+        st = st_next;
     };
     f32x16 s0, dp0, s1, dp1;
-    bw_wait_vmcnt<(BW_PF - 1) * LPW>();              // block 0 has landed
+    bw_wait_vmcnt<0>();
     bw_barrier();
     scores(lds, s0, dp0);
     for (int it = 0; it < n_blocks; it += 2) {       // two blocks per trip: the two score sets swap roles, no copies
-        block(it, s0, dp0, s1, dp1);
-        if (it + 1 < n_blocks) block(it + 1, s1, dp1, s0, dp0);
+        if (it > 0) {
+            bw_wait_vmcnt<0>();
+            bw_barrier();
+        }
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            int sj = st + 3 + j;
+            if (sj >= NS) sj -= NS;
+            issue(li.kb, sj);
+            bw_iter_advance(gr, li);
+        }
+        block(s0, dp0, s1, dp1);
+        if (it + 1 < n_blocks) block(s1, dp1, s0, dp0);
     }
     bw_wait_vmcnt<0>();                               // the loads issued past the end have landed before the wave leaves
 
@@ -256,7 +327,7 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     constexpr int KS = D / 16, DB = D / 32;
     constexpr int KB_BYTES = KBLOCK * D * 2;
     constexpr int NREG = 4;
-    extern __shared__ __attribute__((aligned(16))) char lds[];   // [BW_NS][NREG x KB_BYTES | 256]
+    extern __shared__ __attribute__((aligned(16))) char lds[];   // [BW_DKV_NS][NREG x KB_BYTES | 256]
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int col = lane & 31, half = lane >> 5;
@@ -299,79 +370,114 @@ __global__ __launch_bounds__(NW * 64) __attribute__((amdgpu_waves_per_eu(2, 2)))
     // number of loads).
     constexpr int STAGE_BYTES = NREG * KB_BYTES + 256;
     const float* aux_src = (lane < 32 ? lse_h : delta_h - 32) + lane;
+    const __amdgpu_buffer_rsrc_t rsrc[NREG] = {bw_region(src[0]), bw_region(src[1]), bw_region(src[2]), bw_region(src[3])};
     auto issue = [&](int blk_i, int stage) {
 #pragma unroll
         for (int l = 0; l < LPW; ++l) {
-            const int f = wave_u + NW * l, region = f / FPR, fr = f % FPR;
-            const char* from = src[region] + int64_t(blk_i) * KB_BYTES + fr * 1024 + lane * 16;
+            static_assert(FPR == NW && LPW == NREG, "wave w loads fragment w of every region");
+            const int region = l, fr = wave_u;
             char* to = lds + stage * STAGE_BYTES + region * KB_BYTES + fr * 1024;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(from),
-                                             (__attribute__((address_space(3))) void*)(to), 16, 0, 0);
+            bw_load_lds16(rsrc[region], to, lane * 16, blk_i * KB_BYTES + fr * 1024);
         }
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(aux_src + blk_i * KBLOCK),
                                          (__attribute__((address_space(3))) void*)(lds + stage * STAGE_BYTES + NREG * KB_BYTES), 4, 0, 0);
     };
     constexpr int LOADS = LPW + 1;                    // per wave and block
+    constexpr int NS = BW_DKV_NS, PF = BW_DKV_PF;
+    static_assert((NS & (NS - 1)) == 0, "stage index by mask");
 #pragma unroll
-    for (int j = 0; j < BW_PF; ++j) issue(min(qb_begin + j, qb_end - 1), j);
+    for (int j = 0; j < PF; ++j) issue(min(qb_begin + j, qb_end - 1), j);
+
+    // One block = 32 operand fragments from LDS, one MFMA each (16 for the two feature-contracting products S and dP,
+    // then, behind the vector work that turns them into P and dZ, 16 for the two row-contracting products).  The reads
+    // are issued by hand, AHEAD fragments before the MFMA that consumes them, into a ring of RING register buffers,
+    // with counted waits (bw_lds_wait<N>: N = reads issued since); the compiler's own order put every read right
+    // before its MFMA and left the LDS latency exposed 16 times per block.  Fragment i of a part lives in buffer i % RING;
+    // a buffer is read again only behind the MFMA that consumed it.
+    constexpr int RING = 4, AHEAD = 3, NF = 2 * KS;   // NF fragments per part
+    static_assert(2 * DB * 2 == NF, "both parts have 2 KS fragments");
+    u32x4 fr[RING];
+    const unsigned lds_lane = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds + lane * 16;
+    // byte offset of fragment i inside a stage: part 0 = q' (K-style), dO (K-style) alternating over ks;
+    // part 1 = dO^T, q'^T (V^T-style) alternating over (t, db)
+    auto frag_off = [&](int part, int i) constexpr {
+        return part == 0 ? (i & 1) * KB_BYTES + (i >> 1) * 1024
+                         : (2 + (i & 1)) * KB_BYTES + (((i >> 1) % DB) * 2 + (i >> 1) / DB) * 1024;
+    };
+    unsigned pw[2][4], dz[2][4];
+    f32x16 s, dp;
+    // P and dZ of half t of the block's rows from the scores, rounded to bf16 (vector pipe only).  Register r stands
+    // for query row0 + 16(r/8) + 8 half + r%8: its lse and delta come from the stage's last 256 bytes, 8 consecutive
+    // values per (t, half) (rows past the clip read the zero padding of the two vectors; they are dead rows).
+    auto weights = [&](const char* blk, int t) {
+        const float* aux = reinterpret_cast<const float*>(blk + NREG * KB_BYTES);
+        const int rb = 16 * t + 8 * half;
+        const f32x4 l0 = *reinterpret_cast<const f32x4*>(aux + rb), l1 = *reinterpret_cast<const f32x4*>(aux + rb + 4);
+        const f32x4 d0 = *reinterpret_cast<const f32x4*>(aux + 32 + rb), d1 = *reinterpret_cast<const f32x4*>(aux + 32 + rb + 4);
+        const float lv[8] = {l0[0], l0[1], l0[2], l0[3], l1[0], l1[1], l1[2], l1[3]};
+        const float dl[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            float pv[2], zv[2];
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                const int r = 8 * t + 2 * e + k;
+                const float pr = __builtin_amdgcn_exp2f(s[r] - lv[2 * e + k]);
+                pv[k] = pr;
+                zv[k] = pr * (dp[r] - dl[2 * e + k]);
+            }
+            pw[t][e] = bw_pack_bf16(pv[0], pv[1]);
+            dz[t][e] = bw_pack_bf16(zv[0], zv[1]);
+        }
+    };
 
     for (int it = 0; it < n_blocks; ++it) {
-        const int qb = qb_begin + it;
-        issue(min(qb + BW_PF, qb_end - 1), (it + BW_PF) & (BW_NS - 1));
-        bw_wait_vmcnt<BW_PF * LOADS>();
+        bw_wait_vmcnt<(PF - 1) * LOADS>();            // this wave's loads of block it have landed
         bw_barrier();
+        issue(min(qb_begin + it + PF, qb_end - 1), (it + PF) & (NS - 1));    // over the stage of block it - 1
+        const unsigned st_a = lds_lane + (it & (NS - 1)) * STAGE_BYTES;
+        const char* blk = lds + (it & (NS - 1)) * STAGE_BYTES;
 
-        const char* blk = lds + (it & (BW_NS - 1)) * STAGE_BYTES;
-        const int row0 = qb * KBLOCK;
-
-        f32x16 s, dp;
+        // part 0: S and dP
+#pragma unroll
+        for (int i = 0; i < AHEAD; ++i) bw_lds_read(fr[i % RING], st_a, frag_off(0, i));
 #pragma unroll
         for (int r = 0; r < 16; ++r) s[r] = dp[r] = 0.f;
 #pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-            const bf16x8 aq = *reinterpret_cast<const bf16x8*>(blk + ks * 1024 + lane * 16);
-            const bf16x8 ad = *reinterpret_cast<const bf16x8*>(blk + KB_BYTES + ks * 1024 + lane * 16);
-            s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq, kf[ks], s, 0, 0, 0);
-            dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ad, vf[ks], dp, 0, 0, 0);
+        for (int i = 0; i < NF; ++i) {
+            if (i + AHEAD < NF) bw_lds_read(fr[(i + AHEAD) % RING], st_a, frag_off(0, i + AHEAD));
+            bw_lds_wait_n(fr[i % RING], NF - 1 - i < AHEAD ? NF - 1 - i : AHEAD);
+            const bf16x8 a = __builtin_bit_cast(bf16x8, fr[i % RING]);
+            if (i & 1) dp = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, vf[i >> 1], dp, 0, 0, 0);
+            else s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, kf[i >> 1], s, 0, 0, 0);
         }
-        if (row0 < row_lo || row0 + KBLOCK > row_hi)     // uniform: only the blocks at the ends of the range
+        const int row0 = (qb_begin + it) * KBLOCK;
+        if (row0 < row_lo || row0 + KBLOCK > row_hi) {   // uniform: only the blocks at the ends of the range
+            asm volatile("" ::: "memory");
             bw_kill_dead_rows(s, dp, row0, row_lo, row_hi, half);
-        // register r stands for query row0 + 16(r/8) + 8 half + r%8: its lse and delta come from the stage's last
-        // 256 bytes, 8 consecutive values per (t, half) (rows past the clip read the zero padding of the two vectors;
-        // they are dead rows)
-        unsigned pw[2][4], dz[2][4];
-        const float* aux = reinterpret_cast<const float*>(blk + NREG * KB_BYTES);
-#pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const int rb = 16 * t + 8 * half;
-            const f32x4 l0 = *reinterpret_cast<const f32x4*>(aux + rb), l1 = *reinterpret_cast<const f32x4*>(aux + rb + 4);
-            const f32x4 d0 = *reinterpret_cast<const f32x4*>(aux + 32 + rb), d1 = *reinterpret_cast<const f32x4*>(aux + 32 + rb + 4);
-            const float lv[8] = {l0[0], l0[1], l0[2], l0[3], l1[0], l1[1], l1[2], l1[3]};
-            const float dl[8] = {d0[0], d0[1], d0[2], d0[3], d1[0], d1[1], d1[2], d1[3]};
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                float pv[2], zv[2];
-#pragma unroll
-                for (int k = 0; k < 2; ++k) {
-                    const int r = 8 * t + 2 * e + k;
-                    const float pr = __builtin_amdgcn_exp2f(s[r] - lv[2 * e + k]);
-                    pv[k] = pr;
-                    zv[k] = pr * (dp[r] - dl[2 * e + k]);
-                }
-                pw[t][e] = bw_pack_bf16(pv[0], pv[1]);
-                dz[t][e] = bw_pack_bf16(zv[0], zv[1]);
-            }
         }
+        // the first fragments of part 1 are read while the second half of the vector work runs (not earlier: the
+        // registers of the scores' first half are free only then)
+        weights(blk, 0);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int t = 0; t < 2; ++t) {
-            const u32x4 bp = {pw[t][0], pw[t][1], pw[t][2], pw[t][3]};
-            const u32x4 bz = {dz[t][0], dz[t][1], dz[t][2], dz[t][3]};
+        for (int i = 0; i < AHEAD; ++i) bw_lds_read(fr[i % RING], st_a, frag_off(1, i));
+        weights(blk, 1);
+        __builtin_amdgcn_sched_barrier(0);
+
+        // part 1: dV^T += dO^T P, Gk^T += q'^T dZ; fragment i is (t, db) = ((i / 2) / DB, (i / 2) % DB), dO^T then q'^T
 #pragma unroll
-            for (int db = 0; db < DB; ++db) {
-                const bf16x8 a_d = *reinterpret_cast<const bf16x8*>(blk + 2 * KB_BYTES + (db * 2 + t) * 1024 + lane * 16);
-                const bf16x8 a_q = *reinterpret_cast<const bf16x8*>(blk + 3 * KB_BYTES + (db * 2 + t) * 1024 + lane * 16);
-                acc_v[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_d, __builtin_bit_cast(bf16x8, bp), acc_v[db], 0, 0, 0);
-                acc_k[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a_q, __builtin_bit_cast(bf16x8, bz), acc_k[db], 0, 0, 0);
+        for (int i = 0; i < NF; ++i) {
+            if (i + AHEAD < NF) bw_lds_read(fr[(i + AHEAD) % RING], st_a, frag_off(1, i + AHEAD));
+            bw_lds_wait_n(fr[i % RING], NF - 1 - i < AHEAD ? NF - 1 - i : AHEAD);
+            const bf16x8 a = __builtin_bit_cast(bf16x8, fr[i % RING]);
+            const int t = (i >> 1) / DB, db = (i >> 1) % DB;
+            if (i & 1) {
+                const u32x4 bz = {dz[t][0], dz[t][1], dz[t][2], dz[t][3]};
+                acc_k[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, bz), acc_k[db], 0, 0, 0);
+            } else {
+                const u32x4 bp = {pw[t][0], pw[t][1], pw[t][2], pw[t][3]};
+                acc_v[db] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, bp), acc_v[db], 0, 0, 0);
             }
         }
     }
@@ -473,7 +579,7 @@ int bwd_tile_cols(int D) { return D == 128 ? 256 : 128; }
 hipError_t launch_bwd_dq(const BwdParams& p, hipStream_t s) {
     const int total = p.n_tiles * p.H;
     if (total <= 0) return hipSuccess;
-    const int grid = ((total + 7) / 8) * 8, lds = BW_NS * 3 * KBLOCK * p.D * 2;
+    const int grid = ((total + 7) / 8) * 8, lds = BW_DQ_NS * 3 * KBLOCK * p.D * 2;
     static bool done128 = false, done64 = false;
     if (p.D == 128) {
         hipError_t e = set_lds(reinterpret_cast<const void*>(ll_bwd_dq_kernel<128, 8>), lds, done128);
@@ -490,7 +596,7 @@ hipError_t launch_bwd_dq(const BwdParams& p, hipStream_t s) {
 hipError_t launch_bwd_dkv(const BwdParams& p, hipStream_t s) {
     const int total = p.n_tiles * p.H;
     if (total <= 0) return hipSuccess;
-    const int grid = ((total + 7) / 8) * 8, lds = BW_NS * (4 * KBLOCK * p.D * 2 + 256);
+    const int grid = ((total + 7) / 8) * 8, lds = BW_DKV_NS * (4 * KBLOCK * p.D * 2 + 256);
     static bool done128 = false, done64 = false;
     if (p.D == 128) {
         hipError_t e = set_lds(reinterpret_cast<const void*>(ll_bwd_dkv_kernel<128, 8>), lds, done128);

@@ -53,3 +53,18 @@ def test_bf16_stream_kernels_do_not_spill(source, kernel):
     spills = dict(re.findall(r"\.name:\s+(\S+)[\s\S]*?\.vgpr_spill_count:\s+(\d+)", text))
     stream = {k: int(v) for k, v in spills.items() if kernel + "I" in k}
     assert len(stream) >= 6 and all(v == 0 for v in stream.values()), f"spills: {stream}"
+
+
+def test_backward_kernels_do_not_spill():
+    """The two backward kernels of the train-time rule issue their LDS fragment reads by hand, with counted waits:
+    a spill of a fragment register between its read and its wait would store stale data."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    src = os.path.join(ROOT, "paper_2509_22622_amd", "csrc", "attn_bwd.hip")
+    with tempfile.TemporaryDirectory() as tmp:
+        out = os.path.join(tmp, "attn_bwd.s")
+        subprocess.run([hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-Xclang", "-target-feature", "-Xclang",
+                        "-packed-fp32-ops", "-S", "--cuda-device-only", src, "-o", out], check=True, capture_output=True)
+        text = open(out).read()
+    spills = dict(re.findall(r"\.name:\s+(\S+)[\s\S]*?\.vgpr_spill_count:\s+(\d+)", text))
+    kernels = {k: int(v) for k, v in spills.items() if "ll_bwd_dq_kernel" in k or "ll_bwd_dkv_kernel" in k}
+    assert len(kernels) == 4 and all(v == 0 for v in kernels.values()), f"spills: {kernels}"
