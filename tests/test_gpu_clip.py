@@ -1,12 +1,14 @@
 """The train-time rule on the GPU (ll_clip_forward, ll_clip_backward) against the fp64 oracle.
 
-Tolerances.  Forward: those of the inference path (max-abs 1e-2, relative L2 5e-3).  Gradients: the backward kernels
-rebuild the softmax weights P from bf16 operands, round P and dZ = P (dP - delta) to bf16 for the second products and
-the results to bf16 again; each rounding is 2^-9 relative and they add up over three stages in which errors of
-different keys average out (delta itself is taken from the forward's unrounded output, so it adds nothing).  Measured:
-3.1e-3 to 3.8e-3 at ordinary shapes, 5.8e-3 at the worst of 300 random geometries (2 queries, 5 keys, one key holding
-most of the weight: nothing averages out).  Relative L2 <= 8e-3 per gradient tensor, and no element further off than
-2 % of the tensor's largest magnitude.
+Tolerances.  Forward: those of the inference path (max-abs 1e-2, relative L2 5e-3).  Gradients: derived from the
+number of bf16 roundings on each tensor's way (tests/test_grad_rounding_model.py has the derivation and checks it on
+the CPU with a rounding model of this path): with unit roundoff u = 2^-8 and rho = u / sqrt(3) per rounding, n_r = 5
+roundings for dq and dk, 4 for dv, independent and averaged over many terms,
+    relative L2 <= sqrt(n_r) rho = 5.0e-3 (dq, dk), 4.5e-3 (dv)          [the model and the kernels: 3.1e-3 to 3.9e-3]
+where nothing averages (a handful of keys with one dominant: `few_terms`) each rounding may sit at its maximum,
+    relative L2 <= sqrt(n_r) u = 8.7e-3 (dq, dk), 7.8e-3 (dv)            [worst of 300 random geometries: 5.8e-3]
+and no element is further off than n_r u = 2 % (1.6 % for dv) of the tensor's largest magnitude.  delta = dO . O is
+taken from the forward's unrounded output, so it adds no rounding of its own.
 """
 import numpy as np
 import pytest
@@ -21,15 +23,24 @@ import gpu_harness as H
 
 pytestmark = pytest.mark.gpu
 
-GRAD_REL_L2 = 8e-3
-GRAD_MAX_FRAC = 2e-2
+U_BF16 = 2.0 ** -8
+N_ROUNDINGS = {"dq": 5, "dk": 5, "dv": 4}
+
+
+def grad_rel_l2(name, few_terms=False):
+    return float(np.sqrt(N_ROUNDINGS[name]) * (U_BF16 if few_terms else U_BF16 / np.sqrt(3.0)))
+
+
+def grad_max_frac(name):
+    return N_ROUNDINGS[name] * U_BF16
 
 
 def bits(shape, stream, tensor, cfg_id=41):
     return synth.normal_bf16(shape, cfg_id, 0, stream, tensor)
 
 
-def run_case(heads, head_dim, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip, seed=0, dout_rows=None, q_scale=1.0):
+def run_case(heads, head_dim, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip, seed=0, dout_rows=None, q_scale=1.0,
+             few_terms=False):
     cfg = OracleConfig(1, heads, head_dim, gh, gw, C, S, W)
     P = gh * gw
     oracle = ClipOracle(cfg)
@@ -56,7 +67,7 @@ def run_case(heads, head_dim, gh, gw, C, S, W, T, ctx_start, n_ctx, n_clip, seed
         g = bf16_bits_to_f64(H.to_bits(t))
         assert np.isfinite(g).all(), f"{what} {name}: non-finite"
         max_abs, rel = error_metrics(g, w)
-        assert rel <= GRAD_REL_L2 * q_scale and max_abs <= GRAD_MAX_FRAC * q_scale * np.abs(w).max(), \
+        assert rel <= grad_rel_l2(name, few_terms) * q_scale and max_abs <= grad_max_frac(name) * q_scale * np.abs(w).max(), \
             f"{what} {name}: max_abs {max_abs:.3e} of {np.abs(w).max():.3e}, rel_l2 {rel:.3e}"
         got[name] = g
     clip.close()
@@ -108,7 +119,7 @@ def test_second_step_with_a_shorter_clip_reuses_the_handle():
         H.assert_parity(H.to_bits(out), oracle.forward(ctx_start, n_ctx, n_clip, *(bf16_bits_to_f64(t) for t in (q, k, v))), f"step {step}")
         for name, t, w in zip(("dq", "dk", "dv"), (dq, dk, dv), oracle.backward(bf16_bits_to_f64(dout))):
             max_abs, rel = error_metrics(bf16_bits_to_f64(H.to_bits(t)), w)
-            assert rel <= GRAD_REL_L2, f"step {step} {name}: rel_l2 {rel:.3e}"
+            assert rel <= grad_rel_l2(name), f"step {step} {name}: rel_l2 {rel:.3e}"
     clip.close()
 
 
@@ -193,7 +204,7 @@ def test_one_dominant_key():
     """Two queries over five keys, one key holding most of each row's weight: dP - delta is then a small difference of
     large numbers, and a delta taken from the bf16-rounded output would be off by about 2^-9 |dO||O|, 2.5 % of dK
     here.  The handle keeps the forward's output unrounded for this."""
-    run_case(1, 128, 1, 1, 4, 3, 3, 2, 27, 0, 2, seed=238)
+    run_case(1, 128, 1, 1, 4, 3, 3, 2, 27, 0, 2, seed=238, few_terms=True)
 
 
 def test_bench_shape_sampled():
@@ -226,5 +237,5 @@ def test_bench_shape_sampled():
         g = bf16_bits_to_f64(H.to_bits(t)[rows][:, sel, :])
         assert np.isfinite(g).all()
         max_abs, rel = error_metrics(g, w)
-        assert rel <= GRAD_REL_L2 and max_abs <= GRAD_MAX_FRAC * np.abs(w).max(), f"{name}: max_abs {max_abs:.3e} of {np.abs(w).max():.3e}, rel_l2 {rel:.3e}"
+        assert rel <= grad_rel_l2(name) and max_abs <= grad_max_frac(name) * np.abs(w).max(), f"{name}: max_abs {max_abs:.3e} of {np.abs(w).max():.3e}, rel_l2 {rel:.3e}"
     clip.close()
