@@ -167,6 +167,31 @@ __device__ __forceinline__ void s16_segment(const AttnParams& p, const AttnChunk
 #define S16_PHYS_KB(v) ((v) + s16_pick((v), n0, n01, kb0, kb1 - n0, kb2 - n01))
 #define S16_LIVE(v) s16_live_mask(S16_PHYS_KB(v) * KBLOCK, s16_pick((v), n0, n01, rs0, rs1, rs2), s16_pick((v), n0, n01, re0, re1, re2), g)
 
+    const char* kbase = reinterpret_cast<const char*>(p.k_cache + head * p.head_stride);
+    const char* vbase = reinterpret_cast<const char*>(p.v_cache + head * p.head_stride);
+
+    const unsigned lane_off = lane * 16;
+    const unsigned k_load_off = s16_k_load_offset(lane);
+    // LDS byte address of this lane's 16 bytes in fragment 0 of stage 0; fragment f of a kind adds s16_frag(f)
+    const unsigned lds_a = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds + g * 512 + n * 16;
+#define S16_FRAG(f) (((f) >> 1) * 2048 + ((f) & 1) * 256)
+    auto issue_load = [&](int kb, int stage, int l) {
+        const int64_t kb_off = int64_t(kb) * KB_BYTES;
+        const int f = wave + NW * l;            // fragment of the stage this wave fetches (wave-uniform)
+        const char* src = (f < KS ? kbase + f * 1024 + k_load_off : vbase + (f - KS) * 1024 + lane_off) + kb_off;
+        char* dst = lds + stage * STAGE_BYTES + f * 1024;
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),
+                                         (__attribute__((address_space(3))) void*)(dst), 16, 0, 0);
+    };
+
+    // the ring's first loads go out before the queries are fetched: one memory latency for both
+#pragma unroll
+    for (int j = 0; j < PF; ++j) {
+        const int v = min(vb + j, ve - 1);
+#pragma unroll
+        for (int l = 0; l < LPW; ++l) issue_load(S16_PHYS_KB(v), (vb + j) & (NS - 1), l);
+    }
+
     // Q^T fragments (pre-scaled by log2(e)/sqrt(D)): fragment (qb, s) holds features 32 s + 8 g + 0..7 of query q0 + 16 qb + n
     bf16x8 qf[2][NQ];
     const uint16_t* q_src[2];
@@ -205,29 +230,6 @@ __device__ __forceinline__ void s16_segment(const AttnParams& p, const AttnChunk
                 }
     }
 
-    const char* kbase = reinterpret_cast<const char*>(p.k_cache + head * p.head_stride);
-    const char* vbase = reinterpret_cast<const char*>(p.v_cache + head * p.head_stride);
-
-    const unsigned lane_off = lane * 16;
-    const unsigned k_load_off = s16_k_load_offset(lane);
-    // LDS byte address of this lane's 16 bytes in fragment 0 of stage 0; fragment f of a kind adds s16_frag(f)
-    const unsigned lds_a = (unsigned)(size_t)(__attribute__((address_space(3))) char*)lds + g * 512 + n * 16;
-#define S16_FRAG(f) (((f) >> 1) * 2048 + ((f) & 1) * 256)
-    auto issue_load = [&](int kb, int stage, int l) {
-        const int64_t kb_off = int64_t(kb) * KB_BYTES;
-        const int f = wave + NW * l;            // fragment of the stage this wave fetches (wave-uniform)
-        const char* src = (f < KS ? kbase + f * 1024 + k_load_off : vbase + (f - KS) * 1024 + lane_off) + kb_off;
-        char* dst = lds + stage * STAGE_BYTES + f * 1024;
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(src),
-                                         (__attribute__((address_space(3))) void*)(dst), 16, 0, 0);
-    };
-
-#pragma unroll
-    for (int j = 0; j < PF; ++j) {
-        const int v = min(vb + j, ve - 1);
-#pragma unroll
-        for (int l = 0; l < LPW; ++l) issue_load(S16_PHYS_KB(v), (vb + j) & (NS - 1), l);
-    }
     s16_wait_vmcnt<(PF - LAND) * LPW>();
     __builtin_amdgcn_s_barrier();
 
