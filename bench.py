@@ -1,7 +1,9 @@
 """Benchmark of the sink+window attention hot path on one MI355X.
 
 A step is one pass of the hot path over one 3-frame chunk: for each of the 30 layers,
-ll_chunk_append (rotary + ring write) then ll_sink_window_attn, at the Wan-1.3B shape
+ll_chunk_append (rotary + ring write of the keys and values) then ll_sink_window_attn_unrotated (the attention
+kernel turns the queries as it loads them; --two-call-step: the rotated queries go through memory and
+ll_sink_window_attn reads them), at the Wan-1.3B shape
 (12 heads x 128, 1560 tokens/frame, sink 3, window 9, chunk 3: 4680 queries x 23400
 keys per layer) in steady state (ring full, wrapping).  Prints ONE JSON line.
 """
@@ -19,8 +21,8 @@ PEAK_BF16_TFLOPS = 2516.6      # MI355X dense bf16 MFMA: 256 CU x 4096 flop/clk 
 PEAK_HBM_GBS = 8000.0
 # HBM bytes per attention launch: a constant recorded from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs of this
 # workload (profiles/attn_wan_layer_pmc.txt), not measured by the run that prints it:
-# fetch 100814 KiB x 2.0 (scale from a device copy of known size in the same run) + write 14170 KiB x 1.0
-ATTN_HBM_TRAFFIC_BYTES = int(100814 * 1024 * 2.0 + 14170 * 1024 * 1.0)
+# fetch 100941 KiB x 2.0 (scale from a device copy of known size in the same run) + write 14042 KiB x 1.0
+ATTN_HBM_TRAFFIC_BYTES = int(100941 * 1024 * 2.0 + 14042 * 1024 * 1.0)
 ATTN_HBM_TRAFFIC_SOURCE = "profiles/attn_wan_layer_pmc.txt (recorded constant: 1.28 x the algorithmic bytes, 16 (head, XCD) K/V streams for 12 heads)"
 
 
@@ -379,6 +381,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--variant", type=int, default=0, help="attention kernel variant (0 = default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--two-call-step", action="store_true",
+                    help="time ll_chunk_append(q, q_out) + ll_sink_window_attn(q_out) instead of the pair that keeps the "
+                         "rotated queries out of memory")
     ap.add_argument("--no-recache", action="store_true")
     ap.add_argument("--no-fp8", action="store_true", help="leave out the figures of the 8-bit cache variant")
     ap.add_argument("--fp8-only", action="store_true",
@@ -442,10 +447,16 @@ def main():
             if timed:
                 e0, e1, e2 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
                 e0.record()
-            cache.chunk_append(l, f0, Cf, q[i, l], k[i, l], v[i, l], qr[l])
+            if args.two_call_step:                 # rotated queries written by the append, read by the attention
+                cache.chunk_append(l, f0, Cf, q[i, l], k[i, l], v[i, l], qr[l])
+            else:                                  # keys and values only; the attention kernel turns the queries
+                cache.chunk_append(l, f0, Cf, None, k[i, l], v[i, l], None)
             if timed:
                 e1.record()
-            cache.sink_window_attn(l, qr[l], out[l])
+            if args.two_call_step:
+                cache.sink_window_attn(l, qr[l], out[l])
+            else:
+                cache.sink_window_attn_unrotated(l, q[i, l], out[l])
             if timed:
                 e2.record()
                 events.append((e0, e1, e2))
@@ -455,7 +466,10 @@ def main():
     for _ in range(n_fill):                                    # fill the caches: appends only, so that every
         f0, i = chunk * Cf, chunk % pool                       # attention launch of this run has the steady shape
         for l in range(L):
-            cache.chunk_append(l, f0, Cf, q[i, l], k[i, l], v[i, l], qr[l])
+            if args.two_call_step:
+                cache.chunk_append(l, f0, Cf, q[i, l], k[i, l], v[i, l], qr[l])
+            else:
+                cache.chunk_append(l, f0, Cf, None, k[i, l], v[i, l], None)
         chunk += 1
     for _ in range(args.warmup):
         step()
@@ -473,19 +487,21 @@ def main():
     fl_layer = attn_flops(nq, nk, D, Hh)
     tflops = fl_layer * L / (ms_per_step * 1e-3) / 1e12
     attn_tflops = fl_layer / (attn_ms * 1e-3) / 1e12
-    append_bytes = 4 * nq * Hh * D * 2 + 2 * nq * Hh * D * 2       # read q,k,v + write q', K', V
+    # read q, k, v + write q', K', V; without the queries when the attention kernel turns them itself
+    append_bytes = (6 if args.two_call_step else 4) * nq * Hh * D * 2
     res = {
         "metric": "sink+window attn TFLOP/s & ms per 3-frame chunk (30 layers); % bf16 MFMA peak",
         "value": round(tflops, 2), "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "wan1.3b-30layers: 30 layers x (12 heads x 128, 1560 tok/frame, chunk 3, sink 3, window 9; "
-                               "4680 queries x 23400 keys), steady state, append + attention per layer",
+                               "4680 queries x 23400 keys), steady state, append + attention per layer"
+                               + ("" if args.two_call_step else " (ll_chunk_append of keys and values, ll_sink_window_attn_unrotated)"),
                    "attn_variant": binding.attn_variant_names().get(args.variant, "default")},
         "pct_of_bf16_mfma_peak": round(100 * tflops / PEAK_BF16_TFLOPS, 2),
         "attn_ms_per_layer": round(attn_ms, 4), "append_ms_per_layer": round(append_ms, 4),
         "append_GBps": round(append_bytes / (append_ms * 1e-3) / 1e9, 1),
-        "roofline": {"bound": "mfma", "kernel": "ll_attn_stream16_kernel<128, false, false>", "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS,
+        "roofline": {"bound": "mfma", "kernel": "ll_attn_stream16_kernel<128, false, false, %d>" % (9 if args.two_call_step else 25), "achieved": round(attn_tflops, 2), "peak": PEAK_BF16_TFLOPS,
                      "unit": "TFLOP/s", "frac": round(attn_tflops / PEAK_BF16_TFLOPS, 4), "traffic": ATTN_HBM_TRAFFIC_BYTES,
                      "traffic_source": ATTN_HBM_TRAFFIC_SOURCE,
                      "flops_per_launch": fl_layer, "avg_launch_ms": round(attn_ms, 4),
@@ -506,8 +522,12 @@ def main():
     f0g, ig = (chunk - 1) * Cf, (chunk - 1) % pool
     def repass():
         for l in range(L):
-            cache.chunk_append(l, f0g, Cf, q[ig, l], k[ig, l], v[ig, l], qr[l])
-            cache.sink_window_attn(l, qr[l], out[l])
+            if args.two_call_step:
+                cache.chunk_append(l, f0g, Cf, q[ig, l], k[ig, l], v[ig, l], qr[l])
+                cache.sink_window_attn(l, qr[l], out[l])
+            else:
+                cache.chunk_append(l, f0g, Cf, None, k[ig, l], v[ig, l], None)
+                cache.sink_window_attn_unrotated(l, q[ig, l], out[l])
     repass()
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()

@@ -108,7 +108,9 @@ ll_status ll_cache_reset(ll_cache* cache, int layer);
  *   frame_start equal to staged start + its length -> the staged chunk becomes permanent,
  *       frames older than frame_start - W (non-sink) stop being live, sink frames stay;
  *   first call after create/reset must have frame_start 0; anything else -> LL_ERR_STATE.
- *   1 <= n_frames <= chunk_frames.  q, k, v, q_out: device, [n_frames*P, H, D] bf16. */
+ *   1 <= n_frames <= chunk_frames.  q, k, v, q_out: device, [n_frames*P, H, D] bf16.
+ *   q and q_out may both be NULL (bf16 cache): keys and values only; the chunk's queries then go, unrotated, to
+ *   ll_sink_window_attn_unrotated, and the rotated queries never pass through memory. */
 ll_status ll_chunk_append(ll_cache* cache, int layer, int64_t frame_start, int n_frames,
                           const void* q, const void* k, const void* v, void* q_out,
                           void* stream);
@@ -120,6 +122,15 @@ ll_status ll_chunk_append(ll_cache* cache, int layer, int64_t frame_start, int n
  *   LL_ERR_STATE if no chunk is staged. */
 ll_status ll_sink_window_attn(ll_cache* cache, int layer, const void* q_roped, void* out,
                               void* stream);
+/* The same attention (Sec. 3.3) from the queries as the model's projection made them: q: device, [Nq, H, D] bf16,
+ * unrotated and unscaled, the rows of the staged chunk's frames in order.  The kernel applies the 3D rotary
+ * embedding at each row's (absolute frame, row, column) and the factor log2(e)/sqrt(D) as it loads the queries, with
+ * the arithmetic and the one rounding of ll_chunk_append's q_out, so the result is bit for bit that of
+ * ll_chunk_append(q, q_out) followed by ll_sink_window_attn(q_out).  The chunk must have been staged by
+ * ll_chunk_append (with or without queries) or ll_recache_prefill on the same stream before.  out must not alias q.
+ * bf16 cache only (LL_ERR_UNSUPPORTED for an 8-bit cache, for a chunk whose sink is re-indexed by
+ * ll_cache_set_sink_relative, and while a diagnostic kernel variant is forced); other errors as above. */
+ll_status ll_sink_window_attn_unrotated(ll_cache* cache, int layer, const void* q, void* out, void* stream);
 
 /* KV-recache for one layer (Sec. 3.1 "KV Recache"; Sec. 3.3 last sentence; Alg. 2 line
  * "recache"): rebuild the cache from frames [0, S) (if include_sink) followed by

@@ -28,6 +28,7 @@ SIGNATURES = {
     "ll_cache_reset": (_i, [_vp, _i]),
     "ll_chunk_append": (_i, [_vp, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]),
     "ll_sink_window_attn": (_i, [_vp, _i, _vp, _vp, _vp]),
+    "ll_sink_window_attn_unrotated": (_i, [_vp, _i, _vp, _vp, _vp]),
     "ll_recache_prefill": (_i, [_vp, _i, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]),
     "ll_recache_prefill_static": (_i, [_vp, _i, _i, _i64, _i, _vp, _vp, _vp, _vp, _vp]),
     "ll_cache_live_frames": (_i, [_vp, _i, C.POINTER(_i64), _i, C.POINTER(_i)]),
@@ -195,11 +196,16 @@ class Cache:
         _check(lib().ll_cache_reset(self._h, layer))
 
     def chunk_append(self, layer, frame_start, n_frames, q=None, k=None, v=None, q_out=None):
-        stream = _stream() if q is not None else None
+        """q and q_out None with k, v given: keys and values only (the queries go to sink_window_attn_unrotated)."""
+        stream = _stream() if k is not None else None
         _check(lib().ll_chunk_append(self._h, layer, frame_start, n_frames, _ptr(q), _ptr(k), _ptr(v), _ptr(q_out), stream))
 
     def sink_window_attn(self, layer, q_roped, out):
         _check(lib().ll_sink_window_attn(self._h, layer, _ptr(q_roped), _ptr(out), _stream()))
+
+    def sink_window_attn_unrotated(self, layer, q, out):
+        """The same attention from the chunk's unrotated, unscaled queries (the kernel turns them on load)."""
+        _check(lib().ll_sink_window_attn_unrotated(self._h, layer, _ptr(q), _ptr(out), _stream()))
 
     def recache_prefill(self, layer, include_sink, win_start, n_win, q=None, k=None, v=None, out=None):
         stream = _stream() if q is not None else None

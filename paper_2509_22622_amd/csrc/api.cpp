@@ -27,8 +27,11 @@ struct ll_cache {
     int64_t head_stride;    // elements between heads (K region + V region); bytes for the 8-bit cache
     int64_t layer_stride;   // elements between layers
     RopeTables rope;
+    float2* t_table;        // bf16 cache: per layer, the frame-axis (cos, sin) of the frames of the last cache write,
+    int64_t t_stride;       // [S + W + C][MAX_T_PAIRS], for the attention kernels that turn the queries themselves
     std::vector<double> inv_freq_t;   // host copy of the frame-axis frequencies (the device copy is rope.inv_freq_t)
     std::vector<LayerIndex> layer;
+    std::vector<int> staged_t_row;    // per layer: row of t_table at which the staged chunk's frames begin
 };
 
 static thread_local std::string g_err;
@@ -54,7 +57,7 @@ namespace {
 struct Sizes {
     int64_t kblocks, head_stride, layer_stride, cache_elems;
     int n_t, n_h, n_w;
-    size_t stage_off, table_off, row_off, col_off, total;
+    size_t stage_off, table_off, row_off, col_off, tt_off, total;
 };
 bool shapes_ok(int layers, int H, int D, int P, int S, int W, int C) {
     return layers >= 1 && H >= 1 && (D == 64 || D == 128) && P >= 1 && S >= 0 && W >= 0 && C >= 1 &&
@@ -78,6 +81,8 @@ Sizes sizes(int fmt, int layers, int H, int D, int P, int S, int W, int C, int g
     z.row_off = off; off += size_t(grid_h) * z.n_h * sizeof(float2);
     off = (off + 255) & ~size_t(255);
     z.col_off = off; off += size_t(grid_w) * z.n_w * sizeof(float2);
+    off = (off + 255) & ~size_t(255);
+    z.tt_off = off; off += size_t(layers) * (S + W + C) * MAX_T_PAIRS * sizeof(float2);
     z.total = (off + 255) & ~size_t(255);
     return z;
 }
@@ -105,7 +110,10 @@ ll_status static_stage(void** ptr) {
     return LL_OK;
 }
 // upper bound of the table area when the grid is not known yet (ll_cache_bytes)
-size_t table_bound(int D, int P) { return 3 * 256 + 64 * sizeof(double) + 2 * size_t(P) * (D / 2) * sizeof(float2); }
+size_t table_bound(int D, int P, int layers, int ring_frames) {
+    return 4 * 256 + 64 * sizeof(double) + 2 * size_t(P) * (D / 2) * sizeof(float2) +
+           size_t(layers) * ring_frames * MAX_T_PAIRS * sizeof(float2);
+}
 }  // namespace
 
 extern "C" {
@@ -114,7 +122,7 @@ static size_t cache_bytes(int fmt, int layers, int heads, int head_dim, int toke
                           int window_frames, int chunk_frames) {
     if (!shapes_ok(layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames)) return 0;
     Sizes z = sizes(fmt, layers, heads, head_dim, tokens_per_frame, sink_frames, window_frames, chunk_frames, 0, 0);
-    return z.table_off + table_bound(head_dim, tokens_per_frame);
+    return z.table_off + table_bound(head_dim, tokens_per_frame, layers, sink_frames + window_frames + chunk_frames);
 }
 
 size_t ll_cache_bytes(int layers, int heads, int head_dim, int tokens_per_frame, int sink_frames,
@@ -160,6 +168,7 @@ static ll_status cache_create(int fmt, int k_exp, int v_exp, int layers, int hea
     c->dev = static_cast<char*>(dev_buffer);
     c->kblocks = z.kblocks; c->head_stride = z.head_stride; c->layer_stride = z.layer_stride;
     c->layer.assign(layers, LayerIndex());
+    c->staged_t_row.assign(layers, 0);
     c->rope = RopeTables{nullptr, nullptr, nullptr, z.n_t, z.n_h, z.n_w};
     if (z.n_t > MAX_T_PAIRS) { delete c; return fail(LL_ERR_UNSUPPORTED, "%d frame-axis rotary pairs, at most %d", z.n_t, MAX_T_PAIRS); }
     c->inv_freq_t.resize(z.n_t);
@@ -187,6 +196,8 @@ static ll_status cache_create(int fmt, int k_exp, int v_exp, int layers, int hea
         c->rope.inv_freq_t = reinterpret_cast<const double*>(c->dev + z.table_off);
         c->rope.row_cs = reinterpret_cast<const float2*>(c->dev + z.row_off);
         c->rope.col_cs = reinterpret_cast<const float2*>(c->dev + z.col_off);
+        c->t_table = reinterpret_cast<float2*>(c->dev + z.tt_off);
+        c->t_stride = int64_t(sink_frames + window_frames + chunk_frames) * MAX_T_PAIRS;
     }
     *out = c;
     return LL_OK;
@@ -244,7 +255,7 @@ static ll_status enqueue_append(ll_cache* c, int layer, const int64_t* frames, i
     for (int base = 0; base < n; base += MAX_APPEND_FRAMES) {
         AppendParams p{};
         const int m = std::min(MAX_APPEND_FRAMES, n - base);
-        p.q = static_cast<const uint16_t*>(q) + base * frame_elems;
+        p.q = q ? static_cast<const uint16_t*>(q) + base * frame_elems : nullptr;       // null: keys and values only
         p.k = static_cast<const uint16_t*>(k) + base * frame_elems;
         p.v = static_cast<const uint16_t*>(v) + base * frame_elems;
         p.q_scale = float(1.4426950408889634 / std::sqrt(double(c->D)));
@@ -254,8 +265,9 @@ static ll_status enqueue_append(ll_cache* c, int layer, const int64_t* frames, i
             p.q_scale = std::ldexp(p.q_scale, c->k_exp);
             p.k_mul = std::ldexp(1.0f, -c->k_exp); p.v_mul = std::ldexp(1.0f, -c->v_exp);
         } else {
-            p.q_out = static_cast<uint16_t*>(q_out) + base * frame_elems;
+            p.q_out = q_out ? static_cast<uint16_t*>(q_out) + base * frame_elems : nullptr;
             p.k_cache = layer_k(c, layer); p.v_cache = layer_v(c, layer);
+            if (base + m <= c->t_stride / MAX_T_PAIRS) p.t_table_out = c->t_table + layer * c->t_stride + base * MAX_T_PAIRS;
         }
         p.head_stride = c->head_stride;
         p.rope = c->rope;
@@ -276,11 +288,12 @@ static ll_status enqueue_append(ll_cache* c, int layer, const int64_t* frames, i
 }
 
 static int pick_variant(const ll_cache* c) {
-    if (g_variant != 0 && attn_variant_supports(g_variant, c->D, c->kb)) return g_variant;
+    // (the kernel that turns its queries itself is chosen by the calls that hand it unrotated queries, never forced)
+    if (g_variant != 0 && attn_variant_supports(g_variant, c->D, c->kb) && g_variant != attn_variant_qrope(c->D)) return g_variant;
     return attn_variant_default(c->D, c->kb);
 }
 
-struct ChunkWork { int q_begin, q_end; std::vector<SlotRange> ranges; int64_t f0; };
+struct ChunkWork { int q_begin, q_end; std::vector<SlotRange> ranges; int64_t f0; int t_row = 0; };
 
 // Frames by which the queries of a chunk starting at f0 are turned back for the sink's scores (0: plain rule).
 static int64_t sink_shift_of(const ll_cache* c, int64_t f0) {
@@ -292,9 +305,15 @@ static int64_t sink_shift_of(const ll_cache* c, int64_t f0) {
 // here, before anything is enqueued or any bookkeeping changes.
 struct AttnLaunches { int variant = 0; std::vector<AttnParams> params; };
 
+// The queries can be turned by the attention kernel itself (then the cache write before it takes keys and values
+// only): bf16 cache, the default kernel, no chunk whose sink is scored with turned-back queries.
+static bool can_turn_queries(const ll_cache* c, const std::vector<ChunkWork>& work);
+
+// raw_q: q holds the queries before the rotary embedding; chunk i's frames are rows work[i].t_row .. of the table the
+// cache write of the same call (or, for a staged chunk, the last ll_chunk_append) left for the layer.
 static ll_status build_attn(const ll_cache* c, int layer, const std::vector<ChunkWork>& work, const void* q, void* out,
-                            AttnLaunches& L) {
-    const int variant = pick_variant(c);
+                            AttnLaunches& L, bool raw_q = false) {
+    const int variant = raw_q ? attn_variant_qrope(c->D) : pick_variant(c);
     const int qt = attn_variant_qtile(variant);
     L.variant = variant;
     L.params.clear();
@@ -313,6 +332,12 @@ static ll_status build_attn(const ll_cache* c, int layer, const std::vector<Chun
         p.head_stride = c->head_stride;
         p.H = c->H; p.D = c->D;
         p.scale_log2e = 1.0f;          // ll_chunk_append already folded log2(e)/sqrt(D) into q
+        if (raw_q) {
+            p.t_table = c->t_table + layer * c->t_stride;
+            p.row_cs = c->rope.row_cs; p.col_cs = c->rope.col_cs;
+            p.n_h = c->rope.n_h; p.n_w = c->rope.n_w; p.P = c->g.P; p.grid_w = c->grid_w;
+            p.q_scale = float(1.4426950408889634 / std::sqrt(double(c->D)));
+        }
         const int m = int(std::min<size_t>(MAX_ATTN_CHUNKS, work.size() - base));
         // longest key sets first: they bound the launch
         std::vector<int> order(m);
@@ -341,6 +366,7 @@ static ll_status build_attn(const ll_cache* c, int layer, const std::vector<Chun
             AttnChunk& ch = p.chunk[i];
             ch.q_begin = w.q_begin; ch.q_end = w.q_end; ch.tile_begin = tiles;
             ch.sink_shift = int(shift);
+            ch.t_row = w.t_row;
             ch.n_ranges = int(w.ranges.size());
             for (int r = 0; r < ch.n_ranges; ++r) { ch.rs[r] = int(w.ranges[r].begin); ch.re[r] = int(w.ranges[r].end); }
             tiles += (w.q_end - w.q_begin + qt - 1) / qt;
@@ -349,6 +375,13 @@ static ll_status build_attn(const ll_cache* c, int layer, const std::vector<Chun
         L.params.push_back(p);
     }
     return LL_OK;
+}
+
+static bool can_turn_queries(const ll_cache* c, const std::vector<ChunkWork>& work) {
+    if (c->fmt || g_variant != 0) return false;
+    for (const ChunkWork& w : work)
+        if (sink_shift_of(c, w.f0) != 0) return false;
+    return true;
 }
 
 static ll_status launch_built_attn(const AttnLaunches& L, hipStream_t s) {
@@ -365,8 +398,11 @@ ll_status ll_chunk_append(ll_cache* cache, int layer, int64_t frame_start, int n
     if (n_frames < 1 || n_frames > cache->g.C)
         return fail(LL_ERR_INVALID_ARG, "n_frames %d outside [1, %d]", n_frames, cache->g.C);
     if (frame_start < 0) return fail(LL_ERR_INVALID_ARG, "negative frame_start");
+    // q and q_out both null: keys and values only (the queries then go, unrotated, to ll_sink_window_attn_unrotated)
+    const bool kv_only = cache->dev && !q && !q_out && k && v;
+    if (kv_only && cache->fmt) return fail(LL_ERR_UNSUPPORTED, "the 8-bit cache takes its queries in ll_chunk_append");
     const bool any_null = !q || !k || !v || !q_out;
-    if (cache->dev && any_null) return fail(LL_ERR_INVALID_ARG, "null tensor");
+    if (cache->dev && any_null && !kv_only) return fail(LL_ERR_INVALID_ARG, "null tensor");
     if (!cache->dev && !(!q && !k && !v && !q_out)) return fail(LL_ERR_INVALID_ARG, "index-only handle takes null tensors");
     if (!aligned16(q, k, v, q_out)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
     if (cache->fmt && cache->dev && (q_out == q || q_out == k || q_out == v))
@@ -382,6 +418,7 @@ ll_status ll_chunk_append(ll_cache* cache, int layer, int64_t frame_start, int n
         if (st != LL_OK) return st;
     }
     apply_append(cache->g, L, frame_start, n_frames);
+    cache->staged_t_row[layer] = 0;
     return LL_OK;
 }
 
@@ -399,6 +436,28 @@ ll_status ll_sink_window_attn(ll_cache* cache, int layer, const void* q_roped, v
     work[0].f0 = L.staged_f0;
     AttnLaunches launches;
     ll_status st = build_attn(cache, layer, work, q_roped, out, launches);
+    if (st != LL_OK) return st;
+    return launch_built_attn(launches, static_cast<hipStream_t>(stream));
+}
+
+ll_status ll_sink_window_attn_unrotated(ll_cache* cache, int layer, const void* q, void* out, void* stream) {
+    CHECK_CACHE_LAYER(cache, layer);
+    if (!cache->dev) return fail(LL_ERR_INVALID_ARG, "index-only handle has no device cache");
+    if (!q || !out) return fail(LL_ERR_INVALID_ARG, "null tensor");
+    if (!aligned16(q, out)) return fail(LL_ERR_INVALID_ARG, "tensors must be 16-byte aligned");
+    const LayerIndex& L = cache->layer[layer];
+    if (L.staged_n == 0) return fail(LL_ERR_STATE, "layer %d: no staged chunk", layer);
+    std::vector<ChunkWork> work(1);
+    work[0].q_begin = 0;
+    work[0].q_end = L.staged_n * cache->g.P;
+    work[0].ranges = live_ranges(cache->g, L);
+    work[0].f0 = L.staged_f0;
+    work[0].t_row = cache->staged_t_row[layer];       // where the last cache write left the staged chunk's frames
+    if (cache->fmt) return fail(LL_ERR_UNSUPPORTED, "the 8-bit cache takes its queries in ll_chunk_append");
+    if (!can_turn_queries(cache, work))
+        return fail(LL_ERR_UNSUPPORTED, "unrotated queries need the default kernel and a sink that is not re-indexed for this chunk");
+    AttnLaunches launches;
+    ll_status st = build_attn(cache, layer, work, q, out, launches, true);
     if (st != LL_OK) return st;
     return launch_built_attn(launches, static_cast<hipStream_t>(stream));
 }
@@ -435,6 +494,7 @@ static ll_status recache_prefill(ll_cache* cache, int layer, int include_sink, i
         w.q_begin = row; w.q_end = row + c.n * g.P;
         w.ranges = live_ranges(g, next);
         w.f0 = c.f0;
+        w.t_row = row / g.P;                          // frames of the call, in row order
         work.push_back(w);
         row = w.q_end;
     }
@@ -443,6 +503,9 @@ static ll_status recache_prefill(ll_cache* cache, int layer, int include_sink, i
     // wave reads exactly the rows it writes).  E4M3 queries are half as wide as the output rows, so they are
     // staged in the cache buffer's own area instead.
     void* q_stage = cache->fmt ? static_cast<void*>(cache->q8_stage) : out;
+    // bf16 cache, default kernel: the attention kernel turns the queries as it loads them, the cache write takes keys
+    // and values only and the rotated queries never go through memory
+    const bool turn_in_attn = can_turn_queries(cache, work);
     ll_status st = LL_OK;
     if (cache->fmt && use_static_stage) {
         const size_t need = size_t(n_total) * g.P * cache->H * cache->D;      // one byte per element
@@ -452,17 +515,20 @@ static ll_status recache_prefill(ll_cache* cache, int layer, int include_sink, i
         if (st != LL_OK) return st;
     }
     AttnLaunches launches;
-    st = build_attn(cache, layer, work, q_stage, out, launches);
+    st = turn_in_attn ? build_attn(cache, layer, work, q, out, launches, true)
+                      : build_attn(cache, layer, work, q_stage, out, launches);
     if (st != LL_OK) return st;
     hipStream_t s = static_cast<hipStream_t>(stream);
     std::vector<int64_t> frames;
     for (const ChunkSpan& c : chunks)
         for (int i = 0; i < c.n; ++i) frames.push_back(c.f0 + i);
-    st = enqueue_append(cache, layer, frames.data(), int(frames.size()), q, k, v, q_stage, s);
+    st = turn_in_attn ? enqueue_append(cache, layer, frames.data(), int(frames.size()), nullptr, k, v, nullptr, s)
+                      : enqueue_append(cache, layer, frames.data(), int(frames.size()), q, k, v, q_stage, s);
     if (st == LL_OK) st = launch_built_attn(launches, s);
     // a launch that failed half way leaves slots overwritten that the old bookkeeping still describes: forget the
     // layer, so that later calls report LL_ERR_STATE instead of reading a half-written cache
     L = st == LL_OK ? next : LayerIndex();
+    cache->staged_t_row[layer] = work.empty() ? 0 : work.back().t_row;
     return st;
 }
 

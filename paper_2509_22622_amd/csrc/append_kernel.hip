@@ -106,6 +106,9 @@ __global__ __launch_bounds__(256) void ll_append_kernel(const AppendParams p) {
         }
     }
     if (turn && tid < n_t) t_cs[tid] = p.t_cs[fi][tid];
+    if (p.t_table_out != nullptr && blockIdx.x == 0)               // uniform
+        for (int i = tid; i < p.n_frames * MAX_T_PAIRS; i += 256)
+            p.t_table_out[i] = p.t_cs[i / MAX_T_PAIRS][i % MAX_T_PAIRS];
     __syncthreads();
 
     // ---- rotation, q' out, K rows and V rows into LDS
@@ -123,8 +126,10 @@ __global__ __launch_bounds__(256) void ll_append_kernel(const AppendParams p) {
             if (turn && pi < n_t) w = t_cs[pi];
             const float qr = bf16_to_f32(qv[it][2 * e]), qi = bf16_to_f32(qv[it][2 * e + 1]);
             const float kr = bf16_to_f32(kv[it][2 * e]), ki = bf16_to_f32(kv[it][2 * e + 1]);
-            qo[2 * e] = f32_to_bf16((qr * w.x - qi * w.y) * p.q_scale);
-            qo[2 * e + 1] = f32_to_bf16((qr * w.y + qi * w.x) * p.q_scale);
+            float q_re, q_im;
+            rope_turn_scaled(qr, qi, w, p.q_scale, q_re, q_im);
+            qo[2 * e] = f32_to_bf16(q_re);
+            qo[2 * e + 1] = f32_to_bf16(q_im);
             ko[2 * e] = f32_to_bf16(kr * w.x - ki * w.y);
             ko[2 * e + 1] = f32_to_bf16(kr * w.y + ki * w.x);
         }

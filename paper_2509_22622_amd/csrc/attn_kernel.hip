@@ -317,11 +317,12 @@ int attn_variant_qtile(int v) { return variant(v)->qtile; }
 bool attn_variant_supports(int v, int D, int kblock) { return variant(v) && variant(v)->D == D && variant(v)->kblock == kblock; }
 // only the software-pipelined bf16 kernels take queries turned back for the sink range (AttnChunk::sink_shift)
 bool attn_variant_sink_shift(int v) {
-    return (v > kNumSimple && v <= kNumSimple + 2) || (is_stream16(v) && (v < first_stream16() + 2 || v >= first_stream16() + 6));
+    return (v > kNumSimple && v <= kNumSimple + 2) || (is_stream16(v) && (v < first_stream16() + 2 || (v >= first_stream16() + 6 && v < first_stream16() + 8)));
 }
 // the software-pipelined kernel that multiplies the queries by AttnParams::scale_log2e itself
 int attn_variant_qscale(int D) { return first_stream16() + (D == 128 ? 2 : 3); }
 int attn_variant_lse(int D) { return first_stream16() + (D == 128 ? 4 : 5); }
+int attn_variant_qrope(int D) { return first_stream16() + (D == 128 ? 8 : 9); }
 // the 128-query kernel that leaves room for three workgroups per CU (short key sets, many query tiles)
 int attn_variant_short_keys(int D) { return D == 128 ? 8 : 10; }
 bool attn_variant_out_frag(int v) { return (v >= 1 && v <= kNumSimple) || is_stream16(v); }

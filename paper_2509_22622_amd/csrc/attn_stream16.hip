@@ -201,6 +201,32 @@ __device__ __forceinline__ void s16_segment(const AttnParams& p, const AttnChunk
 #pragma unroll
         for (int s = 0; s < NQ; ++s) qf[qb][s] = *reinterpret_cast<const bf16x8*>(q_src[qb] + s * 32);
     }
+    if constexpr ((SCHED & 16) != 0) {
+        // the queries come as the model's projection made them: turn this lane's pairs (3D rotary embedding, the
+        // frame axis from the table the cache write left, rows and columns from the cache's tables) and fold in the
+        // softmax scale, with the arithmetic of the cache-write kernel (kernels.h: rope_turn_scaled)
+        const int n_t = p.n_t, n_h = p.n_h;
+#pragma unroll
+        for (int qb = 0; qb < 2; ++qb) {
+            const int rel = min(q0 + 16 * qb + n, q_end - 1) - ch.q_begin;
+            const int fi = rel / p.P, tok = rel - fi * p.P;
+            const int y = tok / p.grid_w, x = tok - y * p.grid_w;
+            const float2* t_cs = p.t_table + (ch.t_row + fi) * MAX_T_PAIRS;
+            const float2* r_cs = p.row_cs + y * n_h - n_t;
+            const float2* c_cs = p.col_cs + x * p.n_w - n_t - n_h;
+#pragma unroll
+            for (int s = 0; s < NQ; ++s)
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int pi = 16 * s + 4 * g + j;      // rotary pair of features 32 s + 8 g + 2 j, + 1
+                    const float2 w = *(pi < n_t ? t_cs + pi : (pi < n_t + n_h ? r_cs + pi : c_cs + pi));
+                    float re, im;
+                    rope_turn_scaled(float(qf[qb][s][2 * j]), float(qf[qb][s][2 * j + 1]), w, p.q_scale, re, im);
+                    qf[qb][s][2 * j] = __bf16(re);
+                    qf[qb][s][2 * j + 1] = __bf16(im);
+                }
+        }
+    }
     if constexpr (QSCALE) {
         const float c = p.scale_log2e;
 #pragma unroll
@@ -596,7 +622,8 @@ __global__ __launch_bounds__(S16_THREADS) __attribute__((amdgpu_waves_per_eu(2, 
 }
 
 // Default schedule: exponentials of the second query block behind the S^T slots, and the reference kept fixed with
-// the second, maximum-following pass as the fallback (SCHED 9).  The *_tracked variants follow the maximum throughout.
+// the second, maximum-following pass as the fallback (SCHED 9).  The *_tracked variants follow the maximum throughout;
+// the *_qrope variants (SCHED bit 4) take unrotated queries and turn them on load.
 constexpr int S16_DEFAULT = 9, S16_TRACKED = 1;
 #define S16_ENTRY(name, D, QS, LSE, SCHED) \
     {name, D, 256, 8 * 2 * KBLOCK * D * 2, ll_attn_stream16_kernel<D, QS, LSE, SCHED>, S16_THREADS, KBLOCK}
@@ -609,6 +636,8 @@ const AttnVariant kStream16Variants[] = {
     S16_ENTRY("d64_stream16_lse", 64, false, true, S16_DEFAULT),
     S16_ENTRY("d128_stream16_tracked", 128, false, false, S16_TRACKED),
     S16_ENTRY("d64_stream16_tracked", 64, false, false, S16_TRACKED),
+    S16_ENTRY("d128_stream16_qrope", 128, false, false, S16_DEFAULT | 16),
+    S16_ENTRY("d64_stream16_qrope", 64, false, false, S16_DEFAULT | 16),
 };
 #undef S16_ENTRY
 const int kNumStream16Variants = sizeof(kStream16Variants) / sizeof(kStream16Variants[0]);

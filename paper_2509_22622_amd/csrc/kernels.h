@@ -81,6 +81,9 @@ struct AppendParams {
     // passes unchanged; q, where given, only takes q_scale) - the tables are not read then.
     float2 t_cs[MAX_APPEND_FRAMES][MAX_T_PAIRS];
     int identity;
+    // When set (bf16 cache): t_cs[0 .. n_frames) is also stored there, [n_frames][MAX_T_PAIRS], for the attention
+    // kernels that turn the queries themselves (AttnParams::t_table).
+    float2* t_table_out;
     int64_t slot[MAX_APPEND_FRAMES];                            // first token slot
     int seg_begin[MAX_APPEND_FRAMES + 1];                       // prefix sum of kblock segments (32 or 64 slots)
     // 8-bit cache (all null / unused for the bf16 cache): byte pointers, head_stride in bytes
@@ -97,6 +100,15 @@ inline void set_frame_rotation(AppendParams& p, const double* inv_freq_t_host) {
         }
 }
 
+// One rotary pair (re, im) turned by w = (cos, sin) and scaled, in fp32.  The cache-write kernel and the attention
+// kernels that turn their queries on load both go through here, with the contraction fixed by hand, so that they
+// produce the same bits.
+__device__ __forceinline__ void rope_turn_scaled(float re, float im, float2 w, float scale, float& o_re, float& o_im) {
+    const float t = im * w.y, u = im * w.x;
+    o_re = __builtin_fmaf(re, w.x, -t) * scale;
+    o_im = __builtin_fmaf(re, w.y, u) * scale;
+}
+
 struct AttnChunk {
     int q_begin, q_end;          // query rows [q_begin, q_end) of the q tensor
     int tile_begin;              // first query tile of this chunk in the launch
@@ -106,6 +118,9 @@ struct AttnChunk {
     // Sink at a fixed rotary distance (0 = off): range 0 is exactly the sink, and its scores are taken with the
     // queries turned back by sink_shift frames on the frame axis of the rotary embedding.
     int sink_shift;
+    // Queries given before the rotary embedding (AttnParams::t_table set): row r of the chunk is token (r - q_begin)
+    // % P of the frame whose frame-axis (cos, sin) are row t_row + (r - q_begin) / P of the table.
+    int t_row;
 };
 
 struct AttnParams {
@@ -134,6 +149,12 @@ struct AttnParams {
     float* lse;                  // *_lse kernels: log2 of each row's sum of 2^score, [H][lse_stride] (null otherwise)
     int64_t lse_stride;
     float* out32;                // *_lse kernels: the output once more in fp32, [rows, H, D] (null: not wanted)
+    // *_qrope kernels: q holds the queries as the model's projection made them; a wave turns its rows on load
+    // (3D rotary embedding, the same arithmetic as the cache-write kernel) and scales them by q_scale.
+    const float2* t_table;       // frame-axis (cos, sin), [frames of the call][MAX_T_PAIRS], written by the cache write
+    const float2* row_cs; const float2* col_cs;   // as in RopeTables
+    int n_h, n_w, P, grid_w;
+    float q_scale;
     uint16_t xcd_first[9];
     uint16_t xcd_group[MAX_XCD_GROUPS];
     AttnChunk chunk[MAX_ATTN_CHUNKS];
@@ -210,6 +231,7 @@ bool attn_variant_sink_shift(int v);          // the variant honours AttnChunk::
 int attn_variant_lse(int D);                   // the variant that also writes AttnParams::lse
 int attn_variant_qscale(int D);                // the variant for queries not yet scaled (honours scale_log2e)
 int attn_variant_short_keys(int D);            // small workgroups, three per CU: for short key sets
+int attn_variant_qrope(int D);                 // the variant that turns the queries itself (AttnParams::t_table)
 bool attn_variant_applies_scale(int v);        // the variant multiplies the scores (or queries) by scale_log2e itself
 bool attn_variant_out_frag(int v);             // the variant honours AttnParams::out_frag
 

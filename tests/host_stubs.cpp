@@ -12,6 +12,7 @@ bool attn_variant_supports(int v, int D, int kblock) { return v == attn_variant_
 bool attn_variant_sink_shift(int v) { return v <= 2; }
 int attn_variant_lse(int D) { return D == 128 ? 1 : 2; }
 int attn_variant_qscale(int D) { return D == 128 ? 1 : 2; }
+int attn_variant_qrope(int D) { return D == 128 ? 1 : 2; }
 int attn_variant_short_keys(int D) { return D == 128 ? 1 : 2; }
 bool attn_variant_applies_scale(int) { return true; }
 bool attn_variant_out_frag(int) { return true; }

@@ -68,6 +68,32 @@ def test_wan_layer_streaming():
     cache.close()
 
 
+def test_wan_layer_unrotated_queries():
+    """Config 2 in the launch configuration bench.py times: the cache write takes keys and values only and the
+    attention kernel turns the queries itself.  Every element equals the two-call path bit for bit (warm-up, steady
+    state, ring wrap); sampled rows against the oracle in the steady state."""
+    w = synth.WAN_LAYER
+    two_calls, fused, oracle = H.make_cache(w), H.make_cache(w), Oracle(H.oracle_cfg(w))
+    for i in range(7):
+        f0 = 3 * i
+        q, k, v = synth.chunk_qkv(w, 0, i)
+        qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+        qr, out_a, out_b = torch.empty_like(qd), torch.empty_like(qd), torch.empty_like(qd)
+        two_calls.chunk_append(0, f0, 3, qd, kd, vd, qr)
+        two_calls.sink_window_attn(0, qr, out_a)
+        fused.chunk_append(0, f0, 3, None, kd, vd, None)
+        fused.sink_window_attn_unrotated(0, qd, out_b)
+        torch.cuda.synchronize()
+        assert torch.equal(out_a.view(torch.int16), out_b.view(torch.int16)), f"chunk {i}"
+        oracle.append(0, f0, q, k, v)
+        assert fused.live_frames(0) == oracle.live_frames(0)
+        if i >= 5:
+            _check_sampled(out_b, oracle, 0, _sample_rows(w.chunk_tokens, 300 + i), f"cfg2 chunk {i} (unrotated queries)")
+        _trim(oracle, 0, f0 - w.window_frames, w.sink_frames)
+    two_calls.close()
+    fused.close()
+
+
 def test_wan_layer_sink_relative():
     """Config 2's shape with the sink at a fixed rotary distance (the configuration bench.py times as
     cfg2_sink_relative): the sink is a key range of its own once f0 > W + S (chunks 5 and 6 here, shifts 3 and 6),

@@ -88,7 +88,8 @@ def test_random_geometries_every_element(idx):
 
 def _bf16_variants(prefix):
     """Names of the library's bf16-cache kernel variants for one head_dim (the library loads without a GPU)."""
-    return [n for n in B.attn_variant_names().values() if n.startswith(prefix) and "fp8" not in n]
+    return [n for n in B.attn_variant_names().values()
+            if n.startswith(prefix) and "fp8" not in n and "qrope" not in n]     # qrope: its own calls, tested below
 
 
 def _variant_id(name):
@@ -105,6 +106,72 @@ def test_every_d128_variant(name):
 def test_every_d64_variant(name):
     _stream_and_check(ODD64, 6, variant=_variant_id(name), check_cache=False)
     _stream_and_check(synth.TINY, 5, variant=_variant_id(name), check_cache=False)
+
+
+@pytest.mark.parametrize("w", [synth.TINY, MID128, ODD128, NOSINK, ODD64, WIDE, HEADS6], ids=lambda w: w.name)
+def test_unrotated_queries_bit_for_bit(w):
+    """ll_chunk_append(keys and values only) + ll_sink_window_attn_unrotated against ll_chunk_append(q, q_out) +
+    ll_sink_window_attn: the attention kernel turns the queries with the cache write's arithmetic, so the outputs
+    agree bit for bit, and both agree with the oracle.  Several denoising passes per chunk, a short last chunk."""
+    two_calls, fused, oracle = H.make_cache(w), H.make_cache(w), Oracle(H.oracle_cfg(w))
+    f0, n_chunks = 0, min(w.n_chunks, 6)
+    for i in range(n_chunks):
+        n = 1 if i == n_chunks - 1 else w.chunk_frames
+        for rep in range(2):
+            q, k, v = synth.chunk_qkv(w, 0, i + 1000 * (1 - rep), n)
+            qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+            qr, out_a, out_b = torch.empty_like(qd), torch.empty_like(qd), torch.full_like(qd, 7.0)
+            two_calls.chunk_append(0, f0, n, qd, kd, vd, qr)
+            two_calls.sink_window_attn(0, qr, out_a)
+            fused.chunk_append(0, f0, n, None, kd, vd, None)
+            fused.sink_window_attn_unrotated(0, qd, out_b)
+            torch.cuda.synchronize()
+            assert torch.equal(out_a.view(torch.int16), out_b.view(torch.int16)), f"{w.name} chunk {i} pass {rep}"
+            oracle.append(0, f0, q, k, v)
+        assert fused.live_frames(0) == oracle.live_frames(0)
+        H.assert_parity(H.to_bits(out_b), oracle.attn(0), f"{w.name} chunk {i} (unrotated queries)")
+        for f in oracle.live_frames(0):
+            H.check_frame(fused, oracle, w, 0, f)
+        f0 += n
+    two_calls.close()
+    fused.close()
+
+
+def test_unrotated_queries_after_a_prefill_and_errors():
+    """The staged chunk after ll_recache_prefill is its last chunk: ll_sink_window_attn_unrotated finds that chunk's
+    frames in the middle of the table the prefill's cache write left.  Then the cases the call refuses."""
+    w = ODD128
+    cache = H.make_cache(w)
+    P, S, C = w.tokens_per_frame, w.sink_frames, w.chunk_frames
+    n_win = 5
+    shape = ((S + n_win) * P, w.heads, w.head_dim)
+    q, k, v = (synth.normal_bf16(shape, w.cfg_id, 0, 77, t) for t in ("q", "k", "v"))
+    qd, out = H.to_dev(q), torch.empty(shape, dtype=torch.bfloat16, device="cuda")
+    cache.recache_prefill(0, True, S, n_win, qd, H.to_dev(k), H.to_dev(v), out)
+    # the prefill's last chunk: frames [S + n_win - last, S + n_win), rows at the tail of q
+    last = n_win % C or C
+    rows = slice((S + n_win - last) * P, (S + n_win) * P)
+    again = torch.empty((last * P, w.heads, w.head_dim), dtype=torch.bfloat16, device="cuda")
+    cache.sink_window_attn_unrotated(0, qd[rows].contiguous(), again)
+    torch.cuda.synchronize()
+    assert torch.equal(again.view(torch.int16), out[rows].view(torch.int16))
+    # refused: a forced diagnostic variant, a re-indexed sink, an 8-bit cache, no staged chunk
+    B.set_attn_variant(_variant_id("d128_stream16_tracked"))
+    with pytest.raises(B.LongLiveError) as e:
+        cache.sink_window_attn_unrotated(0, qd[rows].contiguous(), again)
+    assert e.value.status == B.LL_ERR_UNSUPPORTED
+    B.set_attn_variant(0)
+    cache.reset(0)
+    with pytest.raises(B.LongLiveError) as e:
+        cache.sink_window_attn_unrotated(0, qd[rows].contiguous(), again)
+    assert e.value.status == B.LL_ERR_STATE
+    cache.close()
+    c8 = B.Cache(1, w.heads, w.head_dim, w.grid_h, w.grid_w, C, S, w.window_frames, kv_format="fp8_e4m3")
+    kd = H.to_dev(synth.normal_bf16((C * P, w.heads, w.head_dim), w.cfg_id, 0, 78, "k"))
+    with pytest.raises(B.LongLiveError) as e:
+        c8.chunk_append(0, 0, C, None, kd, kd, None)
+    assert e.value.status == B.LL_ERR_UNSUPPORTED
+    c8.close()
 
 
 def test_peaky_softmax():
