@@ -159,6 +159,9 @@ def test_error_paths():
     with pytest.raises(B.LongLiveError) as e:                              # compute needs a device cache
         B._check(L.ll_sink_window_attn(c._h, 0, None, None, None))
     assert e.value.status == 1
+    with pytest.raises(B.LongLiveError) as e:                              # and so does the form that turns the queries
+        B._check(L.ll_sink_window_attn_unrotated(c._h, 0, None, None, None))
+    assert e.value.status == 1
     buf, n = (C.c_int64 * 2)(), C.c_int()
     assert L.ll_cache_live_frames(c._h, 0, buf, 2, C.byref(n)) == 3 and n.value == 6
     c.reset(0)
