@@ -201,6 +201,24 @@ def test_wan_shape_full_size(n_q):
     p.close()
 
 
+@pytest.mark.parametrize("heads,head_dim,n_q,n_t", [
+    (12, 128, 11000, 256), (12, 64, 12345, 512), (5, 128, 40000, 768), (12, 128, 11000, 250), (12, 128, 11000, 200),
+])
+def test_many_query_tiles(heads, head_dim, n_q, n_t):
+    """Launches of more than two rounds of query tiles (the small-workgroup kernel): 8, 16, 24 kblocks of keys, a
+    partly dead last kblock, ragged last query tiles, both head sizes.  Every output element against the oracle."""
+    p = B.Prompt(1, heads, head_dim, 1024)
+    k, v = bits((n_t, heads, head_dim), 41, "k"), bits((n_t, heads, head_dim), 41, "v")
+    q = bits((n_q, heads, head_dim), 42, "q")
+    p.recache(0, H.to_dev(k), H.to_dev(v))
+    out = torch.full((n_q, heads, head_dim), 3.0, dtype=torch.bfloat16, device="cuda")
+    p.cross_attn(0, H.to_dev(q), out)
+    torch.cuda.synchronize()
+    want = cross_attention(bf16_bits_to_f64(q), bf16_bits_to_f64(k), bf16_bits_to_f64(v))
+    assert_parity_prompt(H.to_bits(out), want, v, f"H{heads} D{head_dim} n_q {n_q} n_t {n_t}")
+    p.close()
+
+
 def test_graph_replay_of_a_prompt_switch():
     """Both calls enqueue kernels only: captured in a graph, a replay re-runs the switch and the cross-attention on
     what the captured tensors hold now."""
@@ -285,15 +303,15 @@ def test_cross_attn_out_parity(heads, head_dim, n_q, n_t):
     p.close()
 
 
-@pytest.mark.parametrize("heads,head_dim,n_q", [(3, 128, 300), (5, 64, 77),
-                                                (12, 128, 11000), (12, 64, 11000)])   # the last two: the kernel for many query tiles
-def test_out_projection_exact_cases(heads, head_dim, n_q):
+@pytest.mark.parametrize("heads,head_dim,n_q,n_t", [(3, 128, 300, 50), (5, 64, 77, 50),
+                                                    (12, 128, 11000, 50), (12, 64, 11000, 50),    # many query tiles: the small-workgroup kernel
+                                                    (12, 128, 11000, 256), (12, 64, 11000, 256)])
+def test_out_projection_exact_cases(heads, head_dim, n_q, n_t):
     """Weights the projection must pass through bit for bit: the identity returns the attention output itself (what
     ll_cross_attn writes: so the hand-over between the two kernels loses and moves nothing), a permutation moves its
     features."""
-    n_t = 50
     n = heads * head_dim
-    p = B.Prompt(1, heads, head_dim, 64)
+    p = B.Prompt(1, heads, head_dim, 256)
     k, v, q = bits((n_t, heads, head_dim), 21, "k"), bits((n_t, heads, head_dim), 21, "v"), bits((n_q, heads, head_dim), 22, "q")
     p.recache(0, H.to_dev(k), H.to_dev(v))
     qd = H.to_dev(q)
