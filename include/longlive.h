@@ -138,8 +138,9 @@ ll_status ll_sink_window_attn_unrotated(ll_cache* cache, int layer, const void* 
  * the frames are cut into chunks of C (the sink first, then the window from win_start);
  * a chunk starting at f0 sees the sink, the retained frames in [f0 - W, f0) and itself.
  *   q, k, v, out: device, [(S if include_sink else 0) + n_win) * P, H, D] bf16 in that
- *   frame order.  out receives the attention output and is also used as the staging area
- *   for the rotated queries (out must not alias q, k or v).
+ *   frame order.  out receives the attention output; it must not alias q, k or v (the attention kernel reads q while
+ *   other rows of out are written; where the kernel cannot turn the queries itself - a forced diagnostic variant, a
+ *   re-indexed sink - out also serves as the staging area for the rotated queries).
  *   All non-sink frames held before are dropped.  include_sink == 0 keeps the sink K/V
  *   already held (LL_ERR_STATE if the sink is incomplete).  win_start >= S, 0 <= n_win <=
  *   W + C; n_win == 0 (the sink alone, include_sink != 0) requires win_start == S.
@@ -163,8 +164,8 @@ ll_status ll_recache_prefill(ll_cache* cache, int layer, int include_sink, int64
  *   Every call on one GPU shares that GPU's array: two such calls must not overlap in time on one GPU, whatever
  *   their handles or layers (enqueue them on one stream, or order the streams); the array keeps the last call's
  *   queries, nothing in it needs clearing (every byte a call reads it has written before).
- *   A bf16 cache stages its queries in `out` and needs no scratch: for such a handle the call is
- *   ll_recache_prefill.  Neither call allocates, frees or synchronises. */
+ *   A bf16 cache needs no scratch (its queries are turned by the attention kernel as it loads them, or staged in
+ *   `out`): for such a handle the call is ll_recache_prefill.  Neither call allocates, frees or synchronises. */
 ll_status ll_recache_prefill_static(ll_cache* cache, int layer, int include_sink, int64_t win_start,
                                     int n_win, const void* q, const void* k, const void* v,
                                     void* out, void* stream);
