@@ -517,6 +517,30 @@ def main():
         print(json.dumps(res))
         return
 
+    # The other form of the same step, for comparison: the one not timed above.
+    def other_step():
+        nonlocal chunk
+        f0, i = chunk * Cf, chunk % pool
+        for l in range(L):
+            if args.two_call_step:
+                cache.chunk_append(l, f0, Cf, None, k[i, l], v[i, l], None)
+                cache.sink_window_attn_unrotated(l, q[i, l], out[l])
+            else:
+                cache.chunk_append(l, f0, Cf, q[i, l], k[i, l], v[i, l], qr[l])
+                cache.sink_window_attn(l, qr[l], out[l])
+        chunk += 1
+    other_step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        other_step()
+    torch.cuda.synchronize()
+    o_ms = (time.perf_counter() - t0) / args.steps * 1e3
+    res["other_form_of_the_step"] = {
+        "ms_per_step": round(o_ms, 4), "TFLOP/s": round(fl_layer * L / (o_ms * 1e-3) / 1e12, 2),
+        "what": ("keys and values appended, queries turned by the attention kernel" if args.two_call_step else
+                 "ll_chunk_append(q, q_out) + ll_sink_window_attn(q_out): the rotated queries go through memory")}
+
     # The repeated denoising passes of one chunk (same frames, new contents) as one captured HIP graph: the
     # 60 launches of a step replayed without per-launch host work.
     f0g, ig = (chunk - 1) * Cf, (chunk - 1) % pool
