@@ -82,3 +82,52 @@ def test_graph_replay_equals_eager_passes(kv_format):
     assert torch.equal(outs[0].view(torch.int16), outs[1].view(torch.int16))
     eager.close()
     graphed.close()
+
+
+def test_graph_replay_of_the_unrotated_query_pair():
+    """ll_chunk_append(keys and values only) + ll_sink_window_attn_unrotated captured in a HIP graph: the cache write
+    leaves the frame-axis table for the attention kernel with a plain store (no memset node, no host copy), so replays
+    with fresh contents match the eager two-call path bit for bit, and the oracle."""
+    P, C = W.tokens_per_frame, W.chunk_frames
+    make = lambda: B.Cache(W.layers, W.heads, W.head_dim, W.grid_h, W.grid_w, C, W.sink_frames, W.window_frames)
+    eager, graphed, oracle = make(), make(), Oracle(H.oracle_cfg(W))
+    shape = (C * P, W.heads, W.head_dim)
+    hist = 5
+    for i in range(hist):
+        for l in range(W.layers):
+            q, k, v = synth.chunk_qkv(W, l, i)
+            qd, kd, vd = H.to_dev(q), H.to_dev(k), H.to_dev(v)
+            eager.chunk_append(l, i * C, C, qd, kd, vd, torch.empty_like(qd))
+            graphed.chunk_append(l, i * C, C, None, kd, vd, None)
+            if l == 0:
+                oracle.append(0, i * C, q, k, v)
+    f0 = hist * C
+    sq, sk, sv = (torch.zeros((W.layers,) + shape, dtype=torch.bfloat16, device="cuda") for _ in range(3))
+    sout = torch.empty_like(sq)
+
+    def fused_pass():
+        for l in range(W.layers):
+            graphed.chunk_append(l, f0, C, None, sk[l], sv[l], None)
+            graphed.sink_window_attn_unrotated(l, sq[l], sout[l])
+
+    fused_pass()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        fused_pass()
+    for rep in range(4):
+        host = [synth.chunk_qkv(W, l, 300 + rep) for l in range(W.layers)]
+        q, k, v = (torch.stack([H.to_dev(h[t]) for h in host]) for t in range(3))
+        qr, out = torch.empty_like(q), torch.empty_like(q)
+        for l in range(W.layers):                           # the program's own eager work between replays
+            eager.chunk_append(l, f0, C, q[l], k[l], v[l], qr[l])
+            eager.sink_window_attn(l, qr[l], out[l])
+        torch.cuda.synchronize()
+        sq.copy_(q), sk.copy_(k), sv.copy_(v)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(sout.view(torch.int16), out.view(torch.int16)), f"replay {rep}"
+        oracle.append(0, f0, *host[0])
+        H.assert_parity(H.to_bits(sout[0]), oracle.attn(0), f"replay {rep} vs oracle")
+    eager.close()
+    graphed.close()
