@@ -602,8 +602,12 @@ def main():
         for c in range(60):
             i = c % pool
             for l in range(L):
-                cache.chunk_append(l, c * Cf, Cf, q[i, l], k[i, l], v[i, l], qr[l])
-                cache.sink_window_attn(l, qr[l], out[l])
+                if args.two_call_step:
+                    cache.chunk_append(l, c * Cf, Cf, q[i, l], k[i, l], v[i, l], qr[l])
+                    cache.sink_window_attn(l, qr[l], out[l])
+                else:
+                    cache.chunk_append(l, c * Cf, Cf, None, k[i, l], v[i, l], None)
+                    cache.sink_window_attn_unrotated(l, q[i, l], out[l])
             marks[c + 1].record()
         torch.cuda.synchronize()
         per_chunk = [marks[c].elapsed_time(marks[c + 1]) for c in range(60)]
